@@ -1,0 +1,164 @@
+/*
+ * mpa — mixed-batch paged attention for AMD MI355X (gfx950).  C ABI of libmpa.so.
+ *
+ * The library implements the attention step of one serving iteration over a block-based KV
+ * cache for a batch that mixes prompt-chunk tasks and single-token generation tasks, plus the
+ * append of the iteration's new K/V into the cache:
+ *
+ *   - attention is scaled dot-product self-attention per head, softmax(Q K^T / sqrt(d_k)) V
+ *     (paper Sec. 2.1, the self-attention equation), each query token attending to the keys of
+ *     all earlier tokens of its sequence and to itself;
+ *   - K/V are stored in fixed-size token blocks that need not be contiguous (Sec. 2.2,
+ *     block-based KVC allocation);
+ *   - a prompt may be processed in chunks over successive iterations, each chunk batched with
+ *     other prompts' chunks and with generation tasks (Sec. 2.3; Sec. 4.2 dynamic chunking), and
+ *     a chunk may start and end anywhere, also in the middle of a block (Sec. 4.4, KVC demand of
+ *     a non-first chunk).
+ *
+ * Conventions
+ *   - Every function returns an int status (MPA_OK == 0, errors < 0) unless stated; nothing
+ *     throws or aborts.
+ *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
+ *     host memory read during the call only.  The library allocates no device memory.
+ *   - Work is enqueued on the HIP stream passed as `stream` (a hipStream_t cast to void*,
+ *     NULL = the default stream) and the call returns without waiting for the GPU.
+ *   - Element type is bf16 (stored as 16-bit patterns); accumulation is fp32.
+ *
+ * Tensor layouts (row-major, innermost last)
+ *   q, out, k_new, v_new : [T, H, D]        T = number of query rows in the batch
+ *   k_cache, v_cache     : [NB, H, bs, D]   NB blocks of bs tokens; one (block, head) tile is
+ *                                           bs*D contiguous elements
+ *   block_table          : [S, stride] int32, entry j of row i = physical block of tokens
+ *                          j*bs .. j*bs+bs-1 of sequence i; entries past ceil(ctx_i/bs) are
+ *                          never read (pad with -1)
+ */
+#ifndef MPA_H
+#define MPA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mpa_ctx mpa_ctx; /* opaque, host-side */
+
+enum {
+    MPA_OK = 0,
+    MPA_ERR_INVALID_ARG = -1, /* null pointer, negative size, misaligned pointer           */
+    MPA_ERR_UNSUPPORTED = -2, /* head_dim / block_size / dtype / head layout not built      */
+    MPA_ERR_WORKSPACE = -3,   /* workspace missing or smaller than the batch needs          */
+    MPA_ERR_BAD_BATCH = -4,   /* chunk_starts / context_lens describe no valid batch        */
+    MPA_ERR_HIP = -5          /* a HIP runtime call failed; see mpa_last_hip_error          */
+};
+
+enum { MPA_BF16 = 1 };
+
+typedef struct {
+    int32_t num_heads;    /* H, query heads                                                   */
+    int32_t num_kv_heads; /* must equal num_heads (grouped KV heads are not built)            */
+    int32_t head_dim;     /* D: 64 or 128                                                     */
+    int32_t block_size;   /* bs: 16                                                           */
+    int32_t dtype;        /* MPA_BF16                                                         */
+} mpa_config;
+
+/* Tuning / testing knobs for mpa_set_option. */
+enum {
+    MPA_OPT_TG_SPLIT_BLOCKS = 1, /* KV blocks per generation-row work item; 0 = automatic     */
+    MPA_OPT_PP_SPLIT_TOKENS = 2, /* keys per prompt-tile work item (multiple of 64); 0 = auto */
+    MPA_OPT_PP_ROWSTREAM = 3     /* 1 = run prompt rows through the row-streaming body
+                                    (slow; cross-check of the matrix-core body)               */
+};
+
+/* Create a context for one cache geometry.  Validates cfg; makes no HIP call.
+ * Errors: INVALID_ARG (null), UNSUPPORTED (shape or dtype not built). */
+int mpa_create(mpa_ctx **out, const mpa_config *cfg);
+
+/* Free the context (and the pinned host staging it may hold).  NULL is accepted. */
+int mpa_destroy(mpa_ctx *ctx);
+
+int mpa_set_option(mpa_ctx *ctx, int32_t option, int64_t value);
+
+/* Raw hipError_t of the last failing HIP call made through ctx (0 if none). */
+int mpa_last_hip_error(const mpa_ctx *ctx);
+
+const char *mpa_status_string(int status);
+
+/* Bytes of device workspace mpa_mixed_paged_attention needs for this very batch
+ * (chunk_starts [num_seqs+1] and context_lens [num_seqs] are host pointers, as below).
+ * Returns 0 on a malformed batch. */
+size_t mpa_workspace_bytes_for_batch(const mpa_ctx *ctx, const int32_t *chunk_starts,
+                                     const int32_t *context_lens, int32_t num_seqs);
+
+/* Upper bound of the above over all batches with at most max_seqs sequences, max_tokens query
+ * rows in total and context lengths up to max_ctx. */
+size_t mpa_workspace_bytes(const mpa_ctx *ctx, int32_t max_seqs, int32_t max_tokens,
+                           int32_t max_ctx);
+
+/*
+ * KV-cache append (Sec. 2.2 "KVC allocation": the K/V of all tokens of a step are stored in the
+ * cache).  For every token t in [0, num_tokens) with slot_map[t] >= 0 and every head h, copies
+ * k_new[t,h,:] to k_cache[slot/bs, h, slot%bs, :] and the same for V; bit-exact.
+ *
+ *   k_new, v_new : device, [num_tokens, H, D], 16-byte aligned, read only
+ *   slot_map     : device, [num_tokens] int64; negative = skip the token.  Non-negative
+ *                  entries must be pairwise distinct and below NB*bs (not checked).
+ *   k_cache, v_cache : device, [NB, H, bs, D], 16-byte aligned, written in place
+ *   num_tokens == 0 is a no-op.
+ * Errors: INVALID_ARG, HIP.
+ */
+int mpa_kv_append(mpa_ctx *ctx, const void *k_new, const void *v_new, const int64_t *slot_map,
+                  int32_t num_tokens, void *k_cache, void *v_cache, void *stream);
+
+/*
+ * Attention of every query row of a mixed batch over its sequence's cached K/V.
+ *
+ * Sequence i owns rows chunk_starts[i] .. chunk_starts[i+1]-1 of q/out (q_len_i of them; the
+ * row boundaries of the ragged batch).  context_lens[i] is the sequence's KV length including
+ * this iteration's tokens, which the caller has appended before (same stream => ordered).  Row
+ * j of sequence i sits at absolute position p = context_lens[i] - q_len_i + j and gets
+ *     out = sum_{t<=p} softmax_t(scale * q . k_t) v_t
+ * with k_t, v_t read through block_table[i].  q_len_i == 1 is a generation task, q_len_i > 1 a
+ * prompt chunk; both kinds run in one kernel launch.
+ *
+ *   q            : device, [num_tokens, H, D] bf16, 16-byte aligned
+ *   k_cache, v_cache : device, read only here
+ *   block_table  : device, [num_seqs, block_table_stride] int32; entries
+ *                  [0, ceil(context_lens[i]/bs)) of row i must be valid block ids (not checked)
+ *   chunk_starts : HOST, [num_seqs+1], chunk_starts[0] == 0, strictly increasing,
+ *                  chunk_starts[num_seqs] == num_tokens
+ *   context_lens : HOST, [num_seqs], context_lens[i] >= q_len_i
+ *   scale        : multiplies the scores; <= 0 selects 1/sqrt(D)
+ *   out          : device, [num_tokens, H, D] bf16 (round to nearest even of the fp32 result)
+ *   workspace    : device, 256-byte aligned, at least mpa_workspace_bytes_for_batch bytes; holds
+ *                  the work list and split partial results for the duration of the call's GPU
+ *                  work; contents need no initialisation.  Two calls that may overlap on the GPU
+ *                  need different workspaces.
+ *   num_seqs == 0 (and num_tokens == 0) is a no-op.
+ * Slots past a sequence's context length, unreferenced blocks and table padding never influence
+ * the result (they may hold NaN patterns).
+ * Errors: INVALID_ARG, BAD_BATCH, WORKSPACE, HIP.
+ */
+int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache,
+                              const void *v_cache, const int32_t *block_table,
+                              int32_t block_table_stride, const int32_t *chunk_starts,
+                              const int32_t *context_lens, int32_t num_seqs, int32_t num_tokens,
+                              float scale, void *out, void *workspace, size_t workspace_bytes,
+                              void *stream);
+
+/*
+ * Host-only view of the work decomposition of a batch (no HIP call; usable without a GPU).
+ * Writes up to `cap` work items as 8 int32 each
+ *   {seq, q_row0, q_rows, q_pos0, kv_begin, kv_end, part_row, kind}
+ * and returns the total number of items (which may exceed cap), or a negative status.
+ * counts (optional, 4 int32): {prompt-tile items, row items, merge rows, partial rows}.
+ */
+int64_t mpa_plan_describe(const mpa_ctx *ctx, const int32_t *chunk_starts,
+                          const int32_t *context_lens, int32_t num_seqs, int32_t *items,
+                          int64_t cap, int32_t *counts);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MPA_H */

@@ -1,0 +1,190 @@
+"""Thin Python binding of libmpa.so (argument marshalling only; all compute is in the HIP library).
+
+Device tensors are anything with a ``data_ptr()`` (torch tensors on the GPU); the host-side batch
+description (chunk_starts, context_lens) is a numpy int32 array or a sequence of ints.  There is
+no CPU fallback: if the library is missing, importing names from here raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmpa.so")
+
+MPA_OK = 0
+MPA_ERR_INVALID_ARG = -1
+MPA_ERR_UNSUPPORTED = -2
+MPA_ERR_WORKSPACE = -3
+MPA_ERR_BAD_BATCH = -4
+MPA_ERR_HIP = -5
+MPA_BF16 = 1
+MPA_OPT_TG_SPLIT_BLOCKS = 1
+MPA_OPT_PP_SPLIT_TOKENS = 2
+MPA_OPT_PP_ROWSTREAM = 3
+
+EXPORTS = [
+    "mpa_create", "mpa_destroy", "mpa_set_option", "mpa_last_hip_error", "mpa_status_string",
+    "mpa_workspace_bytes_for_batch", "mpa_workspace_bytes", "mpa_kv_append",
+    "mpa_mixed_paged_attention", "mpa_plan_describe",
+]
+
+
+class MpaConfig(ctypes.Structure):
+    _fields_ = [("num_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32), ("block_size", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+
+
+class MpaError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {status_string(status)} ({status})")
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load libmpa.so (build it first with paper_2503_13737_amd/build.py); raises if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2503_13737_amd.build`")
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+        lib.mpa_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(MpaConfig)]
+        lib.mpa_create.restype = ctypes.c_int
+        lib.mpa_destroy.argtypes = [vp]
+        lib.mpa_destroy.restype = ctypes.c_int
+        lib.mpa_set_option.argtypes = [vp, i32, i64]
+        lib.mpa_set_option.restype = ctypes.c_int
+        lib.mpa_last_hip_error.argtypes = [vp]
+        lib.mpa_last_hip_error.restype = ctypes.c_int
+        lib.mpa_status_string.argtypes = [ctypes.c_int]
+        lib.mpa_status_string.restype = ctypes.c_char_p
+        lib.mpa_workspace_bytes_for_batch.argtypes = [vp, vp, vp, i32]
+        lib.mpa_workspace_bytes_for_batch.restype = sz
+        lib.mpa_workspace_bytes.argtypes = [vp, i32, i32, i32]
+        lib.mpa_workspace_bytes.restype = sz
+        lib.mpa_kv_append.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp]
+        lib.mpa_kv_append.restype = ctypes.c_int
+        lib.mpa_mixed_paged_attention.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, i32, i32,
+                                                  ctypes.c_float, vp, vp, sz, vp]
+        lib.mpa_mixed_paged_attention.restype = ctypes.c_int
+        lib.mpa_plan_describe.argtypes = [vp, vp, vp, i32, vp, i64, vp]
+        lib.mpa_plan_describe.restype = i64
+        _lib = lib
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return load().mpa_status_string(int(status)).decode()
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if hasattr(t, "data_ptr"):
+        return ctypes.c_void_p(t.data_ptr())
+    if isinstance(t, np.ndarray):
+        return ctypes.c_void_p(t.ctypes.data)
+    return ctypes.c_void_p(int(t))
+
+
+def _host_i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+class Context:
+    """Owns an mpa_ctx for one cache geometry."""
+
+    def __init__(self, num_heads: int, head_dim: int, block_size: int = 16, num_kv_heads: int | None = None,
+                 dtype: int = MPA_BF16):
+        cfg = MpaConfig(num_heads, num_heads if num_kv_heads is None else num_kv_heads, head_dim,
+                        block_size, dtype)
+        h = ctypes.c_void_p()
+        rc = load().mpa_create(ctypes.byref(h), ctypes.byref(cfg))
+        if rc != MPA_OK:
+            raise MpaError(rc, "mpa_create")
+        self._h = h
+        self.num_heads, self.head_dim, self.block_size = num_heads, head_dim, block_size
+
+    def close(self):
+        if getattr(self, "_h", None):
+            load().mpa_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def set_option(self, option: int, value: int):
+        rc = load().mpa_set_option(self._h, option, value)
+        if rc != MPA_OK:
+            raise MpaError(rc, "mpa_set_option")
+
+    def last_hip_error(self) -> int:
+        return load().mpa_last_hip_error(self._h)
+
+    def workspace_bytes_for_batch(self, chunk_starts, context_lens) -> int:
+        cs, cl = _host_i32(chunk_starts), _host_i32(context_lens)
+        return int(load().mpa_workspace_bytes_for_batch(self._h, _ptr(cs), _ptr(cl), cl.size))
+
+    def workspace_bytes(self, max_seqs: int, max_tokens: int, max_ctx: int) -> int:
+        return int(load().mpa_workspace_bytes(self._h, max_seqs, max_tokens, max_ctx))
+
+    def plan_describe(self, chunk_starts, context_lens):
+        """(items [n,8] int32, counts [4] int32) — host-only view of the work list."""
+        cs, cl = _host_i32(chunk_starts), _host_i32(context_lens)
+        counts = np.zeros(4, dtype=np.int32)
+        n = load().mpa_plan_describe(self._h, _ptr(cs), _ptr(cl), cl.size, None, 0, _ptr(counts))
+        if n < 0:
+            raise MpaError(int(n), "mpa_plan_describe")
+        items = np.zeros((max(int(n), 1), 8), dtype=np.int32)
+        load().mpa_plan_describe(self._h, _ptr(cs), _ptr(cl), cl.size, _ptr(items), int(n), _ptr(counts))
+        return items[: int(n)], counts
+
+    def kv_append(self, k_new, v_new, slot_map, k_cache, v_cache, stream=None, num_tokens=None):
+        n = int(k_new.shape[0]) if num_tokens is None else int(num_tokens)
+        rc = load().mpa_kv_append(self._h, _ptr(k_new), _ptr(v_new), _ptr(slot_map), n,
+                                  _ptr(k_cache), _ptr(v_cache), _stream_ptr(stream))
+        if rc != MPA_OK:
+            raise MpaError(rc, "mpa_kv_append")
+
+    def mixed_paged_attention(self, q, k_cache, v_cache, block_table, chunk_starts, context_lens, out,
+                              workspace, scale: float = 0.0, stream=None, block_table_stride=None,
+                              workspace_bytes=None):
+        cs, cl = _host_i32(chunk_starts), _host_i32(context_lens)
+        stride = int(block_table.shape[1]) if block_table_stride is None else int(block_table_stride)
+        wsb = (int(workspace.numel() * workspace.element_size()) if workspace_bytes is None
+               else int(workspace_bytes))
+        rc = load().mpa_mixed_paged_attention(
+            self._h, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_table), stride, _ptr(cs), _ptr(cl),
+            cl.size, int(q.shape[0]), float(scale), _ptr(out), _ptr(workspace), wsb, _stream_ptr(stream))
+        if rc != MPA_OK:
+            raise MpaError(rc, "mpa_mixed_paged_attention")
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        try:
+            import torch
+            if torch.cuda.is_available():
+                return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        except ImportError:
+            pass
+        return None
+    if hasattr(stream, "cuda_stream"):
+        return ctypes.c_void_p(stream.cuda_stream)
+    return ctypes.c_void_p(int(stream))
+
+
+# module-level functions with the names of the C entry points
+def kv_append(ctx: Context, k_new, v_new, slot_map, k_cache, v_cache, stream=None):
+    ctx.kv_append(k_new, v_new, slot_map, k_cache, v_cache, stream)
+
+
+def mixed_paged_attention(ctx: Context, q, k_cache, v_cache, block_table, chunk_starts, context_lens, out,
+                          workspace, scale: float = 0.0, stream=None):
+    ctx.mixed_paged_attention(q, k_cache, v_cache, block_table, chunk_starts, context_lens, out, workspace,
+                              scale, stream)

@@ -1,0 +1,239 @@
+// C ABI of libmpa.so: argument checks, planning, upload of the work list, kernel launches.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <mutex>
+#include <new>
+
+#include "../../include/mpa.h"
+#include "mpa_internal.h"
+
+using namespace mpa;
+
+namespace {
+constexpr int kStagingSlots = 8;
+
+struct Staging {
+    void *host = nullptr;  // pinned
+    size_t bytes = 0;
+    hipEvent_t done = nullptr;
+    bool in_flight = false;
+};
+}  // namespace
+
+struct mpa_ctx {
+    mpa_config cfg;
+    PlanOptions opt;
+    int last_hip = 0;
+    Staging staging[kStagingSlots];
+    int next_slot = 0;
+    Plan plan;  // reused between calls to keep its vectors' capacity
+    std::mutex mu;
+};
+
+static bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+extern "C" {
+
+const char *mpa_status_string(int status)
+{
+    switch (status) {
+    case MPA_OK: return "ok";
+    case MPA_ERR_INVALID_ARG: return "invalid argument";
+    case MPA_ERR_UNSUPPORTED: return "unsupported configuration";
+    case MPA_ERR_WORKSPACE: return "workspace missing or too small";
+    case MPA_ERR_BAD_BATCH: return "malformed batch description";
+    case MPA_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+int mpa_create(mpa_ctx **out, const mpa_config *cfg)
+{
+    if (!out || !cfg) return MPA_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (cfg->num_heads <= 0) return MPA_ERR_INVALID_ARG;
+    if (cfg->dtype != MPA_BF16) return MPA_ERR_UNSUPPORTED;
+    if (cfg->num_kv_heads != cfg->num_heads) return MPA_ERR_UNSUPPORTED;
+    if (cfg->head_dim != 64 && cfg->head_dim != 128) return MPA_ERR_UNSUPPORTED;
+    if (cfg->block_size != kBlockSize) return MPA_ERR_UNSUPPORTED;
+    mpa_ctx *c = new (std::nothrow) mpa_ctx();
+    if (!c) return MPA_ERR_INVALID_ARG;
+    c->cfg = *cfg;
+    c->opt.heads = cfg->num_heads;
+    c->opt.head_dim = cfg->head_dim;
+    c->opt.pp_rowstream = 1;  // until the matrix-core body is in place
+    *out = c;
+    return MPA_OK;
+}
+
+int mpa_destroy(mpa_ctx *ctx)
+{
+    if (!ctx) return MPA_OK;
+    for (auto &s : ctx->staging) {
+        if (s.done) {
+            if (s.in_flight) (void)hipEventSynchronize(s.done);
+            (void)hipEventDestroy(s.done);
+        }
+        if (s.host) (void)hipHostFree(s.host);
+    }
+    delete ctx;
+    return MPA_OK;
+}
+
+int mpa_set_option(mpa_ctx *ctx, int32_t option, int64_t value)
+{
+    if (!ctx || value < 0) return MPA_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> g(ctx->mu);
+    switch (option) {
+    case MPA_OPT_TG_SPLIT_BLOCKS: ctx->opt.tg_split_blocks = value; return MPA_OK;
+    case MPA_OPT_PP_SPLIT_TOKENS: ctx->opt.pp_split_tokens = value; return MPA_OK;
+    case MPA_OPT_PP_ROWSTREAM: ctx->opt.pp_rowstream = value ? 1 : 0; return MPA_OK;
+    default: return MPA_ERR_INVALID_ARG;
+    }
+}
+
+int mpa_last_hip_error(const mpa_ctx *ctx) { return ctx ? ctx->last_hip : 0; }
+
+size_t mpa_workspace_bytes_for_batch(const mpa_ctx *ctx, const int32_t *chunk_starts,
+                                     const int32_t *context_lens, int32_t num_seqs)
+{
+    if (!ctx || num_seqs < 0 || (num_seqs > 0 && (!chunk_starts || !context_lens))) return 0;
+    Plan p;
+    if (build_plan(ctx->opt, chunk_starts, context_lens, num_seqs, &p) != MPA_OK) return 0;
+    return p.total_bytes > 256 ? p.total_bytes : 256;
+}
+
+size_t mpa_workspace_bytes(const mpa_ctx *ctx, int32_t max_seqs, int32_t max_tokens, int32_t max_ctx)
+{
+    if (!ctx) return 0;
+    return plan_bytes_upper_bound(ctx->opt, max_seqs, max_tokens, max_ctx);
+}
+
+int64_t mpa_plan_describe(const mpa_ctx *ctx, const int32_t *chunk_starts,
+                          const int32_t *context_lens, int32_t num_seqs, int32_t *items,
+                          int64_t cap, int32_t *counts)
+{
+    if (!ctx || num_seqs < 0 || (num_seqs > 0 && (!chunk_starts || !context_lens)) || cap < 0 ||
+        (cap > 0 && !items))
+        return MPA_ERR_INVALID_ARG;
+    Plan p;
+    int rc = build_plan(ctx->opt, chunk_starts, context_lens, num_seqs, &p);
+    if (rc != MPA_OK) return rc;
+    const int64_t n = (int64_t)p.items.size();
+    if (cap > 0) std::memcpy(items, p.items.data(), (size_t)(n < cap ? n : cap) * sizeof(WorkItem));
+    if (counts) {
+        counts[0] = p.n_tile_items;
+        counts[1] = p.n_row_items;
+        counts[2] = (int32_t)p.merge.size();
+        counts[3] = (int32_t)p.part_rows;
+    }
+    return n;
+}
+
+int mpa_kv_append(mpa_ctx *ctx, const void *k_new, const void *v_new, const int64_t *slot_map,
+                  int32_t num_tokens, void *k_cache, void *v_cache, void *stream)
+{
+    if (!ctx || num_tokens < 0) return MPA_ERR_INVALID_ARG;
+    if (num_tokens == 0) return MPA_OK;
+    if (!k_new || !v_new || !slot_map || !k_cache || !v_cache) return MPA_ERR_INVALID_ARG;
+    if (!aligned(k_new, 16) || !aligned(v_new, 16) || !aligned(k_cache, 16) || !aligned(v_cache, 16) ||
+        !aligned(slot_map, 8))
+        return MPA_ERR_INVALID_ARG;
+    int e = launch_kv_append(k_new, v_new, slot_map, num_tokens, ctx->cfg.num_heads, ctx->cfg.head_dim,
+                             k_cache, v_cache, stream);
+    if (e != 0) {
+        ctx->last_hip = e;
+        return MPA_ERR_HIP;
+    }
+    return MPA_OK;
+}
+
+int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache, const void *v_cache,
+                              const int32_t *block_table, int32_t block_table_stride,
+                              const int32_t *chunk_starts, const int32_t *context_lens,
+                              int32_t num_seqs, int32_t num_tokens, float scale, void *out,
+                              void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!ctx || num_seqs < 0 || num_tokens < 0) return MPA_ERR_INVALID_ARG;
+    if (num_seqs == 0) return num_tokens == 0 ? MPA_OK : MPA_ERR_BAD_BATCH;
+    if (!q || !k_cache || !v_cache || !block_table || !chunk_starts || !context_lens || !out)
+        return MPA_ERR_INVALID_ARG;
+    if (block_table_stride <= 0) return MPA_ERR_INVALID_ARG;
+    if (!aligned(q, 16) || !aligned(out, 16) || !aligned(k_cache, 16) || !aligned(v_cache, 16) ||
+        !aligned(block_table, 4))
+        return MPA_ERR_INVALID_ARG;
+    if (!(scale == scale)) return MPA_ERR_INVALID_ARG;  // NaN
+
+    std::lock_guard<std::mutex> g(ctx->mu);
+    Plan &plan = ctx->plan;
+    int rc = build_plan(ctx->opt, chunk_starts, context_lens, num_seqs, &plan);
+    if (rc != MPA_OK) return rc;
+    if (chunk_starts[num_seqs] != num_tokens) return MPA_ERR_BAD_BATCH;
+    for (int32_t i = 0; i < num_seqs; ++i)
+        if ((int64_t)(context_lens[i] + kBlockSize - 1) / kBlockSize > block_table_stride)
+            return MPA_ERR_BAD_BATCH;
+    if (!workspace || !aligned(workspace, 256) || workspace_bytes < plan.total_bytes)
+        return MPA_ERR_WORKSPACE;
+
+    auto fail = [&](hipError_t e) {
+        ctx->last_hip = (int)e;
+        return MPA_ERR_HIP;
+    };
+
+    // stage the work list in pinned memory and copy it into the workspace on the stream
+    const size_t list_bytes = plan.off_acc;  // items + merge rows, padded
+    Staging &st = ctx->staging[ctx->next_slot];
+    ctx->next_slot = (ctx->next_slot + 1) % kStagingSlots;
+    hipError_t e;
+    if (st.in_flight) {
+        if ((e = hipEventSynchronize(st.done)) != hipSuccess) return fail(e);
+        st.in_flight = false;
+    }
+    if (st.bytes < list_bytes) {
+        if (st.host) (void)hipHostFree(st.host);
+        st.host = nullptr;
+        st.bytes = 0;
+        size_t want = list_bytes * 2;
+        if ((e = hipHostMalloc(&st.host, want, hipHostMallocDefault)) != hipSuccess) return fail(e);
+        st.bytes = want;
+    }
+    if (!st.done && (e = hipEventCreateWithFlags(&st.done, hipEventDisableTiming)) != hipSuccess)
+        return fail(e);
+    char *h = static_cast<char *>(st.host);
+    std::memcpy(h + plan.off_items, plan.items.data(), plan.items.size() * sizeof(WorkItem));
+    std::memcpy(h + plan.off_merge, plan.merge.data(), plan.merge.size() * sizeof(MergeRow));
+    hipStream_t s = (hipStream_t)stream;
+    if ((e = hipMemcpyAsync(workspace, h, list_bytes, hipMemcpyHostToDevice, s)) != hipSuccess)
+        return fail(e);
+    if ((e = hipEventRecord(st.done, s)) != hipSuccess) return fail(e);
+    st.in_flight = true;
+
+    char *ws = static_cast<char *>(workspace);
+    AttnParams p;
+    p.q = static_cast<const uint16_t *>(q);
+    p.k_cache = static_cast<const uint16_t *>(k_cache);
+    p.v_cache = static_cast<const uint16_t *>(v_cache);
+    p.block_table = block_table;
+    p.table_stride = block_table_stride;
+    p.heads = ctx->cfg.num_heads;
+    const float sc = scale > 0.f ? scale : 1.0f / std::sqrt((float)ctx->cfg.head_dim);
+    p.scale_log2e = sc * 1.4426950408889634f;
+    p.out = static_cast<uint16_t *>(out);
+    p.items = reinterpret_cast<const WorkItem *>(ws + plan.off_items);
+    p.n_tile_items = plan.n_tile_items;
+    p.n_row_items = plan.n_row_items;
+    p.part_acc = reinterpret_cast<float *>(ws + plan.off_acc);
+    p.part_ml = reinterpret_cast<float *>(ws + plan.off_ml);
+    p.merge = reinterpret_cast<const MergeRow *>(ws + plan.off_merge);
+    p.n_merge = (int32_t)plan.merge.size();
+
+    int he = launch_attention(p, ctx->cfg.head_dim, stream);
+    if (he != 0) return fail((hipError_t)he);
+    he = launch_merge(p, ctx->cfg.head_dim, stream);
+    if (he != 0) return fail((hipError_t)he);
+    return MPA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,89 @@
+// Internal declarations shared by the host planner, the C ABI and the kernel launchers.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+namespace mpa {
+
+constexpr int kBlockSize = 16;   // tokens per KV block
+constexpr int kTileRows = 128;   // query rows of one prompt tile (matrix-core body)
+constexpr int kKvTile = 64;      // keys staged per step of the matrix-core body
+constexpr int kThreads = 256;    // work-group size of the attention kernel (4 wavefronts)
+constexpr int kWaves = kThreads / 64;
+
+enum ItemKind : int32_t { kRowItem = 0, kTileItem = 1 };
+
+// One unit of work.  A tile item is executed by one work-group per head; a row item by one
+// wavefront per head (a work-group covers kWaves consecutive heads).
+struct WorkItem {
+    int32_t seq;       // sequence index = row of the block table
+    int32_t q_row0;    // first row in q / out
+    int32_t q_rows;    // rows of this item (1 for a row item)
+    int32_t q_pos0;    // absolute position of row 0 inside its sequence
+    int32_t kv_begin;  // first key position covered (multiple of the KV tile / block)
+    int32_t kv_end;    // one past the last key position covered (<= q_pos0 + q_rows)
+    int32_t part_row;  // first row in the partial buffers, or -1: write `out` directly
+    int32_t kind;      // ItemKind
+};
+static_assert(sizeof(WorkItem) == 32, "work item layout");
+
+// One output row whose keys were split over several items.
+struct MergeRow {
+    int32_t out_row;   // row in out
+    int32_t part_row;  // partial row of split 0
+    int32_t stride;    // partial rows between consecutive splits
+    int32_t nsplit;
+};
+static_assert(sizeof(MergeRow) == 16, "merge row layout");
+
+struct PlanOptions {
+    int32_t heads = 0;
+    int32_t head_dim = 0;
+    int64_t tg_split_blocks = 0;  // 0 = automatic
+    int64_t pp_split_tokens = 0;  // 0 = automatic
+    int64_t pp_rowstream = 0;
+};
+
+struct Plan {
+    std::vector<WorkItem> items;  // tile items first, then row items; each group longest first
+    std::vector<MergeRow> merge;
+    int32_t n_tile_items = 0;
+    int32_t n_row_items = 0;
+    int64_t part_rows = 0;
+
+    // workspace layout (byte offsets)
+    size_t off_items = 0, off_merge = 0, off_acc = 0, off_ml = 0, total_bytes = 0;
+};
+
+// Returns MPA_OK or MPA_ERR_BAD_BATCH.
+int build_plan(const PlanOptions &opt, const int32_t *chunk_starts, const int32_t *context_lens,
+               int32_t num_seqs, Plan *plan);
+size_t plan_bytes_upper_bound(const PlanOptions &opt, int64_t max_seqs, int64_t max_tokens,
+                              int64_t max_ctx);
+
+struct AttnParams {
+    const uint16_t *q;
+    const uint16_t *k_cache;
+    const uint16_t *v_cache;
+    const int32_t *block_table;
+    int32_t table_stride;
+    int32_t heads;
+    float scale_log2e;  // scale * log2(e): scores are kept in base-2 exponent units
+    uint16_t *out;
+    const WorkItem *items;
+    int32_t n_tile_items;
+    int32_t n_row_items;
+    float *part_acc;  // [part_rows, H, D]
+    float *part_ml;   // [part_rows, H, 2]  (running max in base-2 units, running sum)
+    const MergeRow *merge;
+    int32_t n_merge;
+};
+
+// Kernel launchers (kernels.hip).  Return the raw hipError_t as int.
+int launch_kv_append(const void *k_new, const void *v_new, const int64_t *slot_map, int32_t T,
+                     int32_t H, int32_t D, void *k_cache, void *v_cache, void *stream);
+int launch_attention(const AttnParams &p, int32_t D, void *stream);
+int launch_merge(const AttnParams &p, int32_t D, void *stream);
+
+}  // namespace mpa

@@ -1,0 +1,175 @@
+// Host planner: turns the ragged batch description (row offsets + context lengths) into the
+// work list the attention kernel consumes.  Pure host code, no HIP.
+//
+// A sequence with one row (generation task) becomes row items: its keys are cut into
+// contiguous ranges of whole KV blocks so that the chip sees several thousand equally sized
+// streams.  A sequence with several rows (prompt chunk; Sec. 2.3 / 4.2 of the paper: rows
+// prior..prior+q_len-1 of the prompt, attending to everything before them) becomes tile items
+// of up to kTileRows rows, each tile's key range [0, last row's position] again cut into
+// ranges when it is long.  Every item that is one of several over the same rows writes a
+// partial result, and the rows are listed for the merge pass.
+#include <algorithm>
+#include <numeric>
+
+#include "../../include/mpa.h"
+#include "mpa_internal.h"
+
+namespace mpa {
+
+namespace {
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Target number of concurrently schedulable units: 256 compute units, 8 wavefronts each,
+// several items per wavefront slot so the tail of the launch stays short.
+constexpr int64_t kRowItemTarget = 256 * 8 * 6;
+constexpr int64_t kMinRowSplitBlocks = 8;
+constexpr int64_t kTileGroupTarget = 1024;
+constexpr int64_t kMinTileSplitSteps = 16;  // 1024 keys
+
+int64_t auto_row_split_blocks(const PlanOptions &opt, int64_t total_blocks)
+{
+    if (opt.tg_split_blocks > 0) return opt.tg_split_blocks;
+    int64_t s = ceil_div(total_blocks * opt.heads, kRowItemTarget);
+    return std::max<int64_t>(s, kMinRowSplitBlocks);
+}
+
+int64_t auto_tile_split_tokens(const PlanOptions &opt, int64_t total_steps)
+{
+    if (opt.pp_split_tokens > 0) return ceil_div(opt.pp_split_tokens, kKvTile) * kKvTile;
+    int64_t s = ceil_div(total_steps * opt.heads, kTileGroupTarget);
+    return std::max<int64_t>(s, kMinTileSplitSteps) * kKvTile;
+}
+
+void finish_layout(const PlanOptions &opt, Plan *p)
+{
+    size_t off = 0;
+    p->off_items = off;
+    off = align_up(off + p->items.size() * sizeof(WorkItem), 256);
+    p->off_merge = off;
+    off = align_up(off + p->merge.size() * sizeof(MergeRow), 256);
+    p->off_acc = off;
+    off = align_up(off + (size_t)p->part_rows * opt.heads * opt.head_dim * sizeof(float), 256);
+    p->off_ml = off;
+    off = align_up(off + (size_t)p->part_rows * opt.heads * 2 * sizeof(float), 256);
+    p->total_bytes = off;
+}
+}  // namespace
+
+int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, int32_t S, Plan *plan)
+{
+    plan->items.clear();
+    plan->merge.clear();
+    plan->part_rows = 0;
+    if (S < 0) return MPA_ERR_BAD_BATCH;
+    if (S == 0) {
+        plan->n_tile_items = plan->n_row_items = 0;
+        finish_layout(opt, plan);
+        return MPA_OK;
+    }
+    if (cs[0] != 0) return MPA_ERR_BAD_BATCH;
+    int64_t row_blocks = 0, tile_steps = 0;
+    for (int32_t i = 0; i < S; ++i) {
+        int64_t q_len = (int64_t)cs[i + 1] - cs[i];
+        if (q_len < 1 || ctx[i] < q_len) return MPA_ERR_BAD_BATCH;
+        int64_t prior = ctx[i] - q_len;
+        if (q_len == 1 || opt.pp_rowstream) {
+            for (int64_t j = 0; j < q_len; ++j) row_blocks += ceil_div(prior + j + 1, kBlockSize);
+        } else {
+            for (int64_t r0 = 0; r0 < q_len; r0 += kTileRows) {
+                int64_t rows = std::min<int64_t>(kTileRows, q_len - r0);
+                tile_steps += ceil_div(prior + r0 + rows, kKvTile);
+            }
+        }
+    }
+    const int64_t row_split = auto_row_split_blocks(opt, row_blocks);
+    const int64_t tile_split = auto_tile_split_tokens(opt, tile_steps);
+
+    std::vector<WorkItem> tiles, rows;
+    auto emit = [&](std::vector<WorkItem> &dst, int32_t kind, int32_t seq, int32_t q_row0,
+                    int32_t q_rows, int32_t q_pos0, int64_t split_len, int64_t granule) {
+        const int64_t kv_len = (int64_t)q_pos0 + q_rows;  // keys visible to the last row
+        int64_t nsplit = ceil_div(kv_len, split_len);
+        // equal ranges, each a whole number of granules
+        int64_t len = ceil_div(ceil_div(kv_len, nsplit), granule) * granule;
+        nsplit = ceil_div(kv_len, len);
+        int32_t part0 = -1;
+        if (nsplit > 1) {
+            part0 = (int32_t)plan->part_rows;
+            plan->part_rows += nsplit * q_rows;
+            for (int32_t r = 0; r < q_rows; ++r) {
+                // a row only has partials from the ranges that start at or below its position
+                int64_t ns_r = std::min<int64_t>(nsplit, ((int64_t)q_pos0 + r) / len + 1);
+                plan->merge.push_back(MergeRow{q_row0 + r, part0 + r, q_rows, (int32_t)ns_r});
+            }
+        }
+        for (int64_t s = 0; s < nsplit; ++s) {
+            WorkItem it;
+            it.seq = seq;
+            it.q_row0 = q_row0;
+            it.q_rows = q_rows;
+            it.q_pos0 = q_pos0;
+            it.kv_begin = (int32_t)(s * len);
+            it.kv_end = (int32_t)std::min<int64_t>(kv_len, (s + 1) * len);
+            it.part_row = nsplit > 1 ? (int32_t)(part0 + s * q_rows) : -1;
+            it.kind = kind;
+            dst.push_back(it);
+        }
+    };
+
+    for (int32_t i = 0; i < S; ++i) {
+        int32_t q_len = cs[i + 1] - cs[i];
+        int32_t prior = ctx[i] - q_len;
+        if (q_len == 1 || opt.pp_rowstream) {
+            for (int32_t j = 0; j < q_len; ++j)
+                emit(rows, kRowItem, i, cs[i] + j, 1, prior + j, row_split * kBlockSize, kBlockSize);
+        } else {
+            for (int32_t r0 = 0; r0 < q_len; r0 += kTileRows) {
+                int32_t nr = std::min<int32_t>(kTileRows, q_len - r0);
+                emit(tiles, kTileItem, i, cs[i] + r0, nr, prior + r0, tile_split, kKvTile);
+            }
+        }
+    }
+    auto cost = [](const WorkItem &w) {
+        // keys actually visited, summed over rows (upper triangle of the last range excluded)
+        int64_t full = (int64_t)(w.kv_end - w.kv_begin) * w.q_rows;
+        return full;
+    };
+    auto longer = [&](const WorkItem &a, const WorkItem &b) { return cost(a) > cost(b); };
+    std::stable_sort(tiles.begin(), tiles.end(), longer);
+    std::stable_sort(rows.begin(), rows.end(), longer);
+    plan->n_tile_items = (int32_t)tiles.size();
+    plan->n_row_items = (int32_t)rows.size();
+    plan->items = std::move(tiles);
+    plan->items.insert(plan->items.end(), rows.begin(), rows.end());
+    finish_layout(opt, plan);
+    return MPA_OK;
+}
+
+size_t plan_bytes_upper_bound(const PlanOptions &opt, int64_t max_seqs, int64_t max_tokens,
+                              int64_t max_ctx)
+{
+    if (max_seqs <= 0 || max_tokens <= 0 || max_ctx <= 0) return 256;
+    // Ranges are never shorter than the minimum split (or the forced one), so:
+    const int64_t row_split = opt.tg_split_blocks > 0 ? opt.tg_split_blocks : kMinRowSplitBlocks;
+    const int64_t tile_split = opt.pp_split_tokens > 0
+                                   ? ceil_div(opt.pp_split_tokens, kKvTile) * kKvTile
+                                   : kMinTileSplitSteps * kKvTile;
+    const int64_t row_ns = ceil_div(ceil_div(max_ctx, kBlockSize), row_split);
+    const int64_t tile_ns = ceil_div(max_ctx, tile_split);
+    // every row may be a generation task; alternatively rows group into tiles
+    const int64_t n_rows_as_items = std::max(max_seqs, max_tokens);
+    const int64_t n_tiles = max_tokens / 2 + max_seqs;  // a tile has >= 2 rows unless it is a remainder
+    const int64_t items = n_rows_as_items * row_ns + n_tiles * tile_ns;
+    const int64_t part_rows = n_rows_as_items * row_ns + (max_tokens + 0) * tile_ns;
+    const int64_t merge_rows = max_tokens;
+    Plan p;
+    size_t off = 0;
+    off = align_up(off + (size_t)items * sizeof(WorkItem), 256);
+    off = align_up(off + (size_t)merge_rows * sizeof(MergeRow), 256);
+    off = align_up(off + (size_t)part_rows * opt.heads * opt.head_dim * sizeof(float), 256);
+    off = align_up(off + (size_t)part_rows * opt.heads * 2 * sizeof(float), 256);
+    return off;
+}
+
+}  // namespace mpa

@@ -1,0 +1,78 @@
+"""Shared helpers of the tests: run a workloads.Batch through the GPU library, and through the
+oracle, and compare.  (The GPU side uses torch only to hold device memory.)"""
+from __future__ import annotations
+
+import numpy as np
+
+import workloads as W
+
+MAX_ABS_TOL = 1e-2   # bf16 in, fp32 accumulate, bf16 out
+REL_L2_TOL = 5e-3
+
+
+def to_dev(a: np.ndarray):
+    import torch
+    if a.dtype == np.uint16:
+        return torch.from_numpy(a.view(np.int16)).cuda()
+    return torch.from_numpy(a).cuda()
+
+
+def to_host_u16(t) -> np.ndarray:
+    import torch
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def errors(got_bits: np.ndarray, ref: np.ndarray):
+    g = W.bf16_to_f64(got_bits)
+    d = g - ref
+    return float(np.abs(d).max()), float(np.sqrt((d * d).sum() / max((ref * ref).sum(), 1e-300)))
+
+
+def assert_close(got_bits, ref, what=""):
+    assert not np.isnan(W.bf16_to_f64(got_bits)).any(), f"{what}: NaN in output"
+    ma, rl = errors(got_bits, ref)
+    assert ma <= MAX_ABS_TOL and rl <= REL_L2_TOL, f"{what}: max-abs {ma:.3e} rel-L2 {rl:.3e}"
+    return ma, rl
+
+
+class DeviceBatch:
+    """Device copies of a small batch (whole pool materialised)."""
+
+    def __init__(self, b: W.Batch, state: str = "prior"):
+        import torch
+        self.b = b
+        kc, vc = b.full_cache(state)
+        self.k_cache, self.v_cache = to_dev(kc), to_dev(vc)
+        kn, vn = b.new_kv()
+        self.k_new, self.v_new = to_dev(kn), to_dev(vn)
+        self.slot_map = to_dev(b.slot_map)
+        self.q = to_dev(b.q)
+        self.block_table = to_dev(np.ascontiguousarray(b.block_table))
+        # poison the output so rows the kernel fails to write show up
+        self.out = torch.full((b.T, b.H, b.D), 0x7FFF, dtype=torch.int16, device="cuda")
+
+
+def gpu_run(ctx, b: W.Batch, append: bool = True, poison_ws: bool = True):
+    """kv_append (optional) + attention on the GPU; returns (out bits, k_cache bits, v_cache bits)."""
+    import torch
+    db = DeviceBatch(b, "prior" if append else "ctx")
+    if append:
+        ctx.kv_append(db.k_new, db.v_new, db.slot_map, db.k_cache, db.v_cache)
+    nbytes = ctx.workspace_bytes_for_batch(b.chunk_starts, b.context_lens)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    if poison_ws:
+        ws.fill_(0xFF)  # NaN patterns in the partial buffers
+    ctx.mixed_paged_attention(db.q, db.k_cache, db.v_cache, db.block_table, b.chunk_starts,
+                              b.context_lens, db.out, ws, scale=b.scale)
+    torch.cuda.synchronize()
+    return to_host_u16(db.out), to_host_u16(db.k_cache), to_host_u16(db.v_cache)
+
+
+def oracle_run(b: W.Batch):
+    """Oracle append + attention; returns (out float64, k_cache, v_cache)."""
+    import oracle
+    kc, vc = b.full_cache("prior")
+    kn, vn = b.new_kv()
+    oracle.kv_append(kn, vn, b.slot_map, kc, vc)
+    out = oracle.attention(b.q, kc, vc, b.block_table, b.chunk_starts, b.context_lens, b.scale)
+    return out, kc, vc

@@ -1,0 +1,130 @@
+"""Host-side tests of the C ABI: the library loads without a GPU, exports what include/mpa.h
+declares, rejects bad arguments before touching the GPU, and plans batches consistently."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2503_13737_amd as mpa
+import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "mpa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(mpa_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = mpa.load()
+    names = declared_symbols()
+    assert len(names) >= 10
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(mpa.EXPORTS) == names
+
+
+def test_create_validates_config():
+    for kw, status in [(dict(num_heads=4, head_dim=96), mpa.MPA_ERR_UNSUPPORTED),
+                       (dict(num_heads=4, head_dim=64, block_size=32), mpa.MPA_ERR_UNSUPPORTED),
+                       (dict(num_heads=4, head_dim=64, num_kv_heads=2), mpa.MPA_ERR_UNSUPPORTED),
+                       (dict(num_heads=4, head_dim=64, dtype=7), mpa.MPA_ERR_UNSUPPORTED),
+                       (dict(num_heads=0, head_dim=64), mpa.MPA_ERR_INVALID_ARG)]:
+        with pytest.raises(mpa.MpaError) as e:
+            mpa.Context(**kw)
+        assert e.value.status == status
+    assert mpa.load().mpa_create(None, None) == mpa.MPA_ERR_INVALID_ARG
+    c = mpa.Context(4, 64)
+    c.close()
+    assert mpa.load().mpa_destroy(None) == mpa.MPA_OK
+    assert mpa.status_string(mpa.MPA_ERR_BAD_BATCH).startswith("malformed")
+
+
+def test_attention_rejects_bad_arguments_without_gpu():
+    lib = mpa.load()
+    c = mpa.Context(4, 64)
+    cs = np.array([0, 3, 4], dtype=np.int32)
+    cl = np.array([5, 9], dtype=np.int32)
+    fake = ctypes.c_void_p(0x1000)  # aligned, never dereferenced: every case fails validation first
+
+    def call(q=fake, kc=fake, vc=fake, tab=fake, stride=4, cs=cs, cl=cl, S=2, T=4, out=fake, ws=fake, wsb=1 << 20):
+        return lib.mpa_mixed_paged_attention(c._h, q, kc, vc, tab, stride, mpa._ptr(cs), mpa._ptr(cl), S, T,
+                                             0.0, out, ws, wsb, None)
+
+    assert call(q=None) == mpa.MPA_ERR_INVALID_ARG
+    assert call(out=None) == mpa.MPA_ERR_INVALID_ARG
+    assert call(q=ctypes.c_void_p(0x1004)) == mpa.MPA_ERR_INVALID_ARG
+    assert call(stride=0) == mpa.MPA_ERR_INVALID_ARG
+    assert call(S=-1) == mpa.MPA_ERR_INVALID_ARG
+    assert call(T=5) == mpa.MPA_ERR_BAD_BATCH                       # rows do not add up
+    assert call(cs=np.array([0, 3, 3], dtype=np.int32)) == mpa.MPA_ERR_BAD_BATCH   # empty sequence
+    assert call(cs=np.array([1, 3, 4], dtype=np.int32)) == mpa.MPA_ERR_BAD_BATCH   # does not start at 0
+    assert call(cl=np.array([2, 9], dtype=np.int32)) == mpa.MPA_ERR_BAD_BATCH      # ctx < q_len
+    assert call(cl=np.array([5, 100], dtype=np.int32)) == mpa.MPA_ERR_BAD_BATCH    # table too narrow
+    assert call(ws=None) == mpa.MPA_ERR_WORKSPACE
+    assert call(wsb=16) == mpa.MPA_ERR_WORKSPACE
+    assert call(ws=ctypes.c_void_p(0x1010)) == mpa.MPA_ERR_WORKSPACE
+    # empty batch is a no-op
+    assert lib.mpa_mixed_paged_attention(c._h, None, None, None, None, 0, None, None, 0, 0, 0.0, None, None, 0, None) == mpa.MPA_OK
+
+
+def test_kv_append_rejects_bad_arguments_without_gpu():
+    lib = mpa.load()
+    c = mpa.Context(4, 64)
+    fake = ctypes.c_void_p(0x1000)
+    assert lib.mpa_kv_append(c._h, None, fake, fake, 3, fake, fake, None) == mpa.MPA_ERR_INVALID_ARG
+    assert lib.mpa_kv_append(c._h, fake, fake, fake, -1, fake, fake, None) == mpa.MPA_ERR_INVALID_ARG
+    assert lib.mpa_kv_append(c._h, fake, fake, ctypes.c_void_p(0x1004), 3, fake, fake, None) == mpa.MPA_ERR_INVALID_ARG
+    assert lib.mpa_kv_append(c._h, None, None, None, 0, None, None, None) == mpa.MPA_OK
+    assert lib.mpa_kv_append(None, fake, fake, fake, 3, fake, fake, None) == mpa.MPA_ERR_INVALID_ARG
+
+
+def check_plan_covers(b, items, counts, H):
+    """Every (row, key) pair under the causal mask is covered exactly once."""
+    ql, pr = b.q_lens, b.priors
+    for i in range(b.S):
+        for j in range(int(ql[i])):
+            row, pos = int(b.chunk_starts[i]) + j, int(pr[i]) + j
+            cover = []
+            for it in items:
+                seq, q_row0, q_rows, q_pos0, kb, ke, part, kind = it
+                if q_row0 <= row < q_row0 + q_rows:
+                    assert seq == i and q_pos0 + (row - q_row0) == pos
+                    lo, hi = kb, min(ke, pos + 1)
+                    if hi > lo:
+                        cover.append((lo, hi, part))
+            cover.sort()
+            assert cover[0][0] == 0 and cover[-1][1] == pos + 1
+            for a, bb in zip(cover, cover[1:]):
+                assert a[1] == bb[0]
+            if len(cover) > 1:
+                assert all(c[2] >= 0 for c in cover)
+
+
+@pytest.mark.parametrize("opts", [{}, {mpa.MPA_OPT_TG_SPLIT_BLOCKS: 1}, {mpa.MPA_OPT_PP_SPLIT_TOKENS: 64},
+                                  {mpa.MPA_OPT_PP_ROWSTREAM: 1, mpa.MPA_OPT_TG_SPLIT_BLOCKS: 2}])
+def test_plan_covers_every_pair_once(opts):
+    b = W.config1()
+    c = mpa.Context(b.H, b.D)
+    for k, v in opts.items():
+        c.set_option(k, v)
+    items, counts = c.plan_describe(b.chunk_starts, b.context_lens)
+    assert counts[0] + counts[1] == len(items)
+    assert (items[:, 4] % 16 == 0).all()
+    assert (items[items[:, 7] == 1][:, 4] % 64 == 0).all()
+    check_plan_covers(b, items, counts, b.H)
+    need = c.workspace_bytes_for_batch(b.chunk_starts, b.context_lens)
+    assert need >= len(items) * 32
+    assert c.workspace_bytes(b.S, b.T, int(b.context_lens.max())) >= need
+
+
+def test_plan_large_configs_fit_upper_bound():
+    for b in (W.config2(), W.config3(), W.config4()):
+        c = mpa.Context(b.H, b.D)
+        need = c.workspace_bytes_for_batch(b.chunk_starts, b.context_lens)
+        ub = c.workspace_bytes(b.S, b.T, int(b.context_lens.max()))
+        assert 0 < need <= ub, (b.name, need, ub)

@@ -1,0 +1,160 @@
+"""GPU parity: the HIP library against the CPU oracle, element by element, through the C ABI."""
+import numpy as np
+import pytest
+
+import workloads as W
+from harness import DeviceBatch, assert_close, errors, gpu_run, oracle_run, to_dev, to_host_u16
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mpa():
+    import paper_2503_13737_amd as m
+    m.load()
+    return m
+
+
+def ctx_for(mpa, b, **opts):
+    c = mpa.Context(b.H, b.D)
+    for k, v in opts.items():
+        c.set_option(getattr(mpa, k), v)
+    return c
+
+
+def test_config1_append_bit_exact_and_attention(mpa):
+    b = W.config1()
+    out, kc, vc = gpu_run(ctx_for(mpa, b), b)
+    ref, okc, ovc = oracle_run(b)
+    assert np.array_equal(kc, okc) and np.array_equal(vc, ovc)
+    ma, rl = assert_close(out, ref, b.name)
+    print(f"cfg1 max-abs {ma:.2e} rel-L2 {rl:.2e}")
+    # per sequence worst case
+    for i in range(b.S):
+        r0, r1 = b.chunk_starts[i], b.chunk_starts[i + 1]
+        assert_close(out[r0:r1], ref[r0:r1], f"{b.name} seq {i}")
+
+
+def test_kv_append_skips_negative_slots_and_leaves_rest(mpa):
+    import oracle
+    import torch
+    b = W.config1()
+    db = DeviceBatch(b, "prior")
+    sm = b.slot_map.copy()
+    sm[1::2] = -1
+    ctx_for(mpa, b).kv_append(db.k_new, db.v_new, to_dev(sm), db.k_cache, db.v_cache)
+    torch.cuda.synchronize()
+    kc, vc = b.full_cache("prior")
+    kn, vn = b.new_kv()
+    oracle.kv_append(kn, vn, sm, kc, vc)
+    assert np.array_equal(to_host_u16(db.k_cache), kc) and np.array_equal(to_host_u16(db.v_cache), vc)
+
+
+@pytest.mark.parametrize("tg_split", [1, 2, 3, 7, 1000])
+def test_forced_row_splits_agree(mpa, tg_split):
+    b = W.config1()
+    ref, _, _ = oracle_run(b)
+    out, _, _ = gpu_run(ctx_for(mpa, b, MPA_OPT_TG_SPLIT_BLOCKS=tg_split), b)
+    assert_close(out, ref, f"tg_split={tg_split}")
+
+
+@pytest.mark.parametrize("pp_split", [64, 128, 192, 100000])
+def test_forced_tile_splits_agree(mpa, pp_split):
+    b = W.config1()
+    ref, _, _ = oracle_run(b)
+    out, _, _ = gpu_run(ctx_for(mpa, b, MPA_OPT_PP_SPLIT_TOKENS=pp_split), b)
+    assert_close(out, ref, f"pp_split={pp_split}")
+
+
+def test_rowstream_body_on_prompt_rows(mpa):
+    b = W.config1()
+    ref, _, _ = oracle_run(b)
+    out, _, _ = gpu_run(ctx_for(mpa, b, MPA_OPT_PP_ROWSTREAM=1), b)
+    assert_close(out, ref, "rowstream")
+
+
+@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("D,H", [(64, 2), (128, 3), (128, 5)])
+def test_random_ragged_batches(mpa, seed, D, H):
+    b = W.random_ragged(1000 + seed, H=H, D=D, n_pp=2 + seed % 2, n_tg=3, max_q=200, max_prior=300, max_ctx=400)
+    ref, okc, ovc = oracle_run(b)
+    out, kc, vc = gpu_run(ctx_for(mpa, b), b)
+    assert np.array_equal(kc, okc) and np.array_equal(vc, ovc)
+    assert_close(out, ref, b.name)
+
+
+@pytest.mark.parametrize("ql,ctx", [
+    ([1], [1]),                      # single key
+    ([1], [16]), ([1], [17]),        # block boundary
+    ([2], [2]), ([16], [16]), ([17], [33]),
+    ([128], [128]), ([129], [129]), ([127], [200]),   # tile boundary
+    ([64], [64 + 48]), ([37], [37]),
+    ([300], [300]), ([130, 1, 1], [700, 65, 1]),
+])
+def test_edge_shapes(mpa, ql, ctx):
+    b = W.make_batch(f"edge-{ql}-{ctx}", 77, 4, 128, 16, sum((c + 15) // 16 for c in ctx) + 2, ql, ctx)
+    ref, okc, ovc = oracle_run(b)
+    for opts in ({}, {"MPA_OPT_PP_SPLIT_TOKENS": 64, "MPA_OPT_TG_SPLIT_BLOCKS": 1}):
+        out, kc, vc = gpu_run(ctx_for(mpa, b, **opts), b)
+        assert np.array_equal(kc, okc) and np.array_equal(vc, ovc)
+        assert_close(out, ref, f"{b.name} {opts}")
+
+
+def test_empty_batch_is_a_noop(mpa):
+    c = mpa.Context(4, 64)
+    lib = mpa.load()
+    assert lib.mpa_mixed_paged_attention(c._h, None, None, None, None, 0, None, None, 0, 0, 0.0, None, None, 0, None) == 0
+    assert lib.mpa_kv_append(c._h, None, None, None, 0, None, None, None) == 0
+
+
+def test_I3_block_permutation_is_bit_identical(mpa):
+    import torch
+    b = W.config1()
+    c = ctx_for(mpa, b)
+    base, _, _ = gpu_run(c, b, append=False)
+    kc, vc = b.full_cache("ctx")
+    perm = W.permutation(b.NB, 4242)
+    kc2, vc2 = np.empty_like(kc), np.empty_like(vc)
+    kc2[perm], vc2[perm] = kc, vc
+    tab2 = np.where(b.block_table >= 0, perm[np.maximum(b.block_table, 0)], -1).astype(np.int32)
+    db = DeviceBatch(b, "ctx")
+    db.k_cache, db.v_cache, db.block_table = to_dev(kc2), to_dev(vc2), to_dev(tab2)
+    ws = torch.empty(c.workspace_bytes_for_batch(b.chunk_starts, b.context_lens), dtype=torch.uint8, device="cuda")
+    c.mixed_paged_attention(db.q, db.k_cache, db.v_cache, db.block_table, b.chunk_starts, b.context_lens, db.out, ws, scale=b.scale)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host_u16(db.out), base)
+
+
+def test_I1_I2_chunked_and_generation_rows_match_one_shot(mpa):
+    L, H, D = 150, 4, 128
+    one = W.make_batch("one", 31, H, D, 16, 12, [L], [L])
+    ids = one.block_table[0, : (L + 15) // 16]
+    ref, _, _ = oracle_run(one)
+    full, _, _ = gpu_run(ctx_for(mpa, one), one)
+    assert_close(full, ref, "one-shot")
+    p = 0
+    for n in (37, 64, 1, 47, 1):
+        part = W.make_batch("part", 31, H, D, 16, 12, [n], [p + n], block_ids=ids)
+        part.q = one.q[p:p + n].copy()
+        got, _, _ = gpu_run(ctx_for(mpa, part), part, append=False)
+        assert_close(got, ref[p:p + n], f"chunk at {p}+{n}")
+        # against the one-shot GPU result: same math up to re-association
+        d = np.abs(W.bf16_to_f64(got) - W.bf16_to_f64(full[p:p + n])).max()
+        assert d <= 2e-2
+        p += n
+    assert p == L
+
+
+def test_I4_batch_order_independence(mpa):
+    b = W.config1()
+    base, _, _ = gpu_run(ctx_for(mpa, b), b, append=False)
+    sub = b.compact([6, 1, 3])
+    import torch
+    kc, vc = sub.compact_cache(b)
+    c = ctx_for(mpa, sub)
+    out = torch.zeros((sub.T, sub.H, sub.D), dtype=torch.int16, device="cuda")
+    ws = torch.empty(c.workspace_bytes_for_batch(sub.chunk_starts, sub.context_lens), dtype=torch.uint8, device="cuda")
+    c.mixed_paged_attention(to_dev(sub.q), to_dev(kc), to_dev(vc), to_dev(sub.block_table), sub.chunk_starts,
+                            sub.context_lens, out, ws, scale=sub.scale)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host_u16(out), base[sub.rows_src])
