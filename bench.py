@@ -1,0 +1,246 @@
+#!/usr/bin/env python3
+"""Benchmark of the mixed-batch paged-attention hot path on one MI355X.
+
+A step = one pass of the whole hot path over one synthetic batch: kv_append of the iteration's
+new K/V followed by mixed_paged_attention (work-list planning and upload included), with all
+tensors already resident in HBM.  Default workload: the OPT-13B-shaped mixed batch (one
+512-token prompt chunk + 48 generation rows, 40 heads x 128, block size 16).
+
+Prints ONE JSON line (see README/DESIGN for the fields).  `roofline` describes the attention
+kernel of the mixed step (HBM bound: the generation rows dominate); `roofline_tg` and
+`roofline_pp` are the same kernel timed on the generation-only and prompt-only parts of the
+batch, against the HBM and bf16 matrix-core peaks respectively.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix, published
+
+
+def make_workload(name: str):
+    import workloads as W
+    if name == "cfg3":
+        return W.config3()
+    if name == "cfg2":
+        return W.config2()
+    if name == "cfg4":
+        return W.config4()
+    if name == "cfg1":
+        return W.config1()
+    if name.startswith("cfg5"):
+        it = int(name.split(":")[1]) if ":" in name else 47
+        return W.config5(it)
+    raise SystemExit(f"unknown workload {name}")
+
+
+class DeviceWorkload:
+    """Device-resident tensors of a batch; only referenced blocks of the pool are generated."""
+
+    def __init__(self, b, mpa, chunk_blocks: int = 512):
+        import torch
+        self.b = b
+        dev = "cuda"
+        shape = (b.NB, b.H, b.bs, b.D)
+        self.k_cache = torch.full(shape, 0x7FFF, dtype=torch.int16, device=dev)
+        self.v_cache = torch.full(shape, 0x7FFF, dtype=torch.int16, device=dev)
+        ids = b.referenced_blocks()
+        for s in range(0, len(ids), chunk_blocks):
+            part = ids[s : s + chunk_blocks]
+            idx = torch.from_numpy(part).to(dev)
+            for which, dst in (("k", self.k_cache), ("v", self.v_cache)):
+                blk = b.blocks_state(which, part, "prior")
+                dst.index_copy_(0, idx, torch.from_numpy(blk.view(np.int16)).to(dev))
+        kn, vn = b.new_kv()
+        self.k_new = torch.from_numpy(kn.view(np.int16)).to(dev)
+        self.v_new = torch.from_numpy(vn.view(np.int16)).to(dev)
+        self.slot_map = torch.from_numpy(b.slot_map).to(dev)
+        self.q = torch.from_numpy(b.q.view(np.int16)).to(dev)
+        self.block_table = torch.from_numpy(np.ascontiguousarray(b.block_table)).to(dev)
+        self.out = torch.zeros((b.T, b.H, b.D), dtype=torch.int16, device=dev)
+        self.ctx = mpa.Context(b.H, b.D)
+        self.ws = torch.empty(self.ctx.workspace_bytes_for_batch(b.chunk_starts, b.context_lens),
+                              dtype=torch.uint8, device=dev)
+
+    def step(self):
+        b = self.b
+        self.ctx.kv_append(self.k_new, self.v_new, self.slot_map, self.k_cache, self.v_cache)
+        self.ctx.mixed_paged_attention(self.q, self.k_cache, self.v_cache, self.block_table,
+                                       b.chunk_starts, b.context_lens, self.out, self.ws, scale=b.scale)
+
+    def attention_only(self, sub, q_rows, out, ws):
+        """Attention over a sub-batch (sequence subset) sharing this workload's cache."""
+        self.ctx.mixed_paged_attention(q_rows, self.k_cache, self.v_cache, sub["table"], sub["cs"],
+                                       sub["ctx"], out, ws, scale=self.b.scale)
+
+
+def algorithmic_bytes(b, seqs=None) -> int:
+    """HBM bytes the attention step must move: every K and V element of every sequence's context
+    once (4*D bytes per token per head, K and V in bf16), plus q in and out out."""
+    sel = np.arange(b.S) if seqs is None else np.asarray(seqs)
+    kv_tokens = int(b.context_lens[sel].sum())
+    rows = int(b.q_lens[sel].sum())
+    return kv_tokens * 4 * b.D * b.H + rows * b.H * b.D * 2 * 2
+
+
+def algorithmic_flops_pp(b, seqs) -> int:
+    """4*D flop per (query, key, head) pair under the causal mask (QK^T and PV)."""
+    ql, pr = b.q_lens[seqs], b.priors[seqs]
+    pairs = int((ql * pr + ql * (ql + 1) // 2).sum())
+    return 4 * b.D * b.H * pairs
+
+
+def time_kernel(dw, fn, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    dw.ctx.profile_enable(steps)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = dw.ctx.profile_read(steps)
+    dw.ctx.profile_enable(0)
+    return wall, ms
+
+
+def sub_batch(dw, seqs):
+    import torch
+    b = dw.b
+    seqs = np.asarray(seqs)
+    ql = b.q_lens[seqs]
+    cs = np.concatenate([[0], np.cumsum(ql)]).astype(np.int32)
+    rows = np.concatenate([np.arange(b.chunk_starts[i], b.chunk_starts[i + 1]) for i in seqs])
+    q = dw.q[torch.from_numpy(rows).cuda()].contiguous()
+    table = dw.block_table[torch.from_numpy(seqs).cuda()].contiguous()
+    ctx = b.context_lens[seqs].copy()
+    out = torch.zeros_like(q)
+    ws = torch.empty(dw.ctx.workspace_bytes_for_batch(cs, ctx), dtype=torch.uint8, device="cuda")
+    return {"cs": cs, "ctx": ctx, "table": table}, q, out, ws
+
+
+def cpu_baseline(b, budget_pair_heads: float = 6.0e7):
+    """The fp64 oracle, as it stands, on a bounded sample of the same batch: all generation rows
+    and every k-th prompt row (all heads), k chosen so the sample is ~budget (query,key,head)
+    triples.  Throughput is scaled to tokens/s of the full batch by triples visited."""
+    import oracle
+    ql, pr = b.q_lens, b.priors
+    rows, triples_full, triples_sample = [], 0, 0
+    tg = [i for i in range(b.S) if ql[i] == 1]
+    pp = [i for i in range(b.S) if ql[i] > 1]
+    tg_triples = int(b.context_lens[tg].sum()) * b.H if tg else 0
+    pp_triples = b.pp_pairs() * b.H
+    triples_full = tg_triples + pp_triples
+    stride = max(1, int(np.ceil(pp_triples / max(budget_pair_heads - tg_triples, budget_pair_heads * 0.25))))
+    for i in tg:
+        rows.append(int(b.chunk_starts[i]))
+    triples_sample += tg_triples
+    for i in pp:
+        js = np.arange(0, int(ql[i]), stride)
+        rows.extend((int(b.chunk_starts[i]) + js).tolist())
+        triples_sample += int((pr[i] + js + 1).sum()) * b.H
+    rows = np.asarray(rows, dtype=np.int32)
+    # compact pool holding the blocks of the whole batch after the append
+    sub = b.compact(range(b.S))
+    kc, vc = sub.compact_cache(b, "ctx")
+    rr = np.repeat(rows, b.H)
+    hh = np.tile(np.arange(b.H, dtype=np.int32), rows.size)
+    t0 = time.perf_counter()
+    oracle.attention_rows(sub.q, kc, vc, sub.block_table, sub.chunk_starts, sub.context_lens, b.scale, rr, hh)
+    dt = time.perf_counter() - t0
+    est_full = dt * triples_full / triples_sample
+    return {
+        "value": b.T / est_full, "unit": "tokens/s", "cores": oracle.threads(), "kind": "oracle",
+        "sample": (f"all {len(tg)} generation rows + every {stride}th prompt row, all heads: "
+                   f"{triples_sample:.3g} of {triples_full:.3g} (query,key,head) triples in {dt:.1f} s; "
+                   f"scaled by triples"),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-parts", action="store_true", help="skip the generation-only / prompt-only timings")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("this build runs on ONE GPU: the path has no cross-GPU part; run with --gpus 1")
+
+    import torch
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU")
+    import paper_2503_13737_amd as mpa
+    mpa.load()  # fails loudly when the HIP library is missing
+
+    b = make_workload(args.workload)
+    dw = DeviceWorkload(b, mpa)
+    torch.cuda.synchronize()
+
+    wall, attn_ms = time_kernel(dw, dw.step, args.steps, args.warmup)
+    ms_per_step = wall * 1e3 / args.steps
+    tokens_per_s = b.T * args.steps / wall
+    attn_avg_ms = float(attn_ms.mean())
+    bytes_alg = algorithmic_bytes(b)
+    achieved = bytes_alg / (attn_avg_ms * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"traffic_{args.workload.replace(':', '_')}.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+
+    result = {
+        "metric": "mixed-batch paged-attn tokens/s", "value": tokens_per_s, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{b.name}: H={b.H} D={b.D} bs={b.bs}, {int((b.q_lens > 1).sum())} prompt chunk(s) "
+                               f"{b.q_lens[b.q_lens > 1].tolist()} at prior {b.priors[b.q_lens > 1].tolist()}, "
+                               f"{int((b.q_lens == 1).sum())} generation rows, {b.tg_kv_tokens()} generation KV tokens",
+                   "rows": b.T, "seqs": b.S, "step": "kv_append + mixed_paged_attention (plan + upload included)"},
+        "roofline": {"kernel": "attention_kernel (mixed)", "bound": "hbm", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "algorithmic_bytes": bytes_alg, "kernel_ms": attn_avg_ms},
+    }
+
+    if not args.no_parts:
+        tg = [i for i in range(b.S) if b.q_lens[i] == 1]
+        pp = [i for i in range(b.S) if b.q_lens[i] > 1]
+        if tg:
+            sub, q, out, ws = sub_batch(dw, tg)
+            _, ms = time_kernel(dw, lambda: dw.attention_only(sub, q, out, ws), args.steps, args.warmup)
+            by = algorithmic_bytes(b, tg)
+            a = by / (float(ms.mean()) * 1e-3) / 1e9
+            result["roofline_tg"] = {"kernel": "attention_kernel (generation rows only)", "bound": "hbm",
+                                     "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": a / HBM_PEAK_GBS,
+                                     "algorithmic_bytes": by, "kernel_ms": float(ms.mean())}
+        if pp:
+            sub, q, out, ws = sub_batch(dw, pp)
+            _, ms = time_kernel(dw, lambda: dw.attention_only(sub, q, out, ws), args.steps, args.warmup)
+            fl = algorithmic_flops_pp(b, pp)
+            a = fl / (float(ms.mean()) * 1e-3) / 1e12
+            result["roofline_pp"] = {"kernel": "attention_kernel (prompt chunks only)", "bound": "mfma",
+                                     "achieved": a, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                     "frac": a / MFMA_BF16_PEAK_TFLOPS, "algorithmic_flops": fl,
+                                     "kernel_ms": float(ms.mean())}
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(b)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

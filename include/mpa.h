@@ -148,6 +148,18 @@ int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache,
                               void *stream);
 
 /*
+ * Kernel timing for benchmarks.  mpa_profile_enable(ctx, n) with n > 0 makes every following
+ * mpa_mixed_paged_attention call record a pair of HIP events on its stream directly around the
+ * launch of the main attention kernel (after the work-list copy, before the merge), for up to n
+ * calls; n == 0 switches it off and frees the events.  mpa_profile_read waits for the recorded
+ * events, writes the elapsed milliseconds of up to `cap` calls (oldest first) to `ms` (host),
+ * stores the count in *n_out and starts a new series.
+ * Errors: INVALID_ARG, HIP.
+ */
+int mpa_profile_enable(mpa_ctx *ctx, int32_t max_calls);
+int mpa_profile_read(mpa_ctx *ctx, float *ms, int32_t cap, int32_t *n_out);
+
+/*
  * Host-only view of the work decomposition of a batch (no HIP call; usable without a GPU).
  * Writes up to `cap` work items as 8 int32 each
  *   {seq, q_row0, q_rows, q_pos0, kv_begin, kv_end, part_row, kind}

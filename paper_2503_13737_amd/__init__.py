@@ -28,7 +28,7 @@ MPA_OPT_PP_ROWSTREAM = 3
 EXPORTS = [
     "mpa_create", "mpa_destroy", "mpa_set_option", "mpa_last_hip_error", "mpa_status_string",
     "mpa_workspace_bytes_for_batch", "mpa_workspace_bytes", "mpa_kv_append",
-    "mpa_mixed_paged_attention", "mpa_plan_describe",
+    "mpa_mixed_paged_attention", "mpa_plan_describe", "mpa_profile_enable", "mpa_profile_read",
 ]
 
 
@@ -73,6 +73,10 @@ def load() -> ctypes.CDLL:
         lib.mpa_mixed_paged_attention.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, i32, i32,
                                                   ctypes.c_float, vp, vp, sz, vp]
         lib.mpa_mixed_paged_attention.restype = ctypes.c_int
+        lib.mpa_profile_enable.argtypes = [vp, i32]
+        lib.mpa_profile_enable.restype = ctypes.c_int
+        lib.mpa_profile_read.argtypes = [vp, vp, i32, vp]
+        lib.mpa_profile_read.restype = ctypes.c_int
         lib.mpa_plan_describe.argtypes = [vp, vp, vp, i32, vp, i64, vp]
         lib.mpa_plan_describe.restype = i64
         _lib = lib
@@ -125,6 +129,20 @@ class Context:
 
     def last_hip_error(self) -> int:
         return load().mpa_last_hip_error(self._h)
+
+    def profile_enable(self, max_calls: int):
+        rc = load().mpa_profile_enable(self._h, int(max_calls))
+        if rc != MPA_OK:
+            raise MpaError(rc, "mpa_profile_enable")
+
+    def profile_read(self, cap: int = 4096) -> np.ndarray:
+        """Milliseconds the main attention kernel took in each profiled call."""
+        ms = np.zeros(cap, dtype=np.float32)
+        n = ctypes.c_int32(0)
+        rc = load().mpa_profile_read(self._h, _ptr(ms), cap, ctypes.byref(n))
+        if rc != MPA_OK:
+            raise MpaError(rc, "mpa_profile_read")
+        return ms[: n.value].copy()
 
     def workspace_bytes_for_batch(self, chunk_starts, context_lens) -> int:
         cs, cl = _host_i32(chunk_starts), _host_i32(context_lens)

@@ -5,6 +5,7 @@
 #include <cstring>
 #include <mutex>
 #include <new>
+#include <vector>
 
 #include "../../include/mpa.h"
 #include "mpa_internal.h"
@@ -29,6 +30,8 @@ struct mpa_ctx {
     Staging staging[kStagingSlots];
     int next_slot = 0;
     Plan plan;  // reused between calls to keep its vectors' capacity
+    std::vector<hipEvent_t> prof_events;  // start/stop pairs
+    int32_t prof_used = 0;                // pairs recorded in the current series
     std::mutex mu;
 };
 
@@ -78,7 +81,45 @@ int mpa_destroy(mpa_ctx *ctx)
         }
         if (s.host) (void)hipHostFree(s.host);
     }
+    for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
     delete ctx;
+    return MPA_OK;
+}
+
+int mpa_profile_enable(mpa_ctx *ctx, int32_t max_calls)
+{
+    if (!ctx || max_calls < 0) return MPA_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> g(ctx->mu);
+    for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
+    ctx->prof_events.clear();
+    ctx->prof_used = 0;
+    for (int32_t i = 0; i < 2 * max_calls; ++i) {
+        hipEvent_t e;
+        hipError_t rc = hipEventCreate(&e);
+        if (rc != hipSuccess) {
+            ctx->last_hip = (int)rc;
+            return MPA_ERR_HIP;
+        }
+        ctx->prof_events.push_back(e);
+    }
+    return MPA_OK;
+}
+
+int mpa_profile_read(mpa_ctx *ctx, float *ms, int32_t cap, int32_t *n_out)
+{
+    if (!ctx || cap < 0 || (cap > 0 && !ms) || !n_out) return MPA_ERR_INVALID_ARG;
+    std::lock_guard<std::mutex> g(ctx->mu);
+    int32_t n = ctx->prof_used < cap ? ctx->prof_used : cap;
+    for (int32_t i = 0; i < n; ++i) {
+        hipError_t rc = hipEventSynchronize(ctx->prof_events[2 * i + 1]);
+        if (rc == hipSuccess) rc = hipEventElapsedTime(&ms[i], ctx->prof_events[2 * i], ctx->prof_events[2 * i + 1]);
+        if (rc != hipSuccess) {
+            ctx->last_hip = (int)rc;
+            return MPA_ERR_HIP;
+        }
+    }
+    *n_out = n;
+    ctx->prof_used = 0;
     return MPA_OK;
 }
 
@@ -229,8 +270,14 @@ int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache, 
     p.merge = reinterpret_cast<const MergeRow *>(ws + plan.off_merge);
     p.n_merge = (int32_t)plan.merge.size();
 
+    const bool prof = (size_t)(2 * ctx->prof_used + 1) < ctx->prof_events.size();
+    if (prof && (e = hipEventRecord(ctx->prof_events[2 * ctx->prof_used], s)) != hipSuccess) return fail(e);
     int he = launch_attention(p, ctx->cfg.head_dim, stream);
     if (he != 0) return fail((hipError_t)he);
+    if (prof) {
+        if ((e = hipEventRecord(ctx->prof_events[2 * ctx->prof_used + 1], s)) != hipSuccess) return fail(e);
+        ++ctx->prof_used;
+    }
     he = launch_merge(p, ctx->cfg.head_dim, stream);
     if (he != 0) return fail((hipError_t)he);
     return MPA_OK;
