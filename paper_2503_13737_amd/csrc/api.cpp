@@ -66,7 +66,6 @@ int mpa_create(mpa_ctx **out, const mpa_config *cfg)
     c->cfg = *cfg;
     c->opt.heads = cfg->num_heads;
     c->opt.head_dim = cfg->head_dim;
-    c->opt.pp_rowstream = 1;  // until the matrix-core body is in place
     *out = c;
     return MPA_OK;
 }

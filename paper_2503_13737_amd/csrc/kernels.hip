@@ -242,12 +242,249 @@ __device__ __forceinline__ void row_body(const AttnParams &p, const WorkItem &it
     }
 }
 
+
+// ------------------------------------------------------------------------------------------
+// Matrix-core body: one work-group (4 wavefronts), one head, a tile of up to 128 query rows
+// (32 per wavefront), a contiguous key range walked in steps of 64 keys.
+//
+// Per step the work-group stages K [64 keys][D] and V transposed [D][64 keys] in LDS.  Each
+// wavefront computes S^T = K Q^T with 32x32x16 bf16 MFMAs (A = K rows from LDS, B = Q^T from
+// registers), so a lane owns ONE query row (lane % 32) and 32 of the 64 keys: the row maximum
+// and sum are in-lane reductions plus one exchange with lane ^ 32.  The exponentials, packed to
+// bf16 in the very registers they were produced in, are the B operand of O^T += V^T P^T, whose
+// result again has the query row on the lane, so the running rescale needs no cross-lane
+// traffic either.
+//
+// Register layouts of v_mfma_f32_32x32x16_bf16 (lane l, half = l / 32):
+//   A: row l % 32, k = 8*half .. 8*half+7        B: column l % 32, k = 8*half .. 8*half+7
+//   C: column l % 32, rows 8*(v/4) + 4*half + v%4 for v = 0..15
+// ------------------------------------------------------------------------------------------
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+template <int D>
+struct TileCfg {
+    static constexpr int KS = D / 16;                   // k-steps of K Q^T
+    static constexpr int DB = D / 32;                   // 32-row blocks of O^T
+    static constexpr int K_STRIDE = D * 2 + 16;         // bytes per key row of the K tile
+    static constexpr int VT_STRIDE = kKvTile * 2 + 8;   // bytes per row of the V^T tile
+    static constexpr int K_BYTES = kKvTile * K_STRIDE;
+    static constexpr int VT_BYTES = D * VT_STRIDE;
+    static constexpr int CPR = D / 8;                   // 16-byte chunks per key row
+    static constexpr int KG = 64 / CPR;                 // key groups per wavefront (V loads)
+    static constexpr int KPT = kBlockSize / KG;         // consecutive keys per thread (V loads)
+    static constexpr int NL = KPT;                      // 16-byte loads per thread per operand
+};
+
+template <int D>
+struct TileRegs {
+    u32x4 k[TileCfg<D>::NL];
+    u32x4 v[TileCfg<D>::NL];
+};
+
+// Wavefront `wave` fetches KV block (k0/16 + wave) of the step that starts at key k0.
+template <int D>
+__device__ __forceinline__ void tile_fetch(TileRegs<D> &r, const AttnParams &p, const int32_t *tab,
+                                           int32_t k0, int32_t kv_end, int head, int wave, int lane)
+{
+    using C = TileCfg<D>;
+    const int32_t kb0 = k0 + wave * kBlockSize;
+    if (kb0 < kv_end) {
+        const int32_t blk = __builtin_amdgcn_readfirstlane(tab[kb0 / kBlockSize]);
+        const size_t tile = ((size_t)blk * p.heads + head) * (kBlockSize * D);
+        const u32x4 *kp = reinterpret_cast<const u32x4 *>(p.k_cache + tile);
+        const u32x4 *vp = reinterpret_cast<const u32x4 *>(p.v_cache + tile);
+        const int c = lane % C::CPR, kg = lane / C::CPR;
+#pragma unroll
+        for (int i = 0; i < C::NL; ++i) r.k[i] = kp[i * 64 + lane];
+#pragma unroll
+        for (int i = 0; i < C::NL; ++i) {
+            const int key = C::KPT * kg + i;
+            u32x4 w = vp[key * C::CPR + c];
+            // keys at or past kv_end may hold anything (also NaN): they must contribute exact zeros
+            if (kb0 + key >= kv_end) w = u32x4{0u, 0u, 0u, 0u};
+            r.v[i] = w;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < C::NL; ++i) {
+            r.k[i] = u32x4{0u, 0u, 0u, 0u};
+            r.v[i] = u32x4{0u, 0u, 0u, 0u};
+        }
+    }
+}
+
+template <int D>
+__device__ __forceinline__ void tile_stage(const TileRegs<D> &r, char *lds_k, char *lds_vt, int wave, int lane)
+{
+    using C = TileCfg<D>;
+    const int c = lane % C::CPR, kg = lane / C::CPR;
+#pragma unroll
+    for (int i = 0; i < C::NL; ++i) {
+        const int j = i * 64 + lane;
+        const int key = wave * kBlockSize + j / C::CPR;
+        *reinterpret_cast<u32x4 *>(lds_k + key * C::K_STRIDE + (j % C::CPR) * 16) = r.k[i];
+    }
+    // transpose in registers: for each of this thread's 8 head-dim elements, the KPT keys
+    const int col = (wave * kBlockSize + C::KPT * kg) * 2;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        auto elem = [&](int i) -> uint32_t {
+            const uint32_t w = r.v[i][e >> 1];
+            return (e & 1) ? (w >> 16) : (w & 0xFFFFu);
+        };
+        char *dst = lds_vt + (8 * c + e) * C::VT_STRIDE + col;
+        if (C::KPT == 4) {
+            u32x2 o = {elem(0) | (elem(1) << 16), elem(2) | (elem(3) << 16)};
+            *reinterpret_cast<u32x2 *>(dst) = o;
+        } else {
+            *reinterpret_cast<uint32_t *>(dst) = elem(0) | (elem(1) << 16);
+        }
+    }
+}
+
+template <int D>
+__device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &it, int head, char *lds)
+{
+    using C = TileCfg<D>;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int half = lane >> 5;
+    const int col = lane & 31;
+    const int H = p.heads;
+    char *lds_k = lds;
+    char *lds_vt = lds + C::K_BYTES;
+
+    // this lane's query row
+    const int r_tile = wave * 32 + col;
+    const int r_eff = min(r_tile, it.q_rows - 1);
+    const int32_t pos = it.q_pos0 + r_eff;
+    bf16x8 qf[C::KS];
+    {
+        const uint16_t *qrow = p.q + ((size_t)(it.q_row0 + r_eff) * H + head) * D + half * 8;
+#pragma unroll
+        for (int ks = 0; ks < C::KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qrow + ks * 16);
+    }
+    const float c2 = p.scale_log2e;
+    float m = -INFINITY, l = 0.f;
+    f32x16 o[C::DB];
+#pragma unroll
+    for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
+
+    const int32_t *tab = p.block_table + (size_t)it.seq * p.table_stride;
+    const int32_t wave_first_pos = it.q_pos0 + min(wave * 32, it.q_rows - 1);
+    const int32_t wave_last_pos = it.q_pos0 + min(wave * 32 + 31, it.q_rows - 1);
+
+    TileRegs<D> regs;
+    tile_fetch<D>(regs, p, tab, it.kv_begin, it.kv_end, head, wave, lane);
+    for (int32_t k0 = it.kv_begin; k0 < it.kv_end; k0 += kKvTile) {
+        tile_stage<D>(regs, lds_k, lds_vt, wave, lane);
+        __syncthreads();
+        if (k0 + kKvTile < it.kv_end) tile_fetch<D>(regs, p, tab, k0 + kKvTile, it.kv_end, head, wave, lane);
+
+        if (k0 <= wave_last_pos) {  // otherwise every key of the step is above all rows of this wavefront
+            f32x16 s[2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < C::KS; ++ks)
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb) {
+                    const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(
+                        lds_k + (kb * 32 + col) * C::K_STRIDE + ks * 32 + half * 16);
+                    s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
+                }
+            const bool masked = k0 + kKvTile - 1 > wave_first_pos;
+            if (masked) {
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int32_t key = k0 + kb * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+                        if (key > pos) s[kb][v] = -INFINITY;
+                    }
+            }
+            float mt = s[0][0];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) mt = fmaxf(mt, s[kb][v]);
+            mt = fmaxf(mt, __shfl_xor(mt, 32));
+            const float m_new = fmaxf(m, mt);
+            const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = fast_exp2((m - m_safe) * c2);
+            const float mc = m_safe * c2;
+            m = m_new;
+            float psum = 0.f;
+            bf16x8 pf[2][2];
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float pv = fast_exp2(fmaf(s[kb][v], c2, -mc));
+                    psum += pv;
+                    pf[kb][v >> 3][v & 7] = static_cast<__bf16>(pv);
+                }
+            l = fmaf(l, alpha, psum);
+#pragma unroll
+            for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+#pragma unroll
+            for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int st = 0; st < 2; ++st) {
+                        const char *src = lds_vt + (db * 32 + col) * C::VT_STRIDE + (kb * 32 + st * 16 + half * 4) * 2;
+                        const u32x2 lo = *reinterpret_cast<const u32x2 *>(src);
+                        const u32x2 hi = *reinterpret_cast<const u32x2 *>(src + 16);
+                        const u32x4 both = {lo.x, lo.y, hi.x, hi.y};
+                        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both),
+                                                                        pf[kb][st], o[db], 0, 0, 0);
+                    }
+        }
+        __syncthreads();
+    }
+
+    const float l_tot = l + __shfl_xor(l, 32);
+    if (r_tile < it.q_rows) {
+        if (it.part_row < 0) {
+            const float inv = 1.f / l_tot;
+            uint16_t *orow = p.out + ((size_t)(it.q_row0 + r_tile) * H + head) * D;
+#pragma unroll
+            for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    u32x2 w = {pack_bf16(o[db][4 * g] * inv, o[db][4 * g + 1] * inv),
+                               pack_bf16(o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv)};
+                    *reinterpret_cast<u32x2 *>(orow + db * 32 + g * 8 + half * 4) = w;
+                }
+        } else {
+            const size_t prow = (size_t)(it.part_row + r_tile) * H + head;
+            float *arow = p.part_acc + prow * D;
+#pragma unroll
+            for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    *reinterpret_cast<float4 *>(arow + db * 32 + g * 8 + half * 4) =
+                        make_float4(o[db][4 * g], o[db][4 * g + 1], o[db][4 * g + 2], o[db][4 * g + 3]);
+            if (half == 0) *reinterpret_cast<float2 *>(p.part_ml + prow * 2) = make_float2(m * c2, l_tot);
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // Unified kernel: work-groups [0, n_tile_items*H) run prompt tiles, the rest run row items
 // (one wavefront per head, kWaves consecutive heads per work-group).
 // ------------------------------------------------------------------------------------------
 template <int D>
-__global__ void __launch_bounds__(kThreads)
+__global__ void __launch_bounds__(kThreads, 2)
 attention_kernel(const AttnParams p)
 {
     const int lane = threadIdx.x & 63;
@@ -255,7 +492,11 @@ attention_kernel(const AttnParams p)
     const int H = p.heads;
     const int64_t n_tile_wg = (int64_t)p.n_tile_items * H;
     if ((int64_t)blockIdx.x < n_tile_wg) {
-        // prompt tiles: matrix-core body (not reached while tiles are planned as row items)
+        __shared__ __attribute__((aligned(16))) char lds[TileCfg<D>::K_BYTES + TileCfg<D>::VT_BYTES];
+        const int32_t item = (int32_t)(blockIdx.x / H);
+        const int head = (int)(blockIdx.x % H);
+        const WorkItem it = p.items[item];
+        tile_body<D>(p, it, head, lds);
         return;
     }
     const int hg = (H + kWaves - 1) / kWaves;
