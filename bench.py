@@ -177,6 +177,9 @@ def main():
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parts", action="store_true", help="skip the generation-only / prompt-only timings")
+    ap.add_argument("--calibrate-append-tokens", type=int, default=0,
+                    help="also run kv_append on this many synthetic tokens (a plain copy kernel of known size, "
+                         "used to scale the HBM byte counters of a profiler run)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("this build runs on ONE GPU: the path has no cross-GPU part; run with --gpus 1")
@@ -236,6 +239,23 @@ def main():
                                      "achieved": a, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                      "frac": a / MFMA_BF16_PEAK_TFLOPS, "algorithmic_flops": fl,
                                      "kernel_ms": float(ms.mean())}
+
+    if args.calibrate_append_tokens > 0:
+        n = args.calibrate_append_tokens
+        assert n <= b.NB * b.bs
+        kn = torch.zeros((n, b.H, b.D), dtype=torch.int16, device="cuda")
+        vn = torch.ones((n, b.H, b.D), dtype=torch.int16, device="cuda")
+        slots = torch.arange(n, dtype=torch.int64, device="cuda")
+        kc = torch.empty((b.NB, b.H, b.bs, b.D), dtype=torch.int16, device="cuda")
+        vc = torch.empty_like(kc)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dw.ctx.kv_append(kn, vn, slots, kc, vc)
+        torch.cuda.synchronize()
+        result["calibration"] = {"kernel": "kv_append_kernel", "tokens": n,
+                                 "bytes_read": 2 * n * b.H * b.D * 2 + n * 8,
+                                 "bytes_written": 2 * n * b.H * b.D * 2}
+        del kn, vn, kc, vc
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(b)

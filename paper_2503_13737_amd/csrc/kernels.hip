@@ -262,19 +262,22 @@ __device__ __forceinline__ void row_body(const AttnParams &p, const WorkItem &it
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 template <int D>
 struct TileCfg {
     static constexpr int KS = D / 16;                   // k-steps of K Q^T
     static constexpr int DB = D / 32;                   // 32-row blocks of O^T
-    static constexpr int K_STRIDE = D * 2 + 16;         // bytes per key row of the K tile
-    static constexpr int VT_STRIDE = kKvTile * 2 + 8;   // bytes per row of the V^T tile
+    // Row strides in LDS.  K rows are read 16 bytes per lane by 32 consecutive rows: a stride of
+    // 4 (mod 32) dwords spreads them over all banks.  V rows are read by the transposing load, 16
+    // lanes touching 4 rows x 32 bytes: a stride of 8 (mod 32) dwords keeps those disjoint.
+    static constexpr int K_STRIDE = D * 2 + 16;
+    static constexpr int V_STRIDE = D * 2 + 32;
     static constexpr int K_BYTES = kKvTile * K_STRIDE;
-    static constexpr int VT_BYTES = D * VT_STRIDE;
+    static constexpr int V_BYTES = kKvTile * V_STRIDE;
     static constexpr int CPR = D / 8;                   // 16-byte chunks per key row
-    static constexpr int KG = 64 / CPR;                 // key groups per wavefront (V loads)
-    static constexpr int KPT = kBlockSize / KG;         // consecutive keys per thread (V loads)
-    static constexpr int NL = KPT;                      // 16-byte loads per thread per operand
+    static constexpr int NL = kBlockSize * CPR / 64;    // 16-byte loads per thread per operand
 };
 
 template <int D>
@@ -283,78 +286,132 @@ struct TileRegs {
     u32x4 v[TileCfg<D>::NL];
 };
 
-// Wavefront `wave` fetches KV block (k0/16 + wave) of the step that starts at key k0.
+// Wavefront `wave` fetches KV block `blk` (16 keys) of a step; nothing is waited for.  Load i of
+// lane l is 16-byte chunk i*64 + l of the contiguous (block, head) tile.
 template <int D>
-__device__ __forceinline__ void tile_fetch(TileRegs<D> &r, const AttnParams &p, const int32_t *tab,
-                                           int32_t k0, int32_t kv_end, int head, int wave, int lane)
+__device__ __forceinline__ void tile_fetch(TileRegs<D> &r, const AttnParams &p, int32_t blk, int head, int lane)
 {
     using C = TileCfg<D>;
-    const int32_t kb0 = k0 + wave * kBlockSize;
-    if (kb0 < kv_end) {
-        const int32_t blk = __builtin_amdgcn_readfirstlane(tab[kb0 / kBlockSize]);
-        const size_t tile = ((size_t)blk * p.heads + head) * (kBlockSize * D);
-        const u32x4 *kp = reinterpret_cast<const u32x4 *>(p.k_cache + tile);
-        const u32x4 *vp = reinterpret_cast<const u32x4 *>(p.v_cache + tile);
-        const int c = lane % C::CPR, kg = lane / C::CPR;
+    const size_t tile = ((size_t)blk * p.heads + head) * (kBlockSize * D);
+    const u32x4 *kp = reinterpret_cast<const u32x4 *>(p.k_cache + tile) + lane;
+    const u32x4 *vp = reinterpret_cast<const u32x4 *>(p.v_cache + tile) + lane;
 #pragma unroll
-        for (int i = 0; i < C::NL; ++i) r.k[i] = kp[i * 64 + lane];
+    for (int i = 0; i < C::NL; ++i) r.k[i] = kp[i * 64];
 #pragma unroll
-        for (int i = 0; i < C::NL; ++i) {
-            const int key = C::KPT * kg + i;
-            u32x4 w = vp[key * C::CPR + c];
-            // keys at or past kv_end may hold anything (also NaN): they must contribute exact zeros
-            if (kb0 + key >= kv_end) w = u32x4{0u, 0u, 0u, 0u};
-            r.v[i] = w;
-        }
-    } else {
-#pragma unroll
-        for (int i = 0; i < C::NL; ++i) {
-            r.k[i] = u32x4{0u, 0u, 0u, 0u};
-            r.v[i] = u32x4{0u, 0u, 0u, 0u};
-        }
-    }
+    for (int i = 0; i < C::NL; ++i) r.v[i] = vp[i * 64];
 }
 
+// Registers -> LDS, both operands row-major [key][D] (rows padded).  keys_valid counts the keys of
+// this step that lie inside the item's range: keys at or past the end may hold anything (also
+// NaN patterns); their scores are masked, but V must contribute exact zeros.
 template <int D>
-__device__ __forceinline__ void tile_stage(const TileRegs<D> &r, char *lds_k, char *lds_vt, int wave, int lane)
+__device__ __forceinline__ void tile_stage(TileRegs<D> &r, char *lds_k, char *lds_v, int wave, int lane,
+                                           int32_t keys_valid)
 {
     using C = TileCfg<D>;
-    const int c = lane % C::CPR, kg = lane / C::CPR;
 #pragma unroll
     for (int i = 0; i < C::NL; ++i) {
         const int j = i * 64 + lane;
         const int key = wave * kBlockSize + j / C::CPR;
-        *reinterpret_cast<u32x4 *>(lds_k + key * C::K_STRIDE + (j % C::CPR) * 16) = r.k[i];
+        const int chunk = j % C::CPR;
+        u32x4 v = r.v[i];
+        if (keys_valid < kKvTile && key >= keys_valid) v = u32x4{0u, 0u, 0u, 0u};
+        *reinterpret_cast<u32x4 *>(lds_k + key * C::K_STRIDE + chunk * 16) = r.k[i];
+        *reinterpret_cast<u32x4 *>(lds_v + key * C::V_STRIDE + chunk * 16) = v;
     }
-    // transpose in registers: for each of this thread's 8 head-dim elements, the KPT keys
-    const int col = (wave * kBlockSize + C::KPT * kg) * 2;
+}
+
+// One step of the matrix-core body for one wavefront: S^T = K Q^T over 64 keys, online softmax,
+// O^T += V^T P^T.  MASKED steps apply the causal limit `pos` of the lane's row.
+template <int D, bool MASKED>
+__device__ __forceinline__ void tile_compute(const char *lds_k, const char *lds_v,
+                                             const bf16x8 (&qf)[TileCfg<D>::KS], f32x16 (&o)[TileCfg<D>::DB],
+                                             float &m, float &l, float c2, int32_t k0, int32_t pos, int half,
+                                             int col)
+{
+    using C = TileCfg<D>;
+    f32x16 s[2];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        auto elem = [&](int i) -> uint32_t {
-            const uint32_t w = r.v[i][e >> 1];
-            return (e & 1) ? (w >> 16) : (w & 0xFFFFu);
-        };
-        char *dst = lds_vt + (8 * c + e) * C::VT_STRIDE + col;
-        if (C::KPT == 4) {
-            u32x2 o = {elem(0) | (elem(1) << 16), elem(2) | (elem(3) << 16)};
-            *reinterpret_cast<u32x2 *>(dst) = o;
-        } else {
-            *reinterpret_cast<uint32_t *>(dst) = elem(0) | (elem(1) << 16);
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
+    const char *krow = lds_k + col * C::K_STRIDE + half * 16;
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(krow + kb * 32 * C::K_STRIDE + ks * 32);
+            s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
         }
+    if (MASKED) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int32_t key = k0 + kb * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+                if (key > pos) s[kb][v] = -INFINITY;
+            }
     }
+    float mt = s[0][0];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) mt = fmaxf(mt, s[kb][v]);
+    mt = fmaxf(mt, __shfl_xor(mt, 32));
+    const float m_new = fmaxf(m, mt);
+    const float m_safe = (MASKED && m_new == -INFINITY) ? 0.f : m_new;
+    const float alpha = fast_exp2((m - m_safe) * c2);
+    const float mc = m_safe * c2;
+    m = m_new;
+    float psum = 0.f;
+    bf16x8 pf[2][2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const float pv = fast_exp2(fmaf(s[kb][v], c2, -mc));
+            psum += pv;
+            pf[kb][v >> 3][v & 7] = static_cast<__bf16>(pv);
+        }
+    l = fmaf(l, alpha, psum);
+#pragma unroll
+    for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+    // A operand of O^T += V^T P^T: lane (row d = 32*db + col, half) needs keys
+    // {base + 4*half + 0..3} and {base + 8 + 4*half + 0..3} of its d.  ds_read_b64_tr_b16 works on
+    // groups of 16 lanes: lane s of a group supplies the address of 4 consecutive d of ONE key and
+    // receives element (i % 4) of lanes (i / 4) + 4j, j = 0..3.  With lane s pointing at key
+    // kk + s/4, elements d0 + 4*(s%4) .. +3, lane i ends up with keys kk..kk+3 at d = d0 + i.
+    const int s16 = col & 15;
+    const int d0 = (col >> 4) * 16;
+    const char *vbase = lds_v + (half * 4 + (s16 >> 2)) * C::V_STRIDE + (d0 + 4 * (s16 & 3)) * 2;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+#pragma unroll
+            for (int db = 0; db < C::DB; ++db) {
+                const char *src = vbase + (kb * 32 + st * 16) * C::V_STRIDE + db * 64;
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(src));
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(src + 8 * C::V_STRIDE));
+                const u32x2 lo2 = __builtin_bit_cast(u32x2, lo), hi2 = __builtin_bit_cast(u32x2, hi);
+                const u32x4 both = {lo2.x, lo2.y, hi2.x, hi2.y};
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[kb][st],
+                                                                o[db], 0, 0, 0);
+            }
 }
 
 template <int D>
 __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &it, int head, char *lds)
 {
     using C = TileCfg<D>;
+    constexpr int BUF = C::K_BYTES + C::V_BYTES;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int half = lane >> 5;
     const int col = lane & 31;
     const int H = p.heads;
-    char *lds_k = lds;
-    char *lds_vt = lds + C::K_BYTES;
 
     // this lane's query row
     const int r_tile = wave * 32 + col;
@@ -378,76 +435,46 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
     const int32_t wave_first_pos = it.q_pos0 + min(wave * 32, it.q_rows - 1);
     const int32_t wave_last_pos = it.q_pos0 + min(wave * 32 + 31, it.q_rows - 1);
 
-    TileRegs<D> regs;
-    tile_fetch<D>(regs, p, tab, it.kv_begin, it.kv_end, head, wave, lane);
-    for (int32_t k0 = it.kv_begin; k0 < it.kv_end; k0 += kKvTile) {
-        tile_stage<D>(regs, lds_k, lds_vt, wave, lane);
-        __syncthreads();
-        if (k0 + kKvTile < it.kv_end) tile_fetch<D>(regs, p, tab, k0 + kKvTile, it.kv_end, head, wave, lane);
+    // Block-table entries of this wavefront's blocks for 64 steps at a time, one per lane.
+    const int32_t nsteps = (it.kv_end - it.kv_begin + kKvTile - 1) / kKvTile;
+    const int32_t nblk_item = (it.kv_end - it.kv_begin + kBlockSize - 1) / kBlockSize;
+    const int32_t *tab_w = tab + it.kv_begin / kBlockSize + wave;
+    auto load_entries = [&](int32_t step0) {
+        const int32_t b = (step0 + lane) * kWaves + wave;
+        return (b < nblk_item) ? tab_w[(step0 + lane) * kWaves] : -1;
+    };
+    int32_t entries = load_entries(0);
 
+    TileRegs<D> regs;
+#pragma unroll
+    for (int i = 0; i < C::NL; ++i) {
+        regs.k[i] = u32x4{0u, 0u, 0u, 0u};
+        regs.v[i] = u32x4{0u, 0u, 0u, 0u};
+    }
+    auto fetch = [&](int32_t step) {
+        if ((step & 63) == 0 && step > 0) entries = load_entries(step);
+        const int32_t blk = __builtin_amdgcn_readlane(entries, step & 63);
+        if (blk >= 0) tile_fetch<D>(regs, p, blk, head, lane);
+    };
+    // Pipeline: while step s is computed from LDS buffer s&1, the registers hold step s+1 (staged
+    // into the other buffer at the end of the step) and the loads of step s+2 are issued.
+    fetch(0);
+    tile_stage<D>(regs, lds, lds + C::K_BYTES, wave, lane, it.kv_end - it.kv_begin);
+    if (nsteps > 1) fetch(1);
+    __syncthreads();
+    for (int32_t step = 0; step < nsteps; ++step) {
+        const int32_t k0 = it.kv_begin + step * kKvTile;
+        const char *buf = lds + (step & 1) * BUF;
         if (k0 <= wave_last_pos) {  // otherwise every key of the step is above all rows of this wavefront
-            f32x16 s[2];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < C::KS; ++ks)
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb) {
-                    const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(
-                        lds_k + (kb * 32 + col) * C::K_STRIDE + ks * 32 + half * 16);
-                    s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
-                }
-            const bool masked = k0 + kKvTile - 1 > wave_first_pos;
-            if (masked) {
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int32_t key = k0 + kb * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
-                        if (key > pos) s[kb][v] = -INFINITY;
-                    }
-            }
-            float mt = s[0][0];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) mt = fmaxf(mt, s[kb][v]);
-            mt = fmaxf(mt, __shfl_xor(mt, 32));
-            const float m_new = fmaxf(m, mt);
-            const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = fast_exp2((m - m_safe) * c2);
-            const float mc = m_safe * c2;
-            m = m_new;
-            float psum = 0.f;
-            bf16x8 pf[2][2];
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const float pv = fast_exp2(fmaf(s[kb][v], c2, -mc));
-                    psum += pv;
-                    pf[kb][v >> 3][v & 7] = static_cast<__bf16>(pv);
-                }
-            l = fmaf(l, alpha, psum);
-#pragma unroll
-            for (int db = 0; db < C::DB; ++db)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
-#pragma unroll
-            for (int db = 0; db < C::DB; ++db)
-#pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                    for (int st = 0; st < 2; ++st) {
-                        const char *src = lds_vt + (db * 32 + col) * C::VT_STRIDE + (kb * 32 + st * 16 + half * 4) * 2;
-                        const u32x2 lo = *reinterpret_cast<const u32x2 *>(src);
-                        const u32x2 hi = *reinterpret_cast<const u32x2 *>(src + 16);
-                        const u32x4 both = {lo.x, lo.y, hi.x, hi.y};
-                        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both),
-                                                                        pf[kb][st], o[db], 0, 0, 0);
-                    }
+            if (k0 + kKvTile - 1 > wave_first_pos)
+                tile_compute<D, true>(buf, buf + C::K_BYTES, qf, o, m, l, c2, k0, pos, half, col);
+            else
+                tile_compute<D, false>(buf, buf + C::K_BYTES, qf, o, m, l, c2, k0, pos, half, col);
+        }
+        if (step + 1 < nsteps) {
+            char *nbuf = lds + ((step + 1) & 1) * BUF;
+            tile_stage<D>(regs, nbuf, nbuf + C::K_BYTES, wave, lane, it.kv_end - (k0 + kKvTile));
+            if (step + 2 < nsteps) fetch(step + 2);
         }
         __syncthreads();
     }
@@ -479,6 +506,21 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
     }
 }
 
+// The item is the same for every lane: keep its fields in scalar registers.
+__device__ __forceinline__ WorkItem load_item(const WorkItem *src)
+{
+    WorkItem it;
+    it.seq = __builtin_amdgcn_readfirstlane(src->seq);
+    it.q_row0 = __builtin_amdgcn_readfirstlane(src->q_row0);
+    it.q_rows = __builtin_amdgcn_readfirstlane(src->q_rows);
+    it.q_pos0 = __builtin_amdgcn_readfirstlane(src->q_pos0);
+    it.kv_begin = __builtin_amdgcn_readfirstlane(src->kv_begin);
+    it.kv_end = __builtin_amdgcn_readfirstlane(src->kv_end);
+    it.part_row = __builtin_amdgcn_readfirstlane(src->part_row);
+    it.kind = __builtin_amdgcn_readfirstlane(src->kind);
+    return it;
+}
+
 // ------------------------------------------------------------------------------------------
 // Unified kernel: work-groups [0, n_tile_items*H) run prompt tiles, the rest run row items
 // (one wavefront per head, kWaves consecutive heads per work-group).
@@ -492,10 +534,10 @@ attention_kernel(const AttnParams p)
     const int H = p.heads;
     const int64_t n_tile_wg = (int64_t)p.n_tile_items * H;
     if ((int64_t)blockIdx.x < n_tile_wg) {
-        __shared__ __attribute__((aligned(16))) char lds[TileCfg<D>::K_BYTES + TileCfg<D>::VT_BYTES];
+        __shared__ __attribute__((aligned(16))) char lds[2 * (TileCfg<D>::K_BYTES + TileCfg<D>::V_BYTES)];
         const int32_t item = (int32_t)(blockIdx.x / H);
         const int head = (int)(blockIdx.x % H);
-        const WorkItem it = p.items[item];
+        const WorkItem it = load_item(p.items + item);
         tile_body<D>(p, it, head, lds);
         return;
     }
@@ -504,7 +546,7 @@ attention_kernel(const AttnParams p)
     const int32_t item = p.n_tile_items + (int32_t)(idx / hg);
     const int head = (int)(idx % hg) * kWaves + wave;
     if (head >= H) return;
-    const WorkItem it = p.items[item];
+    const WorkItem it = load_item(p.items + item);
     row_body<D>(p, it, head, lane);
 }
 
