@@ -358,26 +358,44 @@ __device__ __forceinline__ void tile_compute(const char *lds_k, const char *lds_
 #pragma unroll
         for (int v = 0; v < 16; ++v) mt = fmaxf(mt, s[kb][v]);
     mt = fmaxf(mt, __shfl_xor(mt, 32));
-    const float m_new = fmaxf(m, mt);
-    const float m_safe = (MASKED && m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = fast_exp2((m - m_safe) * c2);
-    const float mc = m_safe * c2;
-    m = m_new;
-    float psum = 0.f;
+    // The reference maximum m only has to be close to the true one: exponents up to kLazyLog2
+    // above it are harmless in fp32 and bf16.  So m is raised (and l, O rescaled) only when some
+    // row's step maximum exceeds it by more than that -- after the first steps, almost never.
+    constexpr float kLazyLog2 = 8.f;
+    const bool raise = mt * c2 > m * c2 + kLazyLog2;  // m == -inf on the first step: always true
+    if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+        const float m_new = fmaxf(m, mt);
+        const float m_fin = (MASKED && m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = fast_exp2((m - m_fin) * c2);
+        l *= alpha;
+#pragma unroll
+        for (int db = 0; db < C::DB; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+        m = m_new;
+    }
+    const float mc = (MASKED && m == -INFINITY) ? 0.f : m * c2;
     bf16x8 pf[2][2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const float pv = fast_exp2(fmaf(s[kb][v], c2, -mc));
-            psum += pv;
-            pf[kb][v >> 3][v & 7] = static_cast<__bf16>(pv);
-        }
-    l = fmaf(l, alpha, psum);
+        for (int v = 0; v < 16; ++v)
+            pf[kb][v >> 3][v & 7] = static_cast<__bf16>(fast_exp2(fmaf(s[kb][v], c2, -mc)));
+    // Row sum of the bf16-rounded weights (the very values the PV product uses, so numerator and
+    // denominator stay consistent), two per instruction.
+    {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
 #pragma unroll
-    for (int db = 0; db < C::DB; ++db)
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+            for (int st = 0; st < 2; ++st)
+#pragma unroll
+                for (int e = 0; e < 8; e += 2) {
+                    const bf16x2 pr = {pf[kb][st][e], pf[kb][st][e + 1]};
+                    l = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, l, false);
+                }
+    }
     // A operand of O^T += V^T P^T: lane (row d = 32*db + col, half) needs keys
     // {base + 4*half + 0..3} and {base + 8 + 4*half + 0..3} of its d.  ds_read_b64_tr_b16 works on
     // groups of 16 lanes: lane s of a group supplies the address of 4 consecutive d of ONE key and

@@ -1,0 +1,103 @@
+"""GPU parity at the full benchmark sizes (configs 2-5), in the launch configuration bench.py
+times: kv_append + mixed_paged_attention on the whole batch, compared with the oracle on sampled
+outputs it can compute one by one (all generation rows for three heads; prompt rows first, last,
+every 61st and those straddling 16- and 128-row boundaries), plus bit-exact kv_append on the
+blocks the new tokens land in."""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+import workloads as W
+from harness import MAX_ABS_TOL, REL_L2_TOL, errors, to_host_u16
+
+sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+
+pytestmark = pytest.mark.gpu
+
+
+def sample_rows(b):
+    rows, heads = [], []
+    hs = sorted({0, b.H // 2, b.H - 1})
+    for i in range(b.S):
+        r0, n = int(b.chunk_starts[i]), int(b.q_lens[i])
+        if n == 1:
+            js = [0]
+        else:
+            js = {0, n - 1} | set(range(0, n, 61))
+            for edge in list(range(16, n, 16))[:3] + list(range(128, n, 128)):
+                js |= {edge - 1, edge}
+            js = sorted(j for j in js if 0 <= j < n)
+        for j in js:
+            for h in hs:
+                rows.append(r0 + j)
+                heads.append(h)
+    return np.asarray(rows, dtype=np.int32), np.asarray(heads, dtype=np.int32)
+
+
+def check_config(b, max_pp_rows_per_head=None):
+    import torch
+    import bench
+    import oracle
+    import paper_2503_13737_amd as mpa
+    print(f"[{b.name}] T={b.T} S={b.S} blocks={b.referenced_blocks().size}", flush=True)
+    dw = bench.DeviceWorkload(b, mpa)
+    dw.out.fill_(0x7FFF)
+    dw.ws.fill_(0xFF)
+    dw.step()
+    torch.cuda.synchronize()
+    out = to_host_u16(dw.out)
+    assert not np.isnan(W.bf16_to_f64(out)).any(), "NaN (or unwritten rows) in the output"
+
+    # kv_append: the blocks holding the new tokens must equal the oracle's append, bit for bit
+    touched = np.unique(b.slot_map // b.bs)
+    kn, vn = b.new_kv()
+    for which, cache, new in (("k", dw.k_cache, kn), ("v", dw.v_cache, vn)):
+        exp = b.blocks_state(which, touched, "prior")
+        # oracle append into a pool holding only the touched blocks
+        remap = {int(x): i for i, x in enumerate(touched)}
+        sm = np.array([remap[int(s // b.bs)] * b.bs + int(s % b.bs) for s in b.slot_map], dtype=np.int64)
+        other = exp.copy()
+        if which == "k":
+            oracle.kv_append(new, new, sm, exp, other)
+        else:
+            oracle.kv_append(new, new, sm, other, exp)
+        got = to_host_u16(cache[torch.from_numpy(touched).cuda()])
+        assert np.array_equal(got, exp), f"{b.name}: kv_append({which}) differs"
+
+    rows, heads = sample_rows(b)
+    sub = b.compact(range(b.S))
+    kc, vc = sub.compact_cache(b, "ctx")
+    ref = oracle.attention_rows(sub.q, kc, vc, sub.block_table, sub.chunk_starts, sub.context_lens, b.scale, rows, heads)
+    got = out[rows, heads]
+    ma, rl = errors(got, ref)
+    print(f"[{b.name}] {rows.size} sampled (row, head) outputs: max-abs {ma:.3e} rel-L2 {rl:.3e}", flush=True)
+    assert ma <= MAX_ABS_TOL and rl <= REL_L2_TOL
+    # per-row worst case stays within the absolute bound too
+    per_row = np.abs(W.bf16_to_f64(got) - ref).max(axis=1)
+    assert per_row.max() <= MAX_ABS_TOL
+    del dw
+    torch.cuda.empty_cache()
+
+
+def test_config2_13b_generation_only():
+    check_config(W.config2())
+
+
+def test_config3_13b_mixed():
+    check_config(W.config3())
+
+
+@pytest.mark.parametrize("prior", [0, 2048, 4096])
+def test_config3_prior_extremes(prior):
+    check_config(W.config3(prior=prior))
+
+
+def test_config4_175b_slice():
+    check_config(W.config4())
+
+
+@pytest.mark.parametrize("iteration", [0, 24, 48])
+def test_config5_long_prompt(iteration):
+    check_config(W.config5(iteration))
