@@ -269,9 +269,10 @@ template <int D>
 struct TileCfg {
     static constexpr int KS = D / 16;                   // k-steps of K Q^T
     static constexpr int DB = D / 32;                   // 32-row blocks of O^T
-    // Row strides in LDS.  K rows are read 16 bytes per lane by 32 consecutive rows: a stride of
-    // 4 (mod 32) dwords spreads them over all banks.  V rows are read by the transposing load, 16
-    // lanes touching 4 rows x 32 bytes: a stride of 8 (mod 32) dwords keeps those disjoint.
+    // Row strides in LDS.  K rows are read 16 bytes per lane by consecutive rows: a stride of
+    // 4 (mod 64) dwords spreads 16 of them over all 64 banks.  V rows are read by the transposing
+    // load, each group of 16 lanes touching 4 rows x 32 bytes and the neighbouring group the next 32
+    // bytes: a stride of 16 (mod 64) dwords keeps all of those apart.
     static constexpr int K_STRIDE = D * 2 + 16;
     static constexpr int V_STRIDE = D * 2 + 32;
     static constexpr int K_BYTES = kKvTile * K_STRIDE;
@@ -314,10 +315,17 @@ __device__ __forceinline__ void tile_stage(TileRegs<D> &r, char *lds_k, char *ld
         const int j = i * 64 + lane;
         const int key = wave * kBlockSize + j / C::CPR;
         const int chunk = j % C::CPR;
-        u32x4 v = r.v[i];
-        if (keys_valid < kKvTile && key >= keys_valid) v = u32x4{0u, 0u, 0u, 0u};
         *reinterpret_cast<u32x4 *>(lds_k + key * C::K_STRIDE + chunk * 16) = r.k[i];
-        *reinterpret_cast<u32x4 *>(lds_v + key * C::V_STRIDE + chunk * 16) = v;
+        *reinterpret_cast<u32x4 *>(lds_v + key * C::V_STRIDE + chunk * 16) = r.v[i];
+    }
+    if (keys_valid < kKvTile) {  // only the last step of a range: uniform branch
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < C::NL; ++i) {
+            const int j = i * 64 + lane;
+            const int key = wave * kBlockSize + j / C::CPR;
+            if (key >= keys_valid) *reinterpret_cast<u32x4 *>(lds_v + key * C::V_STRIDE + (j % C::CPR) * 16) = zero;
+        }
     }
 }
 
@@ -357,7 +365,11 @@ __device__ __forceinline__ void tile_compute(const char *lds_k, const char *lds_
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) mt = fmaxf(mt, s[kb][v]);
-    mt = fmaxf(mt, __shfl_xor(mt, 32));
+    {   // lane l <-> lane l ^ 32 without going through LDS
+        const uint32_t mi = __float_as_uint(mt);
+        auto sw = __builtin_amdgcn_permlane32_swap(mi, mi, false, false);
+        mt = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+    }
     // The reference maximum m only has to be close to the true one: exponents up to kLazyLog2
     // above it are harmless in fp32 and bf16.  So m is raised (and l, O rescaled) only when some
     // row's step maximum exceeds it by more than that -- after the first steps, almost never.
