@@ -9,7 +9,9 @@
 // ranges when it is long.  Every item that is one of several over the same rows writes a
 // partial result, and the rows are listed for the merge pass.
 #include <algorithm>
+#include <functional>
 #include <numeric>
+#include <queue>
 
 #include "../../include/mpa.h"
 #include "mpa_internal.h"
@@ -24,8 +26,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // several items per wavefront slot so the tail of the launch stays short.
 constexpr int64_t kRowItemTarget = 256 * 8 * 6;
 constexpr int64_t kMinRowSplitBlocks = 8;
-constexpr int64_t kTileGroupTarget = 1024;
-constexpr int64_t kMinTileSplitSteps = 16;  // 1024 keys
+constexpr int64_t kMinTileSplitSteps = 8;   // 512 keys
 
 int64_t auto_row_split_blocks(const PlanOptions &opt, int64_t total_blocks)
 {
@@ -34,11 +35,60 @@ int64_t auto_row_split_blocks(const PlanOptions &opt, int64_t total_blocks)
     return std::max<int64_t>(s, kMinRowSplitBlocks);
 }
 
-int64_t auto_tile_split_tokens(const PlanOptions &opt, int64_t total_steps)
+// Key-range length for prompt tiles.  `tile_steps` holds, per tile, the number of 64-key steps
+// of its full key range.  Splitting a tile's range costs a partial-result round trip, so the
+// ranges are kept as long as the launch allows: candidates are tried from "no split" downwards,
+// each scored by a list-scheduling estimate of the launch (every piece exists once per head and
+// occupies one of the kTileSlots resident work-groups; generation rows keep the memory pipe busy
+// for `row_us` anyway), and the longest range within a few percent of the best score wins.
+constexpr int64_t kTileSlots = 512;      // 2 resident work-groups per compute unit
+constexpr double kStepUs = 1.4;          // one 64-key step of a 128-row tile, measured
+constexpr double kPieceOverheadSteps = 3.0;
+constexpr double kRowBytesPerUs = 6.0e6; // generation rows stream at about 6 TB/s
+
+double tile_makespan_us(const std::vector<int64_t> &tile_steps, int64_t heads, int64_t len_steps)
+{
+    std::vector<double> pieces;
+    for (int64_t st : tile_steps) {
+        int64_t n = ceil_div(st, len_steps);
+        int64_t each = ceil_div(st, n);
+        for (int64_t i = 0; i < n; ++i) pieces.push_back((double)std::min(each, st - i * each) + kPieceOverheadSteps);
+    }
+    std::sort(pieces.begin(), pieces.end(), std::greater<double>());
+    // longest first onto the least loaded of kTileSlots slots; every piece H times
+    std::priority_queue<double, std::vector<double>, std::greater<double>> slots;
+    for (int64_t i = 0; i < kTileSlots; ++i) slots.push(0.0);
+    double makespan = 0.0;
+    for (double pc : pieces)
+        for (int64_t h = 0; h < heads; ++h) {
+            double t = slots.top() + pc;
+            slots.pop();
+            slots.push(t);
+            makespan = std::max(makespan, t);
+        }
+    return makespan * kStepUs;
+}
+
+int64_t auto_tile_split_tokens(const PlanOptions &opt, const std::vector<int64_t> &tile_steps, double row_us)
 {
     if (opt.pp_split_tokens > 0) return ceil_div(opt.pp_split_tokens, kKvTile) * kKvTile;
-    int64_t s = ceil_div(total_steps * opt.heads, kTileGroupTarget);
-    return std::max<int64_t>(s, kMinTileSplitSteps) * kKvTile;
+    if (tile_steps.empty()) return kKvTile;
+    const int64_t longest = *std::max_element(tile_steps.begin(), tile_steps.end());
+    std::vector<int64_t> cands;
+    for (int64_t n = 1; n <= 64; ++n) {
+        int64_t len = std::max<int64_t>(ceil_div(longest, n), kMinTileSplitSteps);
+        if (cands.empty() || len < cands.back()) cands.push_back(len);
+        if (len == kMinTileSplitSteps) break;
+    }
+    std::vector<double> score(cands.size());
+    double best = 1e300;
+    for (size_t i = 0; i < cands.size(); ++i) {
+        score[i] = std::max(tile_makespan_us(tile_steps, opt.heads, cands[i]), row_us);
+        best = std::min(best, score[i]);
+    }
+    for (size_t i = 0; i < cands.size(); ++i)
+        if (score[i] <= best * 1.05) return cands[i] * kKvTile;
+    return cands.back() * kKvTile;
 }
 
 void finish_layout(const PlanOptions &opt, Plan *p)
@@ -68,7 +118,8 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
         return MPA_OK;
     }
     if (cs[0] != 0) return MPA_ERR_BAD_BATCH;
-    int64_t row_blocks = 0, tile_steps = 0;
+    int64_t row_blocks = 0;
+    std::vector<int64_t> tile_steps;
     for (int32_t i = 0; i < S; ++i) {
         int64_t q_len = (int64_t)cs[i + 1] - cs[i];
         if (q_len < 1 || ctx[i] < q_len) return MPA_ERR_BAD_BATCH;
@@ -78,12 +129,13 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
         } else {
             for (int64_t r0 = 0; r0 < q_len; r0 += kTileRows) {
                 int64_t rows = std::min<int64_t>(kTileRows, q_len - r0);
-                tile_steps += ceil_div(prior + r0 + rows, kKvTile);
+                tile_steps.push_back(ceil_div(prior + r0 + rows, kKvTile));
             }
         }
     }
     const int64_t row_split = auto_row_split_blocks(opt, row_blocks);
-    const int64_t tile_split = auto_tile_split_tokens(opt, tile_steps);
+    const double row_us = (double)row_blocks * kBlockSize * 4.0 * opt.head_dim * opt.heads / kRowBytesPerUs;
+    const int64_t tile_split = auto_tile_split_tokens(opt, tile_steps, row_us);
 
     std::vector<WorkItem> tiles, rows;
     auto emit = [&](std::vector<WorkItem> &dst, int32_t kind, int32_t seq, int32_t q_row0,
