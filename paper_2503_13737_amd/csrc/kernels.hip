@@ -196,14 +196,20 @@ __device__ __forceinline__ void row_body(const AttnParams &p, const WorkItem &it
             if (tok0 + kBlockSize <= limit) consume<D, false>(r, qf, m, l, acc, tok0, limit, sub);
             else consume<D, true>(r, qf, m, l, acc, tok0, limit, sub);
         };
-        KvRegs<D> r0, r1;
+        // three register sets rotate: two blocks (16 KiB) are in flight while one is consumed
+        KvRegs<D> r0, r1, r2;
         issue_loads<D>(r0, p.k_cache, p.v_cache, blk_of(0), H, head, lane);
-        for (int j = 0; j < n; j += 2) {
-            if (j + 1 < n) issue_loads<D>(r1, p.k_cache, p.v_cache, blk_of(j + 1), H, head, lane);
+        if (n > 1) issue_loads<D>(r1, p.k_cache, p.v_cache, blk_of(1), H, head, lane);
+        for (int j = 0; j < n; j += 3) {
+            if (j + 2 < n) issue_loads<D>(r2, p.k_cache, p.v_cache, blk_of(j + 2), H, head, lane);
             step(r0, j);
             if (j + 1 < n) {
-                if (j + 2 < n) issue_loads<D>(r0, p.k_cache, p.v_cache, blk_of(j + 2), H, head, lane);
+                if (j + 3 < n) issue_loads<D>(r0, p.k_cache, p.v_cache, blk_of(j + 3), H, head, lane);
                 step(r1, j + 1);
+            }
+            if (j + 2 < n) {
+                if (j + 4 < n) issue_loads<D>(r1, p.k_cache, p.v_cache, blk_of(j + 4), H, head, lane);
+                step(r2, j + 2);
             }
         }
     }
