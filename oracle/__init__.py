@@ -32,9 +32,9 @@ def _load():
         lib.mpa_oracle_threads.restype = i
         lib.mpa_oracle_kv_append.argtypes = [p, p, p, i, i, i, i, p, p]
         lib.mpa_oracle_kv_append.restype = None
-        lib.mpa_oracle_attention.argtypes = [p, p, p, p, i, p, p, i, i, i, i, d, p]
+        lib.mpa_oracle_attention.argtypes = [p, p, p, p, i, p, p, i, i, i, i, i, d, p]
         lib.mpa_oracle_attention.restype = i
-        lib.mpa_oracle_attention_rows.argtypes = [p, p, p, p, i, p, p, i, i, i, i, d, p, p, i, p]
+        lib.mpa_oracle_attention_rows.argtypes = [p, p, p, p, i, p, p, i, i, i, i, i, d, p, p, i, p]
         lib.mpa_oracle_attention_rows.restype = i
         _lib = lib
     return _lib
@@ -50,7 +50,7 @@ def _c(a, dt):
 
 
 def kv_append(k_new, v_new, slot_map, k_cache, v_cache):
-    """In place on k_cache/v_cache ([NB,H,bs,D] uint16, C-contiguous)."""
+    """In place on k_cache/v_cache ([NB,HK,bs,D] uint16, C-contiguous); k_new/v_new [T,HK,D]."""
     T, H, D = k_new.shape
     bs = k_cache.shape[2]
     assert k_cache.flags.c_contiguous and v_cache.flags.c_contiguous
@@ -74,7 +74,7 @@ def attention(q, k_cache, v_cache, block_table, chunk_starts, context_lens, scal
     rc = _load().mpa_oracle_attention(q.ctypes.data, k_cache.ctypes.data, v_cache.ctypes.data,
                                       block_table.ctypes.data, block_table.shape[1],
                                       chunk_starts.ctypes.data, context_lens.ctypes.data,
-                                      S, H, D, bs, float(scale), out.ctypes.data)
+                                      S, H, k_cache.shape[1], D, bs, float(scale), out.ctypes.data)
     if rc != 0:
         raise ValueError("malformed batch")
     return out
@@ -93,7 +93,7 @@ def attention_rows(q, k_cache, v_cache, block_table, chunk_starts, context_lens,
     rc = _load().mpa_oracle_attention_rows(q.ctypes.data, k_cache.ctypes.data, v_cache.ctypes.data,
                                            block_table.ctypes.data, block_table.shape[1],
                                            chunk_starts.ctypes.data, context_lens.ctypes.data,
-                                           S, H, D, bs, float(scale), rows.ctypes.data,
+                                           S, H, k_cache.shape[1], D, bs, float(scale), rows.ctypes.data,
                                            heads.ctypes.data, rows.size, out.ctypes.data)
     if rc != 0:
         raise ValueError("malformed batch or row list")

@@ -20,8 +20,12 @@
  *   - The append stores the K/V of the iteration's new tokens in the cache (Sec. 2.2 "KVC
  *     allocation": the KV values of all tokens of a step are stored in the KVC).
  *
+ *   - Query heads may share K/V heads (grouped-query attention, as in the Llama-3-70B model the
+ *     paper also serves, Sec. 6.1): with HK K/V heads, query head h reads K/V head h / (H/HK).
+ *     HK == H is ordinary multi-head attention.
+ *
  * Inputs are bf16 bit patterns widened exactly to double; outputs stay in double.
- * Layouts: q/k_new/v_new [T,H,D]; caches [NB,H,bs,D]; block_table [S,stride].
+ * Layouts: q [T,H,D]; k_new/v_new [T,HK,D]; caches [NB,HK,bs,D]; block_table [S,stride].
  *
  * Pins (tests/test_oracle_pins.py): dense brute force with an explicit masked score matrix,
  * closed forms (single key, zero query, constant V, dominant key), a library causal SDPA in
@@ -55,8 +59,8 @@ int mpa_oracle_threads(void)
 #endif
 }
 
-/* For every token t with slot_map[t] >= 0 and every head: copy the D-vector of K and of V to
- * cache[slot / bs][h][slot % bs][:].  Byte copy, hence exact. */
+/* For every token t with slot_map[t] >= 0 and every K/V head (H of them here): copy the D-vector
+ * of K and of V to cache[slot / bs][h][slot % bs][:].  Byte copy, hence exact. */
 void mpa_oracle_kv_append(const uint16_t *k_new, const uint16_t *v_new, const int64_t *slot_map,
                           int T, int H, int D, int bs, uint16_t *k_cache, uint16_t *v_cache)
 {
@@ -75,13 +79,14 @@ void mpa_oracle_kv_append(const uint16_t *k_new, const uint16_t *v_new, const in
 
 /* One output row: query row `row` of q (belonging to sequence i, absolute position p), head h. */
 static void one_row(const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache,
-                    const int32_t *table_i, int row, int p, int h, int H, int D, int bs,
+                    const int32_t *table_i, int row, int p, int h, int H, int HK, int D, int bs,
                     double scale, double *s, double *out_row)
 {
     const uint16_t *qv = q + ((size_t)row * H + h) * D;
+    const int hk = h / (H / HK); /* the K/V head this query head reads */
     double m = -INFINITY;
     for (int t = 0; t <= p; ++t) {
-        const uint16_t *kv = k_cache + (((size_t)table_i[t / bs] * H + h) * bs + t % bs) * D;
+        const uint16_t *kv = k_cache + (((size_t)table_i[t / bs] * HK + hk) * bs + t % bs) * D;
         double dot = 0.0;
         for (int d = 0; d < D; ++d) dot += widen(qv[d]) * widen(kv[d]);
         s[t] = scale * dot;
@@ -94,7 +99,7 @@ static void one_row(const uint16_t *q, const uint16_t *k_cache, const uint16_t *
     }
     for (int d = 0; d < D; ++d) out_row[d] = 0.0;
     for (int t = 0; t <= p; ++t) {
-        const uint16_t *vv = v_cache + (((size_t)table_i[t / bs] * H + h) * bs + t % bs) * D;
+        const uint16_t *vv = v_cache + (((size_t)table_i[t / bs] * HK + hk) * bs + t % bs) * D;
         for (int d = 0; d < D; ++d) out_row[d] += s[t] * widen(vv[d]);
     }
     for (int d = 0; d < D; ++d) out_row[d] /= Z;
@@ -103,10 +108,11 @@ static void one_row(const uint16_t *q, const uint16_t *k_cache, const uint16_t *
 /* All rows of the batch.  out is [T,H,D] double.  Returns 0, or -1 on a malformed batch. */
 int mpa_oracle_attention(const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache,
                          const int32_t *block_table, int stride, const int32_t *chunk_starts,
-                         const int32_t *context_lens, int S, int H, int D, int bs, double scale,
-                         double *out)
+                         const int32_t *context_lens, int S, int H, int HK, int D, int bs,
+                         double scale, double *out)
 {
     int max_ctx = 0;
+    if (HK < 1 || H % HK != 0) return -1;
     for (int i = 0; i < S; ++i) {
         int q_len = chunk_starts[i + 1] - chunk_starts[i];
         if (q_len < 1 || context_lens[i] < q_len) return -1;
@@ -127,8 +133,8 @@ int mpa_oracle_attention(const uint16_t *q, const uint16_t *k_cache, const uint1
                 int q_len = chunk_starts[i + 1] - chunk_starts[i];
                 int prior = context_lens[i] - q_len;
                 int p = prior + (row - chunk_starts[i]);
-                one_row(q, k_cache, v_cache, block_table + (size_t)i * stride, row, p, h, H, D, bs,
-                        scale, s, out + ((size_t)row * H + h) * D);
+                one_row(q, k_cache, v_cache, block_table + (size_t)i * stride, row, p, h, H, HK, D,
+                        bs, scale, s, out + ((size_t)row * H + h) * D);
             }
         free(s);
     }
@@ -139,10 +145,12 @@ int mpa_oracle_attention(const uint16_t *q, const uint16_t *k_cache, const uint1
 /* Selected (row, head) outputs only: out is [n, D] double. */
 int mpa_oracle_attention_rows(const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache,
                               const int32_t *block_table, int stride, const int32_t *chunk_starts,
-                              const int32_t *context_lens, int S, int H, int D, int bs, double scale,
-                              const int32_t *rows, const int32_t *heads, int n, double *out)
+                              const int32_t *context_lens, int S, int H, int HK, int D, int bs,
+                              double scale, const int32_t *rows, const int32_t *heads, int n,
+                              double *out)
 {
     int max_ctx = 0;
+    if (HK < 1 || H % HK != 0) return -1;
     for (int i = 0; i < S; ++i) {
         int q_len = chunk_starts[i + 1] - chunk_starts[i];
         if (q_len < 1 || context_lens[i] < q_len) return -1;
@@ -159,8 +167,8 @@ int mpa_oracle_attention_rows(const uint16_t *q, const uint16_t *k_cache, const 
             while (chunk_starts[i + 1] <= row) ++i;
             int q_len = chunk_starts[i + 1] - chunk_starts[i];
             int p = context_lens[i] - q_len + (row - chunk_starts[i]);
-            one_row(q, k_cache, v_cache, block_table + (size_t)i * stride, row, p, heads[x], H, D,
-                    bs, scale, s, out + (size_t)x * D);
+            one_row(q, k_cache, v_cache, block_table + (size_t)i * stride, row, p, heads[x], H, HK,
+                    D, bs, scale, s, out + (size_t)x * D);
         }
         free(s);
     }

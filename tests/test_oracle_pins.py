@@ -339,3 +339,41 @@ def test_pins_catch_planted_mistakes():
     assert np.abs(variant() - good[:, 0]).max() < 1e-12
     for kw in (dict(mask_strict=True), dict(no_scale=True), dict(no_max_shift_sign=True), dict(swap_kv=True)):
         assert np.abs(variant(**kw) - good[:, 0]).max() > 1e-3, kw
+
+
+# ---------------------------------------------------------------- grouped K/V heads
+def test_grouped_kv_heads_equal_repeated_heads():
+    """Query heads sharing K/V heads in groups == ordinary attention over caches in which each
+    K/V head is repeated for every query head of its group (bit-exact on the oracle), and both
+    agree with the dense brute force."""
+    H, HK, D = 8, 2, 64
+    b = W.random_ragged(4321, H=H, D=D, n_pp=2, n_tg=3, max_q=40, max_prior=50, max_ctx=60, Hkv=HK)
+    kc, vc = b.full_cache("ctx")
+    assert kc.shape[1] == HK
+    got = oracle.attention(b.q, kc, vc, b.block_table, b.chunk_starts, b.context_lens, b.scale)
+    kc_rep, vc_rep = np.repeat(kc, H // HK, axis=1), np.repeat(vc, H // HK, axis=1)
+    ref = oracle.attention(b.q, kc_rep, vc_rep, b.block_table, b.chunk_starts, b.context_lens, b.scale)
+    assert np.array_equal(got, ref)
+    # a wrong head map (h % HK instead of h / group) must differ
+    kc_bad, vc_bad = np.tile(kc, (1, H // HK, 1, 1)), np.tile(vc, (1, H // HK, 1, 1))
+    bad = oracle.attention(b.q, kc_bad, vc_bad, b.block_table, b.chunk_starts, b.context_lens, b.scale)
+    assert np.abs(bad - got).max() > 1e-3
+    for i in range(b.S):
+        L, n, prior = int(b.context_lens[i]), int(b.q_lens[i]), int(b.priors[i])
+        pos = np.arange(L)
+        k = kc_rep[b.block_table[i, pos // 16], :, pos % 16, :]
+        v = vc_rep[b.block_table[i, pos // 16], :, pos % 16, :]
+        r0 = b.chunk_starts[i]
+        dense = dense_causal(W.bf16_to_f64(b.q[r0:r0 + n]), W.bf16_to_f64(k), W.bf16_to_f64(v), b.scale, prior)
+        assert np.abs(got[r0:r0 + n] - dense).max() < 1e-12
+
+
+def test_grouped_kv_append_writes_kv_heads_only():
+    H, HK, D = 8, 2, 64
+    b = W.random_ragged(77, H=H, D=D, n_pp=1, n_tg=2, max_q=20, max_prior=20, max_ctx=30, Hkv=HK)
+    kc, vc = b.full_cache("prior")
+    kn, vn = b.new_kv()
+    assert kn.shape == (b.T, HK, D)
+    oracle.kv_append(kn, vn, b.slot_map, kc, vc)
+    k2, v2 = b.full_cache("ctx")
+    assert np.array_equal(kc, k2) and np.array_equal(vc, v2)

@@ -8,8 +8,10 @@ All randomness is counter based (value = f(seed, index), see gen.c), so any part
 tensor can be produced alone and both sides see bit-identical arrays.
 
 Layouts (bf16 stored as uint16 bit patterns):
-    q, k_new, v_new : [T, H, D]     T = total query rows of the batch (ragged concatenation)
-    k_cache, v_cache: [NB, H, bs, D]  one (block, head) tile is bs*D contiguous elements
+    q               : [T, H, D]     T = total query rows of the batch (ragged concatenation)
+    k_cache, v_cache: [NB, HK, bs, D] one (block, kv head) tile is bs*D contiguous elements; HK = H
+                      unless query heads share K/V heads in groups of H/HK consecutive heads
+    k_new, v_new    : [T, HK, D]
     block_table     : [S, MB] int32, -1 padded, logical block j of sequence i -> physical block
     chunk_starts    : [S+1] int32 row offsets of each sequence's rows in q/out
     context_lens    : [S] int32 KV length of each sequence *including* this iteration's rows
@@ -120,11 +122,16 @@ class Batch:
     slot_map: np.ndarray = field(default=None)
     q: np.ndarray = field(default=None)
     content_seed: int = field(default=None)  # seed of the cache content (defaults to `seed`)
+    Hkv: int = field(default=None)           # K/V heads (query heads share them in groups); None = H
 
     # ---- derived metadata -------------------------------------------------------------
     @property
     def S(self) -> int:
         return int(self.context_lens.size)
+
+    @property
+    def HK(self) -> int:
+        return self.H if self.Hkv is None else self.Hkv
 
     @property
     def T(self) -> int:
@@ -185,23 +192,23 @@ class Batch:
         return self
 
     def block_contents(self, which: str, ids: np.ndarray) -> np.ndarray:
-        """Generated content of physical blocks `ids`: [n, H, bs, D] bf16 bits, no poison."""
+        """Generated content of physical blocks `ids`: [n, HK, bs, D] bf16 bits, no poison."""
         seed = self.seed_k if which == "k" else self.seed_v
-        per = self.H * self.bs * self.D
+        per = self.HK * self.bs * self.D
         offs = np.asarray(ids, dtype=np.uint64) * np.uint64(per)
-        return normal_bf16_segments(offs, per, seed).reshape(len(ids), self.H, self.bs, self.D)
+        return normal_bf16_segments(offs, per, seed).reshape(len(ids), self.HK, self.bs, self.D)
 
     def new_kv(self):
-        """k_new, v_new [T,H,D]: the values the destination slots are defined to hold."""
+        """k_new, v_new [T,HK,D]: the values the destination slots are defined to hold."""
         blk = self.slot_map // self.bs
         off = self.slot_map % self.bs
         outs = []
         for which in ("k", "v"):
             seed = self.seed_k if which == "k" else self.seed_v
             # one segment of D values per (token, head)
-            base = (blk[:, None] * self.H + np.arange(self.H)[None, :]) * self.bs + off[:, None]
+            base = (blk[:, None] * self.HK + np.arange(self.HK)[None, :]) * self.bs + off[:, None]
             offs = (base.astype(np.uint64) * np.uint64(self.D)).reshape(-1)
-            outs.append(normal_bf16_segments(offs, self.D, seed).reshape(self.T, self.H, self.D))
+            outs.append(normal_bf16_segments(offs, self.D, seed).reshape(self.T, self.HK, self.D))
         return outs[0], outs[1]
 
     def poison_mask(self, ids: np.ndarray, limit: str) -> np.ndarray:
@@ -244,7 +251,7 @@ class Batch:
         cs = np.concatenate([[0], np.cumsum(ql)]).astype(np.int32)
         rows = np.concatenate([np.arange(self.chunk_starts[i], self.chunk_starts[i + 1]) for i in seq_ids])
         b = Batch(self.name + "/compact", self.seed, self.H, self.D, self.bs, max(1, len(old)), cs,
-                  self.context_lens[seq_ids].copy(), newtab, content_seed=self.content_seed)
+                  self.context_lens[seq_ids].copy(), newtab, content_seed=self.content_seed, Hkv=self.Hkv)
         b.compact_src = old
         b.rows_src = rows
         b.q = self.q[rows]
@@ -261,7 +268,7 @@ class Batch:
                 parent.blocks_state("v", self.compact_src, limit))
 
 
-def make_batch(name, seed, H, D, bs, NB, q_lens, context_lens, block_ids=None) -> Batch:
+def make_batch(name, seed, H, D, bs, NB, q_lens, context_lens, block_ids=None, Hkv=None) -> Batch:
     """Build a batch from per-sequence (q_len, context_len); block ids are drawn without
     replacement from the pool unless given."""
     q_lens = np.asarray(q_lens, dtype=np.int64)
@@ -279,7 +286,7 @@ def make_batch(name, seed, H, D, bs, NB, q_lens, context_lens, block_ids=None) -
         tab[i, : nb[i]] = block_ids[p : p + nb[i]]
         p += int(nb[i])
     cs = np.concatenate([[0], np.cumsum(q_lens)]).astype(np.int32)
-    return Batch(name, seed, H, D, bs, NB, cs, ctx.astype(np.int32), tab)._finish()
+    return Batch(name, seed, H, D, bs, NB, cs, ctx.astype(np.int32), tab, Hkv=Hkv)._finish()
 
 
 def config_seed(index: int) -> int:
@@ -363,7 +370,8 @@ def config5(iteration: int) -> Batch:
 
 
 def random_ragged(seed: int, H: int = 2, D: int = 64, bs: int = 16, n_pp: int = 2, n_tg: int = 3,
-                  max_q: int = 70, max_prior: int = 90, max_ctx: int = 120, NB: int | None = None) -> Batch:
+                  max_q: int = 70, max_prior: int = 90, max_ctx: int = 120, NB: int | None = None,
+                  Hkv: int | None = None) -> Batch:
     """Small random mixed batch for property-style tests (sizes are arbitrary integers)."""
     ql_pp = uniform_ints(n_pp, 2, max_q, seed * 8 + 1) if n_pp else np.zeros(0, dtype=np.int64)
     pr_pp = uniform_ints(n_pp, 0, max_prior, seed * 8 + 2) if n_pp else np.zeros(0, dtype=np.int64)
@@ -373,7 +381,7 @@ def random_ragged(seed: int, H: int = 2, D: int = 64, bs: int = 16, n_pp: int = 
     order = permutation(len(ql), seed * 8 + 4)
     ql, ctx = ql[order], ctx[order]
     need = int(((ctx + bs - 1) // bs).sum())
-    return make_batch(f"ragged-{seed}", seed, H, D, bs, NB or (need + 5), ql, ctx)
+    return make_batch(f"ragged-{seed}", seed, H, D, bs, NB or (need + 5), ql, ctx, Hkv=Hkv)
 
 
 def f32_to_bf16(a) -> np.ndarray:
