@@ -38,6 +38,8 @@ def make_workload(name: str):
         return W.config4()
     if name == "cfg1":
         return W.config1()
+    if name == "gqa":
+        return W.config_gqa()
     if name.startswith("cfg5"):
         it = int(name.split(":")[1]) if ":" in name else 47
         return W.config5(it)
@@ -51,7 +53,7 @@ class DeviceWorkload:
         import torch
         self.b = b
         dev = "cuda"
-        shape = (b.NB, b.H, b.bs, b.D)
+        shape = (b.NB, b.HK, b.bs, b.D)
         self.k_cache = torch.full(shape, 0x7FFF, dtype=torch.int16, device=dev)
         self.v_cache = torch.full(shape, 0x7FFF, dtype=torch.int16, device=dev)
         ids = b.referenced_blocks()
@@ -68,7 +70,7 @@ class DeviceWorkload:
         self.q = torch.from_numpy(b.q.view(np.int16)).to(dev)
         self.block_table = torch.from_numpy(np.ascontiguousarray(b.block_table)).to(dev)
         self.out = torch.zeros((b.T, b.H, b.D), dtype=torch.int16, device=dev)
-        self.ctx = mpa.Context(b.H, b.D)
+        self.ctx = mpa.Context(b.H, b.D, num_kv_heads=b.HK)
         self.ws = torch.empty(self.ctx.workspace_bytes_for_batch(b.chunk_starts, b.context_lens),
                               dtype=torch.uint8, device=dev)
 
@@ -86,11 +88,11 @@ class DeviceWorkload:
 
 def algorithmic_bytes(b, seqs=None) -> int:
     """HBM bytes the attention step must move: every K and V element of every sequence's context
-    once (4*D bytes per token per head, K and V in bf16), plus q in and out out."""
+    once (4*D bytes per token per K/V head, K and V in bf16), plus q in and out out."""
     sel = np.arange(b.S) if seqs is None else np.asarray(seqs)
     kv_tokens = int(b.context_lens[sel].sum())
     rows = int(b.q_lens[sel].sum())
-    return kv_tokens * 4 * b.D * b.H + rows * b.H * b.D * 2 * 2
+    return kv_tokens * 4 * b.D * b.HK + rows * b.H * b.D * 2 * 2
 
 
 def algorithmic_flops_pp(b, seqs) -> int:

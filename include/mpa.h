@@ -25,8 +25,9 @@
  *   - Element type is bf16 (stored as 16-bit patterns); accumulation is fp32.
  *
  * Tensor layouts (row-major, innermost last)
- *   q, out, k_new, v_new : [T, H, D]        T = number of query rows in the batch
- *   k_cache, v_cache     : [NB, H, bs, D]   NB blocks of bs tokens; one (block, head) tile is
+ *   q, out               : [T, H, D]        T = number of query rows in the batch
+ *   k_new, v_new         : [T, HK, D]       HK = num_kv_heads
+ *   k_cache, v_cache     : [NB, HK, bs, D]  NB blocks of bs tokens; one (block, kv head) tile is
  *                                           bs*D contiguous elements
  *   block_table          : [S, stride] int32, entry j of row i = physical block of tokens
  *                          j*bs .. j*bs+bs-1 of sequence i; entries past ceil(ctx_i/bs) are
@@ -57,7 +58,8 @@ enum { MPA_BF16 = 1 };
 
 typedef struct {
     int32_t num_heads;    /* H, query heads                                                   */
-    int32_t num_kv_heads; /* must equal num_heads (grouped KV heads are not built)            */
+    int32_t num_kv_heads; /* HK, K/V heads; divides H.  Query head h reads K/V head h / (H/HK)
+                             (grouped-query attention); HK == H is multi-head attention       */
     int32_t head_dim;     /* D: 64 or 128                                                     */
     int32_t block_size;   /* bs: 16                                                           */
     int32_t dtype;        /* MPA_BF16                                                         */
@@ -98,13 +100,13 @@ size_t mpa_workspace_bytes(const mpa_ctx *ctx, int32_t max_seqs, int32_t max_tok
 
 /*
  * KV-cache append (Sec. 2.2 "KVC allocation": the K/V of all tokens of a step are stored in the
- * cache).  For every token t in [0, num_tokens) with slot_map[t] >= 0 and every head h, copies
+ * cache).  For every token t in [0, num_tokens) with slot_map[t] >= 0 and every K/V head h, copies
  * k_new[t,h,:] to k_cache[slot/bs, h, slot%bs, :] and the same for V; bit-exact.
  *
- *   k_new, v_new : device, [num_tokens, H, D], 16-byte aligned, read only
+ *   k_new, v_new : device, [num_tokens, HK, D], 16-byte aligned, read only
  *   slot_map     : device, [num_tokens] int64; negative = skip the token.  Non-negative
  *                  entries must be pairwise distinct and below NB*bs (not checked).
- *   k_cache, v_cache : device, [NB, H, bs, D], 16-byte aligned, written in place
+ *   k_cache, v_cache : device, [NB, HK, bs, D], 16-byte aligned, written in place
  *   num_tokens == 0 is a no-op.
  * Errors: INVALID_ARG, HIP.
  */
@@ -119,7 +121,8 @@ int mpa_kv_append(mpa_ctx *ctx, const void *k_new, const void *v_new, const int6
  * this iteration's tokens, which the caller has appended before (same stream => ordered).  Row
  * j of sequence i sits at absolute position p = context_lens[i] - q_len_i + j and gets
  *     out = sum_{t<=p} softmax_t(scale * q . k_t) v_t
- * with k_t, v_t read through block_table[i].  q_len_i == 1 is a generation task, q_len_i > 1 a
+ * with k_t, v_t of the head's K/V head read through block_table[i] (the paper also serves
+ * Llama-3-70B, Sec. 6.1, whose query heads share K/V heads).  q_len_i == 1 is a generation task, q_len_i > 1 a
  * prompt chunk; both kinds run in one kernel launch.
  *
  *   q            : device, [num_tokens, H, D] bf16, 16-byte aligned

@@ -58,13 +58,15 @@ int mpa_create(mpa_ctx **out, const mpa_config *cfg)
     *out = nullptr;
     if (cfg->num_heads <= 0) return MPA_ERR_INVALID_ARG;
     if (cfg->dtype != MPA_BF16) return MPA_ERR_UNSUPPORTED;
-    if (cfg->num_kv_heads != cfg->num_heads) return MPA_ERR_UNSUPPORTED;
+    if (cfg->num_kv_heads <= 0) return MPA_ERR_INVALID_ARG;
+    if (cfg->num_kv_heads > cfg->num_heads || cfg->num_heads % cfg->num_kv_heads != 0) return MPA_ERR_UNSUPPORTED;
     if (cfg->head_dim != 64 && cfg->head_dim != 128) return MPA_ERR_UNSUPPORTED;
     if (cfg->block_size != kBlockSize) return MPA_ERR_UNSUPPORTED;
     mpa_ctx *c = new (std::nothrow) mpa_ctx();
     if (!c) return MPA_ERR_INVALID_ARG;
     c->cfg = *cfg;
     c->opt.heads = cfg->num_heads;
+    c->opt.kv_heads = cfg->num_kv_heads;
     c->opt.head_dim = cfg->head_dim;
     *out = c;
     return MPA_OK;
@@ -181,7 +183,7 @@ int mpa_kv_append(mpa_ctx *ctx, const void *k_new, const void *v_new, const int6
     if (!aligned(k_new, 16) || !aligned(v_new, 16) || !aligned(k_cache, 16) || !aligned(v_cache, 16) ||
         !aligned(slot_map, 8))
         return MPA_ERR_INVALID_ARG;
-    int e = launch_kv_append(k_new, v_new, slot_map, num_tokens, ctx->cfg.num_heads, ctx->cfg.head_dim,
+    int e = launch_kv_append(k_new, v_new, slot_map, num_tokens, ctx->cfg.num_kv_heads, ctx->cfg.head_dim,
                              k_cache, v_cache, stream);
     if (e != 0) {
         ctx->last_hip = e;
@@ -258,6 +260,8 @@ int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache, 
     p.block_table = block_table;
     p.table_stride = block_table_stride;
     p.heads = ctx->cfg.num_heads;
+    p.kv_heads = ctx->cfg.num_kv_heads;
+    p.group = ctx->cfg.num_heads / ctx->cfg.num_kv_heads;
     const float sc = scale > 0.f ? scale : 1.0f / std::sqrt((float)ctx->cfg.head_dim);
     p.scale_log2e = sc * 1.4426950408889634f;
     p.out = static_cast<uint16_t *>(out);

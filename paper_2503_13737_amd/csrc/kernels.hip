@@ -96,9 +96,9 @@ struct KvRegs {
 template <int D>
 __device__ __forceinline__ void issue_loads(KvRegs<D> &r, const uint16_t *__restrict__ k_cache,
                                             const uint16_t *__restrict__ v_cache, int32_t blk,
-                                            int32_t H, int32_t head, int lane)
+                                            int32_t HK, int32_t kv_head, int lane)
 {
-    const size_t tile = ((size_t)blk * H + head) * (kBlockSize * D);
+    const size_t tile = ((size_t)blk * HK + kv_head) * (kBlockSize * D);
     const u32x4 *kp = reinterpret_cast<const u32x4 *>(k_cache + tile) + lane;
     const u32x4 *vp = reinterpret_cast<const u32x4 *>(v_cache + tile) + lane;
 #pragma unroll
@@ -166,6 +166,8 @@ __device__ __forceinline__ void row_body(const AttnParams &p, const WorkItem &it
 {
     using C = RowCfg<D>;
     const int H = p.heads;
+    const int HK = p.kv_heads;
+    const int kv_head = head / p.group;
     const int c = lane % C::LPR;
     const int sub = lane / C::LPR;
 
@@ -198,17 +200,17 @@ __device__ __forceinline__ void row_body(const AttnParams &p, const WorkItem &it
         };
         // three register sets rotate: two blocks (16 KiB) are in flight while one is consumed
         KvRegs<D> r0, r1, r2;
-        issue_loads<D>(r0, p.k_cache, p.v_cache, blk_of(0), H, head, lane);
-        if (n > 1) issue_loads<D>(r1, p.k_cache, p.v_cache, blk_of(1), H, head, lane);
+        issue_loads<D>(r0, p.k_cache, p.v_cache, blk_of(0), HK, kv_head, lane);
+        if (n > 1) issue_loads<D>(r1, p.k_cache, p.v_cache, blk_of(1), HK, kv_head, lane);
         for (int j = 0; j < n; j += 3) {
-            if (j + 2 < n) issue_loads<D>(r2, p.k_cache, p.v_cache, blk_of(j + 2), H, head, lane);
+            if (j + 2 < n) issue_loads<D>(r2, p.k_cache, p.v_cache, blk_of(j + 2), HK, kv_head, lane);
             step(r0, j);
             if (j + 1 < n) {
-                if (j + 3 < n) issue_loads<D>(r0, p.k_cache, p.v_cache, blk_of(j + 3), H, head, lane);
+                if (j + 3 < n) issue_loads<D>(r0, p.k_cache, p.v_cache, blk_of(j + 3), HK, kv_head, lane);
                 step(r1, j + 1);
             }
             if (j + 2 < n) {
-                if (j + 4 < n) issue_loads<D>(r1, p.k_cache, p.v_cache, blk_of(j + 4), H, head, lane);
+                if (j + 4 < n) issue_loads<D>(r1, p.k_cache, p.v_cache, blk_of(j + 4), HK, kv_head, lane);
                 step(r2, j + 2);
             }
         }
@@ -299,7 +301,7 @@ template <int D>
 __device__ __forceinline__ void tile_fetch(TileRegs<D> &r, const AttnParams &p, int32_t blk, int head, int lane)
 {
     using C = TileCfg<D>;
-    const size_t tile = ((size_t)blk * p.heads + head) * (kBlockSize * D);
+    const size_t tile = ((size_t)blk * p.kv_heads + head / p.group) * (kBlockSize * D);
     const u32x4 *kp = reinterpret_cast<const u32x4 *>(p.k_cache + tile) + lane;
     const u32x4 *vp = reinterpret_cast<const u32x4 *>(p.v_cache + tile) + lane;
 #pragma unroll

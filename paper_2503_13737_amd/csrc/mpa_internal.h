@@ -39,6 +39,7 @@ static_assert(sizeof(MergeRow) == 16, "merge row layout");
 
 struct PlanOptions {
     int32_t heads = 0;
+    int32_t kv_heads = 0;
     int32_t head_dim = 0;
     int64_t tg_split_blocks = 0;  // 0 = automatic
     int64_t pp_split_tokens = 0;  // 0 = automatic
@@ -68,7 +69,9 @@ struct AttnParams {
     const uint16_t *v_cache;
     const int32_t *block_table;
     int32_t table_stride;
-    int32_t heads;
+    int32_t heads;      // query heads
+    int32_t kv_heads;   // K/V heads; query head h reads K/V head h / (heads / kv_heads)
+    int32_t group;      // heads / kv_heads
     float scale_log2e;  // scale * log2(e): scores are kept in base-2 exponent units
     uint16_t *out;
     const WorkItem *items;

@@ -134,7 +134,7 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
         }
     }
     const int64_t row_split = auto_row_split_blocks(opt, row_blocks);
-    const double row_us = (double)row_blocks * kBlockSize * 4.0 * opt.head_dim * opt.heads / kRowBytesPerUs;
+    const double row_us = (double)row_blocks * kBlockSize * 4.0 * opt.head_dim * opt.kv_heads / kRowBytesPerUs;
     const int64_t tile_split = auto_tile_split_tokens(opt, tile_steps, row_us);
 
     std::vector<WorkItem> tiles, rows;

@@ -98,6 +98,10 @@ def test_config4_175b_slice():
     check_config(W.config4())
 
 
+def test_grouped_kv_layer():
+    check_config(W.config_gqa())
+
+
 @pytest.mark.parametrize("iteration", [0, 24, 48])
 def test_config5_long_prompt(iteration):
     check_config(W.config5(iteration))

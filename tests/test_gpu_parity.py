@@ -16,7 +16,7 @@ def mpa():
 
 
 def ctx_for(mpa, b, **opts):
-    c = mpa.Context(b.H, b.D)
+    c = mpa.Context(b.H, b.D, num_kv_heads=b.HK)
     for k, v in opts.items():
         c.set_option(getattr(mpa, k), v)
     return c
@@ -81,6 +81,19 @@ def test_random_ragged_batches(mpa, seed, D, H):
     out, kc, vc = gpu_run(ctx_for(mpa, b), b)
     assert np.array_equal(kc, okc) and np.array_equal(vc, ovc)
     assert_close(out, ref, b.name)
+
+
+@pytest.mark.parametrize("seed", range(4))
+@pytest.mark.parametrize("D,H,HK", [(64, 8, 2), (128, 8, 1), (128, 12, 4), (128, 16, 2)])
+def test_grouped_kv_heads(mpa, seed, D, H, HK):
+    """Query heads sharing K/V heads (h reads K/V head h / (H/HK)): append and attention."""
+    b = W.random_ragged(3000 + seed, H=H, D=D, n_pp=2, n_tg=4, max_q=260, max_prior=400, max_ctx=700, Hkv=HK)
+    ref, okc, ovc = oracle_run(b)
+    for opts in ({}, {"MPA_OPT_PP_SPLIT_TOKENS": 128, "MPA_OPT_TG_SPLIT_BLOCKS": 3}):
+        out, kc, vc = gpu_run(ctx_for(mpa, b, **opts), b)
+        assert kc.shape[1] == HK
+        assert np.array_equal(kc, okc) and np.array_equal(vc, ovc)
+        assert_close(out, ref, f"{b.name} H={H} HK={HK} {opts}")
 
 
 @pytest.mark.parametrize("ql,ctx", [

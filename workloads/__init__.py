@@ -331,6 +331,20 @@ def config4() -> Batch:
     return make_batch("cfg4-175b-slice", s, 12, 128, 16, 32768, ql, ctx)
 
 
+def config_gqa() -> Batch:
+    """Grouped-query layer (not one of the benchmark's five configs): a 4-way tensor-parallel
+    share of a 64-query-head / 8-KV-head layer (the head layout of the Llama-3-70B model the paper
+    also serves): 16 query heads over 2 K/V heads, head_dim 128.  Same sequence mix as config 3:
+    one 512-row chunk at prior context uniform on [0, 4096], 48 generation rows with contexts
+    uniform on [512, 4096]."""
+    s = config_seed(6)
+    prior = int(uniform_ints(1, 0, 4096, s * 4 + 3)[0])
+    ctx_tg = uniform_ints(48, 512, 4096, s * 4 + 2)
+    ql = np.concatenate([[512], np.ones(48, dtype=np.int64)])
+    ctx = np.concatenate([[prior + 512], ctx_tg])
+    return make_batch("gqa-16q-2kv-mixed", s, 16, 128, 16, 32768, ql, ctx, Hkv=2)
+
+
 CFG5_PROMPT = 100_000
 CFG5_CHUNK = 2048
 CFG5_ITERS = (CFG5_PROMPT + CFG5_CHUNK - 1) // CFG5_CHUNK  # 49
