@@ -133,7 +133,7 @@ def sub_batch(dw, seqs):
     return {"cs": cs, "ctx": ctx, "table": table}, q, out, ws
 
 
-def cpu_baseline(b, budget_pair_heads: float = 6.0e7):
+def cpu_baseline(b, budget_pair_heads: float = 1.0e9):
     """The fp64 oracle, as it stands, on a bounded sample of the same batch: all generation rows
     and every k-th prompt row (all heads), k chosen so the sample is ~budget (query,key,head)
     triples.  Throughput is scaled to tokens/s of the full batch by triples visited."""

@@ -116,11 +116,15 @@ class Context:
         self.num_heads, self.head_dim, self.block_size = num_heads, head_dim, block_size
 
     def close(self):
-        if getattr(self, "_h", None):
-            load().mpa_destroy(self._h)
-            self._h = None
+        h, self._h = getattr(self, "_h", None), None
+        if h and _lib is not None:
+            _lib.mpa_destroy(h)
 
-    __del__ = close
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:  # interpreter shutdown: module globals may already be gone
+            pass
 
     def set_option(self, option: int, value: int):
         rc = load().mpa_set_option(self._h, option, value)

@@ -10,6 +10,7 @@
 // partial result, and the rows are listed for the merge pass.
 #include <algorithm>
 #include <functional>
+#include <map>
 #include <numeric>
 #include <queue>
 
@@ -188,7 +189,20 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
         return full;
     };
     auto longer = [&](const WorkItem &a, const WorkItem &b) { return cost(a) > cost(b); };
-    std::stable_sort(tiles.begin(), tiles.end(), longer);
+    // Tiles: all query tiles of one (sequence, key range) read the same K/V blocks.  They are kept
+    // adjacent (one launch position apart per head, hence on the same XCD and resident together)
+    // so that one tile's fetch serves the others from L2; groups go longest first.
+    {
+        std::map<std::pair<int32_t, int32_t>, int64_t> group_cost;
+        for (const WorkItem &w : tiles) group_cost[{w.seq, w.kv_begin}] += cost(w);
+        std::stable_sort(tiles.begin(), tiles.end(), [&](const WorkItem &a, const WorkItem &b) {
+            const std::pair<int32_t, int32_t> ka{a.seq, a.kv_begin}, kb{b.seq, b.kv_begin};
+            if (ka == kb) return a.q_row0 < b.q_row0;
+            const int64_t ca = group_cost[ka], cb = group_cost[kb];
+            if (ca != cb) return ca > cb;
+            return ka < kb;
+        });
+    }
     std::stable_sort(rows.begin(), rows.end(), longer);
     plan->n_tile_items = (int32_t)tiles.size();
     plan->n_row_items = (int32_t)rows.size();
