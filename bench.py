@@ -179,6 +179,9 @@ def main():
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-parts", action="store_true", help="skip the generation-only / prompt-only timings")
+    ap.add_argument("--only-part", choices=["tg", "pp"], default=None,
+                    help="profiling aid: time ONLY the generation rows (tg) or ONLY the prompt chunks (pp) of the "
+                         "workload, so that a profiler run sees one launch shape; prints that part's roofline")
     ap.add_argument("--calibrate-append-tokens", type=int, default=0,
                     help="also run kv_append on this many synthetic tokens (a plain copy kernel of known size, "
                          "used to scale the HBM byte counters of a profiler run)")
@@ -195,6 +198,26 @@ def main():
     b = make_workload(args.workload)
     dw = DeviceWorkload(b, mpa)
     torch.cuda.synchronize()
+
+    if args.only_part:
+        sel = [i for i in range(b.S) if (b.q_lens[i] == 1) == (args.only_part == "tg")]
+        if not sel:
+            raise SystemExit(f"workload has no {args.only_part} sequences")
+        sub, q, out, ws = sub_batch(dw, sel)
+        _, ms = time_kernel(dw, lambda: dw.attention_only(sub, q, out, ws), args.steps, args.warmup)
+        t = float(ms.mean()) * 1e-3
+        if args.only_part == "tg":
+            by = algorithmic_bytes(b, sel)
+            part = {"kernel": "attention_kernel (generation rows only)", "bound": "hbm", "achieved": by / t / 1e9,
+                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": by / t / 1e9 / HBM_PEAK_GBS,
+                    "algorithmic_bytes": by, "kernel_ms": t * 1e3}
+        else:
+            fl = algorithmic_flops_pp(b, sel)
+            part = {"kernel": "attention_kernel (prompt chunks only)", "bound": "mfma", "achieved": fl / t / 1e12,
+                    "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": fl / t / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+                    "algorithmic_flops": fl, "kernel_ms": t * 1e3}
+        print(json.dumps({"only_part": args.only_part, "workload": b.name, "steps": args.steps, "roofline": part}), flush=True)
+        return
 
     wall, attn_ms = time_kernel(dw, dw.step, args.steps, args.warmup)
     ms_per_step = wall * 1e3 / args.steps

@@ -503,16 +503,19 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
     for (int32_t step = 0; step < nsteps; ++step) {
         const int32_t k0 = it.kv_begin + step * kKvTile;
         const char *buf = lds + (step & 1) * BUF;
+        // First hand the next step's data (fetched one step ago) to the other LDS buffer and issue
+        // the fetch of the step after it, so that both overlap with this step's arithmetic.  The
+        // other buffer was last read in the previous step, which every wavefront has left.
+        if (step + 1 < nsteps) {
+            char *nbuf = lds + ((step + 1) & 1) * BUF;
+            tile_stage<D>(regs, nbuf, nbuf + C::K_BYTES, wave, lane, it.kv_end - (k0 + kKvTile));
+            if (step + 2 < nsteps) fetch(step + 2);
+        }
         if (k0 <= wave_last_pos) {  // otherwise every key of the step is above all rows of this wavefront
             if (k0 + kKvTile - 1 > wave_first_pos)
                 tile_compute<D, true>(buf, buf + C::K_BYTES, qf, o, m, l, c2, k0, pos, half, col);
             else
                 tile_compute<D, false>(buf, buf + C::K_BYTES, qf, o, m, l, c2, k0, pos, half, col);
-        }
-        if (step + 1 < nsteps) {
-            char *nbuf = lds + ((step + 1) & 1) * BUF;
-            tile_stage<D>(regs, nbuf, nbuf + C::K_BYTES, wave, lane, it.kv_end - (k0 + kKvTile));
-            if (step + 2 < nsteps) fetch(step + 2);
         }
         __syncthreads();
     }
