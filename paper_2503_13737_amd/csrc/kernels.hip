@@ -277,73 +277,151 @@ template <int D>
 struct TileCfg {
     static constexpr int KS = D / 16;                   // k-steps of K Q^T
     static constexpr int DB = D / 32;                   // 32-row blocks of O^T
-    // Row strides in LDS.  K rows are read 16 bytes per lane by consecutive rows: a stride of
-    // 4 (mod 64) dwords spreads 16 of them over all 64 banks.  V rows are read by the transposing
-    // load, each group of 16 lanes touching 4 rows x 32 bytes and the neighbouring group the next 32
-    // bytes: a stride of 16 (mod 64) dwords keeps all of those apart.
-    static constexpr int K_STRIDE = D * 2 + 16;
-    static constexpr int V_STRIDE = D * 2 + 32;
-    static constexpr int K_BYTES = kKvTile * K_STRIDE;
-    static constexpr int V_BYTES = kKvTile * V_STRIDE;
+    // K and V tiles sit in LDS row-major, [64 keys][D], rows unpadded (ROW bytes), because they are
+    // written by direct-to-LDS loads that place a wavefront's 64 x 16 bytes contiguously.  Bank
+    // conflicts are avoided by a swizzle instead: the 16-byte chunk c of row r is stored at chunk
+    // position c ^ swz(r), applied on the global-address side of the load.
+    //   K rows are read 16 bytes per lane, four consecutive lanes (= four consecutive rows, same c)
+    //   per LDS cycle: swz_k(r) = r mod CPR keeps them on different banks.
+    //   V rows are read by the transposing load, 16 lanes touching 4 rows x 32 bytes: swz_v(r) =
+    //   VSW * (r mod 4) spreads those rows (and the neighbouring lane group's 32 bytes) over all banks.
+    static constexpr int ROW = D * 2;
+    static constexpr int TILE_BYTES = kKvTile * ROW;
+    static constexpr int K_BYTES = TILE_BYTES;
+    static constexpr int V_BYTES = TILE_BYTES;
     static constexpr int CPR = D / 8;                   // 16-byte chunks per key row
-    static constexpr int NL = kBlockSize * CPR / 64;    // 16-byte loads per thread per operand
+    static constexpr int RPL = 64 / CPR;                // key rows covered by one wavefront-wide load
+    static constexpr int NL = kBlockSize / RPL;         // loads per wavefront per operand and block
+    static constexpr int VSW = CPR / 4;                 // 4 for D = 128, 2 for D = 64
 };
 
+// Wavefront `wave` brings KV block `blk` (keys wave*16 .. wave*16+15 of the 64-key tile) of both
+// operands from HBM straight into LDS (global_load_lds_dwordx4: lane l's 16 bytes land at
+// base + 16*l, no registers involved, nothing is waited for here).  Lane l of load i serves row
+// i*RPL + l/CPR of the block at chunk position l % CPR, so it fetches chunk (l % CPR) ^ swz(row).
+// keys_valid counts the keys of the tile that lie inside the item's range: rows at or past it are
+// not loaded; the V rows among them are zeroed instead (their scores are masked, but 0 * NaN
+// would poison the PV product), the K rows may hold anything.
 template <int D>
-struct TileRegs {
-    u32x4 k[TileCfg<D>::NL];
-    u32x4 v[TileCfg<D>::NL];
-};
-
-// Wavefront `wave` fetches KV block `blk` (16 keys) of a step; nothing is waited for.  Load i of
-// lane l is 16-byte chunk i*64 + l of the contiguous (block, head) tile.
-template <int D>
-__device__ __forceinline__ void tile_fetch(TileRegs<D> &r, const AttnParams &p, int32_t blk, int head, int lane)
+__device__ __forceinline__ void tile_load(const AttnParams &p, int32_t blk, int head, char *lds_k, char *lds_v,
+                                          int wave, int lane, int32_t keys_valid)
 {
     using C = TileCfg<D>;
-    const size_t tile = ((size_t)blk * p.kv_heads + head / p.group) * (kBlockSize * D);
-    const u32x4 *kp = reinterpret_cast<const u32x4 *>(p.k_cache + tile) + lane;
-    const u32x4 *vp = reinterpret_cast<const u32x4 *>(p.v_cache + tile) + lane;
-#pragma unroll
-    for (int i = 0; i < C::NL; ++i) r.k[i] = kp[i * 64];
-#pragma unroll
-    for (int i = 0; i < C::NL; ++i) r.v[i] = vp[i * 64];
-}
-
-// Registers -> LDS, both operands row-major [key][D] (rows padded).  keys_valid counts the keys of
-// this step that lie inside the item's range: keys at or past the end may hold anything (also
-// NaN patterns); their scores are masked, but V must contribute exact zeros.
-template <int D>
-__device__ __forceinline__ void tile_stage(TileRegs<D> &r, char *lds_k, char *lds_v, int wave, int lane,
-                                           int32_t keys_valid)
-{
-    using C = TileCfg<D>;
+    typedef const __attribute__((address_space(1))) void *gptr;
+    typedef __attribute__((address_space(3))) void *lptr;
+    const int pos = lane % C::CPR;
+    const int r_in = lane / C::CPR;
+    const size_t tile = ((size_t)(blk < 0 ? 0 : blk) * p.kv_heads + head / p.group) * (kBlockSize * D);
+    const char *gk = reinterpret_cast<const char *>(p.k_cache + tile);
+    const char *gv = reinterpret_cast<const char *>(p.v_cache + tile);
 #pragma unroll
     for (int i = 0; i < C::NL; ++i) {
-        const int j = i * 64 + lane;
-        const int key = wave * kBlockSize + j / C::CPR;
-        const int chunk = j % C::CPR;
-        *reinterpret_cast<u32x4 *>(lds_k + key * C::K_STRIDE + chunk * 16) = r.k[i];
-        *reinterpret_cast<u32x4 *>(lds_v + key * C::V_STRIDE + chunk * 16) = r.v[i];
-    }
-    if (keys_valid < kKvTile) {  // only the last step of a range: uniform branch
-        const u32x4 zero = {0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int i = 0; i < C::NL; ++i) {
-            const int j = i * 64 + lane;
-            const int key = wave * kBlockSize + j / C::CPR;
-            if (key >= keys_valid) *reinterpret_cast<u32x4 *>(lds_v + key * C::V_STRIDE + (j % C::CPR) * 16) = zero;
+        const int row_b = i * C::RPL + r_in;            // row inside the block
+        const int row = wave * kBlockSize + row_b;      // row inside the tile
+        const int ck = pos ^ (row & (C::CPR - 1));
+        const int cv = pos ^ (C::VSW * (row & 3));
+        char *dk = lds_k + (wave * kBlockSize + i * C::RPL) * C::ROW;   // wave-uniform destinations
+        char *dv = lds_v + (wave * kBlockSize + i * C::RPL) * C::ROW;
+        if (blk >= 0 && row < keys_valid) {
+            __builtin_amdgcn_global_load_lds((gptr)(gk + row_b * C::ROW + ck * 16), (lptr)dk, 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((gptr)(gv + row_b * C::ROW + cv * 16), (lptr)dv, 16, 0, 0);
+        } else {
+            *reinterpret_cast<u32x4 *>(dv + lane * 16) = u32x4{0u, 0u, 0u, 0u};
         }
     }
 }
 
+// Source block and target LDS tiles of one wavefront's share of the next step, for the loads
+// that tile_compute issues between its matrix instructions.
+struct TileNext {
+    const char *gk, *gv;   // the wavefront's KV block (16 keys) in the K and V caches
+    char *lk, *lv;         // K and V tile of the LDS buffer being filled
+    int wave, lane;
+};
+
+// Load i (of NL) of tile_load, for a block that lies entirely inside the item's key range.
+template <int D>
+__device__ __forceinline__ void tile_load_part(const TileNext &n, int i)
+{
+    using C = TileCfg<D>;
+    typedef const __attribute__((address_space(1))) void *gptr;
+    typedef __attribute__((address_space(3))) void *lptr;
+    const int pos = n.lane % C::CPR;
+    const int row_b = i * C::RPL + n.lane / C::CPR;
+    const int row = n.wave * kBlockSize + row_b;
+    const int ck = pos ^ (row & (C::CPR - 1));
+    const int cv = pos ^ (C::VSW * (row & 3));
+    const int dst = (n.wave * kBlockSize + i * C::RPL) * C::ROW;
+    __builtin_amdgcn_global_load_lds((gptr)(n.gk + row_b * C::ROW + ck * 16), (lptr)(n.lk + dst), 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((gptr)(n.gv + row_b * C::ROW + cv * 16), (lptr)(n.lv + dst), 16, 0, 0);
+}
+
+// The V operand is read with hand-placed instructions and waits.  The compiler makes every LDS read
+// it knows about wait for all outstanding direct-to-LDS loads, which would stall each step half
+// way through on the loads of the NEXT step (they target the other buffer and are published by
+// the barrier at the end of the step).  An asm read is outside that rule; in exchange the waits
+// for the reads themselves are ours: LDS reads return in order, so once at most N operations are
+// outstanding, every read but the last N issued has landed.
+template <int OFF>
+__device__ __forceinline__ u32x2 lds_read_tr16(uint32_t addr)
+{
+    u32x2 r;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+    return r;
+}
+
+template <int DB>
+struct VGroup {
+    u32x2 lo[DB], hi[DB];   // keys base..base+3 (+4*half) and base+8.. of d = 32*db + col
+};
+
+// 16 keys (group G of the 64-key tile) of V^T for all DB row blocks: 2*DB reads in flight.
+template <int D, int G>
+__device__ __forceinline__ void v_issue(VGroup<TileCfg<D>::DB> &g, const uint32_t (&vaddr)[TileCfg<D>::DB])
+{
+    using C = TileCfg<D>;
+#pragma unroll
+    for (int db = 0; db < C::DB; ++db) {
+        g.lo[db] = lds_read_tr16<G * 16 * C::ROW>(vaddr[db]);
+        g.hi[db] = lds_read_tr16<(G * 16 + 8) * C::ROW>(vaddr[db]);
+    }
+}
+
+// Waits until at most N LDS operations are outstanding; the registers of `g` are operands so
+// that nothing using them can be scheduled above the wait.
+template <int N>
+__device__ __forceinline__ void v_wait(VGroup<4> &g)
+{
+    asm volatile("s_waitcnt lgkmcnt(%[n])"
+                 : "+v"(g.lo[0]), "+v"(g.lo[1]), "+v"(g.lo[2]), "+v"(g.lo[3]), "+v"(g.hi[0]), "+v"(g.hi[1]),
+                   "+v"(g.hi[2]), "+v"(g.hi[3])
+                 : [n] "n"(N));
+}
+template <int N>
+__device__ __forceinline__ void v_wait(VGroup<2> &g)
+{
+    asm volatile("s_waitcnt lgkmcnt(%[n])"
+                 : "+v"(g.lo[0]), "+v"(g.lo[1]), "+v"(g.hi[0]), "+v"(g.hi[1])
+                 : [n] "n"(N));
+}
+
+template <int D>
+__device__ __forceinline__ void pv_group(f32x16 (&o)[TileCfg<D>::DB], const VGroup<TileCfg<D>::DB> &g, bf16x8 pf)
+{
+#pragma unroll
+    for (int db = 0; db < TileCfg<D>::DB; ++db) {
+        const u32x4 both = {g.lo[db].x, g.lo[db].y, g.hi[db].x, g.hi[db].y};
+        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf, o[db], 0, 0, 0);
+    }
+}
+
 // One step of the matrix-core body for one wavefront: S^T = K Q^T over 64 keys, online softmax,
-// O^T += V^T P^T.  MASKED steps apply the causal limit `pos` of the lane's row.
-template <int D, bool MASKED>
+// O^T += V^T P^T.  `masked` steps (wavefront-uniform) apply the causal limit `pos` of the lane's row.
+template <int D, bool LOAD_NEXT>
 __device__ __forceinline__ void tile_compute(const char *lds_k, const char *lds_v,
                                              const bf16x8 (&qf)[TileCfg<D>::KS], f32x16 (&o)[TileCfg<D>::DB],
                                              float &m, float &l, float c2, int32_t k0, int32_t pos, int half,
-                                             int col)
+                                             int col, bool masked, const TileNext &next)
 {
     using C = TileCfg<D>;
     f32x16 s[2];
@@ -351,15 +429,54 @@ __device__ __forceinline__ void tile_compute(const char *lds_k, const char *lds_
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
-    const char *krow = lds_k + col * C::K_STRIDE + half * 16;
+    // chunk 2*ks + half of row kb*32 + col sits at position (2*ks + half) ^ (col mod CPR)
+    const char *krow = lds_k + col * C::ROW;
+    const int kswz = col & (C::CPR - 1);
+    // All K fragments are requested first; with LOAD_NEXT the loads of the next step are then
+    // issued between the matrix instructions, where they cost no issue time of their own (a burst
+    // of them ahead of the step holds the wavefront for as long as the memory pipeline takes to
+    // accept 8 KiB of requests from each of the four wavefronts).
+    bf16x8 kf[C::KS][2];
 #pragma unroll
     for (int ks = 0; ks < C::KS; ++ks)
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(krow + kb * 32 * C::K_STRIDE + ks * 32);
-            s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[kb], 0, 0, 0);
+        for (int kb = 0; kb < 2; ++kb)
+            kf[ks][kb] = *reinterpret_cast<const bf16x8 *>(krow + kb * 32 * C::ROW + (((2 * ks + half) ^ kswz) * 16));
+    constexpr int EVERY = C::KS / C::NL;
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks) {
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+            s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks][kb], qf[ks], s[kb], 0, 0, 0);
+        if (LOAD_NEXT && ks % EVERY == 0) tile_load_part<D>(next, ks / EVERY);
+    }
+    if (LOAD_NEXT) {   // keep that order: 2*EVERY matrix instructions, then one K and one V load
+#pragma unroll
+        for (int i = 0; i < C::NL; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 2 * EVERY, 0);
+            __builtin_amdgcn_sched_group_barrier(0x010, 2, 0);
         }
-    if (MASKED) {
+    }
+    // A operand of O^T += V^T P^T: lane (row d = 32*db + col, half) needs keys
+    // {base + 4*half + 0..3} and {base + 8 + 4*half + 0..3} of its d.  ds_read_b64_tr_b16 works on
+    // groups of 16 lanes: lane s of a group supplies the address of 4 consecutive d of ONE key and
+    // receives element (i % 4) of lanes (i / 4) + 4j, j = 0..3.  With lane s pointing at key
+    // kk + s/4, elements d0 + 4*(s%4) .. +3, lane i ends up with keys kk..kk+3 at d = d0 + i.
+    // The first 32 keys are requested here, ahead of the softmax arithmetic that hides their latency.
+    const int s16 = col & 15;
+    const int d0 = (col >> 4) * 16;
+    // this lane's source row inside a 16-key group is 4*half + s16/4 (+8): its swizzle term is fixed
+    const int vswz = C::VSW * ((s16 >> 2) & 3);
+    const int vchunk = (2 * d0) / 16 + ((s16 & 3) >> 1);   // chunk of d0 + 4*(s16%4) for db = 0
+    const uint32_t vbase = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds_v)) +
+                           (half * 4 + (s16 >> 2)) * C::ROW + 8 * (s16 & 1);
+    uint32_t vaddr[C::DB];
+#pragma unroll
+    for (int db = 0; db < C::DB; ++db) vaddr[db] = vbase + (((vchunk + 4 * db) ^ vswz) * 16);
+    VGroup<C::DB> g0, g1, g2, g3;
+    v_issue<D, 0>(g0, vaddr);
+    v_issue<D, 1>(g1, vaddr);
+    if (masked) {
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -385,7 +502,7 @@ __device__ __forceinline__ void tile_compute(const char *lds_k, const char *lds_
     const bool raise = mt * c2 > m * c2 + kLazyLog2;  // m == -inf on the first step: always true
     if (__builtin_amdgcn_ballot_w64(raise) != 0) {
         const float m_new = fmaxf(m, mt);
-        const float m_fin = (MASKED && m_new == -INFINITY) ? 0.f : m_new;
+        const float m_fin = (m_new == -INFINITY) ? 0.f : m_new;
         const float alpha = fast_exp2((m - m_fin) * c2);
         l *= alpha;
 #pragma unroll
@@ -394,7 +511,7 @@ __device__ __forceinline__ void tile_compute(const char *lds_k, const char *lds_
             for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
         m = m_new;
     }
-    const float mc = (MASKED && m == -INFINITY) ? 0.f : m * c2;
+    const float mc = (m == -INFINITY) ? 0.f : m * c2;
     bf16x8 pf[2][2];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
@@ -416,28 +533,17 @@ __device__ __forceinline__ void tile_compute(const char *lds_k, const char *lds_
                     l = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, l, false);
                 }
     }
-    // A operand of O^T += V^T P^T: lane (row d = 32*db + col, half) needs keys
-    // {base + 4*half + 0..3} and {base + 8 + 4*half + 0..3} of its d.  ds_read_b64_tr_b16 works on
-    // groups of 16 lanes: lane s of a group supplies the address of 4 consecutive d of ONE key and
-    // receives element (i % 4) of lanes (i / 4) + 4j, j = 0..3.  With lane s pointing at key
-    // kk + s/4, elements d0 + 4*(s%4) .. +3, lane i ends up with keys kk..kk+3 at d = d0 + i.
-    const int s16 = col & 15;
-    const int d0 = (col >> 4) * 16;
-    const char *vbase = lds_v + (half * 4 + (s16 >> 2)) * C::V_STRIDE + (d0 + 4 * (s16 & 3)) * 2;
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int st = 0; st < 2; ++st)
-#pragma unroll
-            for (int db = 0; db < C::DB; ++db) {
-                const char *src = vbase + (kb * 32 + st * 16) * C::V_STRIDE + db * 64;
-                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(src));
-                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(src + 8 * C::V_STRIDE));
-                const u32x2 lo2 = __builtin_bit_cast(u32x2, lo), hi2 = __builtin_bit_cast(u32x2, hi);
-                const u32x4 both = {lo2.x, lo2.y, hi2.x, hi2.y};
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[kb][st],
-                                                                o[db], 0, 0, 0);
-            }
+    constexpr int PER = 2 * C::DB;   // reads per group
+    v_wait<PER>(g0);
+    pv_group<D>(o, g0, pf[0][0]);
+    v_issue<D, 2>(g2, vaddr);
+    v_wait<PER>(g1);
+    pv_group<D>(o, g1, pf[0][1]);
+    v_issue<D, 3>(g3, vaddr);
+    v_wait<PER>(g2);
+    pv_group<D>(o, g2, pf[1][0]);
+    v_wait<0>(g3);
+    pv_group<D>(o, g3, pf[1][1]);
 }
 
 template <int D>
@@ -483,39 +589,35 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
     };
     int32_t entries = load_entries(0);
 
-    TileRegs<D> regs;
-#pragma unroll
-    for (int i = 0; i < C::NL; ++i) {
-        regs.k[i] = u32x4{0u, 0u, 0u, 0u};
-        regs.v[i] = u32x4{0u, 0u, 0u, 0u};
-    }
-    auto fetch = [&](int32_t step) {
+    auto step_block = [&](int32_t step) {
         if ((step & 63) == 0 && step > 0) entries = load_entries(step);
-        const int32_t blk = __builtin_amdgcn_readlane(entries, step & 63);
-        if (blk >= 0) tile_fetch<D>(regs, p, blk, head, lane);
+        return __builtin_amdgcn_readlane(entries, step & 63);
     };
-    // Pipeline: while step s is computed from LDS buffer s&1, the registers hold step s+1 (staged
-    // into the other buffer at the end of the step) and the loads of step s+2 are issued.
-    fetch(0);
-    tile_stage<D>(regs, lds, lds + C::K_BYTES, wave, lane, it.kv_end - it.kv_begin);
-    if (nsteps > 1) fetch(1);
+    // Pipeline: while step s is computed from LDS buffer s&1, the direct loads of step s+1 fill the
+    // other buffer.  That buffer was last read in step s-1, which every wavefront has left, and the
+    // barrier at the end of step s (which waits for this wavefront's loads first) publishes it.
+    tile_load<D>(p, step_block(0), head, lds, lds + C::K_BYTES, wave, lane, it.kv_end - it.kv_begin);
     __syncthreads();
     for (int32_t step = 0; step < nsteps; ++step) {
         const int32_t k0 = it.kv_begin + step * kKvTile;
         const char *buf = lds + (step & 1) * BUF;
-        // First hand the next step's data (fetched one step ago) to the other LDS buffer and issue
-        // the fetch of the step after it, so that both overlap with this step's arithmetic.  The
-        // other buffer was last read in the previous step, which every wavefront has left.
-        if (step + 1 < nsteps) {
-            char *nbuf = lds + ((step + 1) & 1) * BUF;
-            tile_stage<D>(regs, nbuf, nbuf + C::K_BYTES, wave, lane, it.kv_end - (k0 + kKvTile));
-            if (step + 2 < nsteps) fetch(step + 2);
-        }
-        if (k0 <= wave_last_pos) {  // otherwise every key of the step is above all rows of this wavefront
-            if (k0 + kKvTile - 1 > wave_first_pos)
-                tile_compute<D, true>(buf, buf + C::K_BYTES, qf, o, m, l, c2, k0, pos, half, col);
-            else
-                tile_compute<D, false>(buf, buf + C::K_BYTES, qf, o, m, l, c2, k0, pos, half, col);
+        char *nbuf = lds + ((step + 1) & 1) * BUF;
+        const bool more = step + 1 < nsteps;
+        const int32_t blk_n = more ? step_block(step + 1) : -1;
+        const int32_t keys_n = it.kv_end - (k0 + kKvTile);
+        // otherwise every key of the step is above all rows of this wavefront
+        const bool active = k0 <= wave_last_pos;
+        const bool masked = k0 + kKvTile - 1 > wave_first_pos;
+        if (active && blk_n >= 0 && keys_n >= kKvTile) {
+            const size_t tile = ((size_t)blk_n * p.kv_heads + head / p.group) * (kBlockSize * D);
+            const TileNext next = {reinterpret_cast<const char *>(p.k_cache + tile),
+                                   reinterpret_cast<const char *>(p.v_cache + tile), nbuf, nbuf + C::K_BYTES, wave, lane};
+            tile_compute<D, true>(buf, buf + C::K_BYTES, qf, o, m, l, c2, k0, pos, half, col, masked, next);
+        } else {
+            const TileNext none = {nullptr, nullptr, nullptr, nullptr, 0, 0};
+            if (more) tile_load<D>(p, blk_n, head, nbuf, nbuf + C::K_BYTES, wave, lane, keys_n);
+            if (active)
+                tile_compute<D, false>(buf, buf + C::K_BYTES, qf, o, m, l, c2, k0, pos, half, col, masked, none);
         }
         __syncthreads();
     }
