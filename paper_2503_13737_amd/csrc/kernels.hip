@@ -1,6 +1,7 @@
 // HIP kernels for gfx950 (MI355X): KV-cache append, the unified mixed-batch attention kernel
 // (row-streaming body for generation rows, matrix-core body for prompt tiles) and the merge of
 // split partial results.
+#include <type_traits>
 #include <hip/hip_runtime.h>
 
 #include "mpa_internal.h"
@@ -331,30 +332,31 @@ __device__ __forceinline__ void tile_load(const AttnParams &p, int32_t blk, int 
     }
 }
 
-// Source block and target LDS tiles of one wavefront's share of the next step, for the loads
-// that tile_compute issues between its matrix instructions.
+// Everything a wavefront needs to issue its share of the next step's loads from inside
+// tile_compute.  Only gk/gv change from step to step, and they are wavefront-uniform, so the
+// loads address memory as scalar base + per-lane 32-bit offset and the loop spends no vector
+// arithmetic on them.
+template <int D>
 struct TileNext {
-    const char *gk, *gv;   // the wavefront's KV block (16 keys) in the K and V caches
-    char *lk, *lv;         // K and V tile of the LDS buffer being filled
-    int wave, lane;
+    const char *gk, *gv;                  // the wavefront's KV block (16 keys) in the K and V caches
+    uint32_t koff[TileCfg<D>::NL];        // this lane's byte offset inside the block for load i (K swizzle)
+    uint32_t voff[TileCfg<D>::NL];        // same with the V swizzle
+    uint32_t lds_w;                       // LDS address of the wavefront's 16 rows in the K tile of buffer 0
 };
 
-// Load i (of NL) of tile_load, for a block that lies entirely inside the item's key range.
-template <int D>
-__device__ __forceinline__ void tile_load_part(const TileNext &n, int i)
+// 16 bytes per lane from base + off (base wavefront-uniform, in scalar registers) straight into
+// LDS at lds_dst + 16 * lane (lds_dst wavefront-uniform; the instruction takes it from M0).
+// Written by hand because the compiler's selection of this instruction always forms a 64-bit
+// address per lane.  It is invisible to the compiler's bookkeeping of outstanding memory
+// operations: whoever needs the data waits for vmcnt(0) explicitly.
+__device__ __forceinline__ void load_to_lds_16(const char *base, uint32_t off, uint32_t lds_dst)
 {
-    using C = TileCfg<D>;
-    typedef const __attribute__((address_space(1))) void *gptr;
-    typedef __attribute__((address_space(3))) void *lptr;
-    const int pos = n.lane % C::CPR;
-    const int row_b = i * C::RPL + n.lane / C::CPR;
-    const int row = n.wave * kBlockSize + row_b;
-    const int ck = pos ^ (row & (C::CPR - 1));
-    const int cv = pos ^ (C::VSW * (row & 3));
-    const int dst = (n.wave * kBlockSize + i * C::RPL) * C::ROW;
-    __builtin_amdgcn_global_load_lds((gptr)(n.gk + row_b * C::ROW + ck * 16), (lptr)(n.lk + dst), 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((gptr)(n.gv + row_b * C::ROW + cv * 16), (lptr)(n.lv + dst), 16, 0, 0);
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(off), "s"(base), "s"(lds_dst)
+                 : "m0");
 }
+__device__ __forceinline__ void wait_loads_to_lds() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // The V operand is read with hand-placed instructions and waits.  The compiler makes every LDS read
 // it knows about wait for all outstanding direct-to-LDS loads, which would stall each step half
@@ -376,14 +378,16 @@ struct VGroup {
 };
 
 // 16 keys (group G of the 64-key tile) of V^T for all DB row blocks: 2*DB reads in flight.
-template <int D, int G>
+template <int D, int G, int BUFI>
 __device__ __forceinline__ void v_issue(VGroup<TileCfg<D>::DB> &g, const uint32_t (&vaddr)[TileCfg<D>::DB])
 {
     using C = TileCfg<D>;
+    constexpr int BASE = BUFI * (C::K_BYTES + C::V_BYTES) + C::K_BYTES;   // V tile of buffer BUFI
+    static_assert(BASE + (3 * 16 + 8) * C::ROW < 65536, "must fit the instruction's offset field");
 #pragma unroll
     for (int db = 0; db < C::DB; ++db) {
-        g.lo[db] = lds_read_tr16<G * 16 * C::ROW>(vaddr[db]);
-        g.hi[db] = lds_read_tr16<(G * 16 + 8) * C::ROW>(vaddr[db]);
+        g.lo[db] = lds_read_tr16<BASE + G * 16 * C::ROW>(vaddr[db]);
+        g.hi[db] = lds_read_tr16<BASE + (G * 16 + 8) * C::ROW>(vaddr[db]);
     }
 }
 
@@ -416,134 +420,135 @@ __device__ __forceinline__ void pv_group(f32x16 (&o)[TileCfg<D>::DB], const VGro
 }
 
 // One step of the matrix-core body for one wavefront: S^T = K Q^T over 64 keys, online softmax,
-// O^T += V^T P^T.  `masked` steps (wavefront-uniform) apply the causal limit `pos` of the lane's row.
-template <int D, bool LOAD_NEXT>
-__device__ __forceinline__ void tile_compute(const char *lds_k, const char *lds_v,
+// O^T += V^T P^T, from LDS buffer BUFI.  `masked` steps (wavefront-uniform) apply the causal limit
+// `pos` of the lane's row.  kaddr/vaddr are the lane's LDS addresses in buffer 0 (loop-invariant:
+// the buffer and the key group enter as instruction offsets); with LOAD_NEXT the wavefront's
+// share of the next step goes into the other buffer along the way.
+template <int D, bool LOAD_NEXT, int BUFI>
+__device__ __forceinline__ void tile_compute(const uint32_t (&kaddr)[TileCfg<D>::KS],
+                                             const uint32_t (&vaddr0)[TileCfg<D>::DB],
                                              const bf16x8 (&qf)[TileCfg<D>::KS], f32x16 (&o)[TileCfg<D>::DB],
                                              float &m, float &l, float c2, int32_t k0, int32_t pos, int half,
-                                             int col, bool masked, const TileNext &next)
+                                             bool masked, const TileNext<D> &next)
 {
     using C = TileCfg<D>;
-    f32x16 s[2];
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef const __attribute__((address_space(3))) bf16x8 lds_bf16x8;
+    constexpr int BUF = C::K_BYTES + C::V_BYTES;
+    // The 64 keys are handled as two halves of 32 whose phases overlap inside the wavefront: the
+    // softmax arithmetic of one half is written between matrix instructions of the other
+    // (QK of half 1 with the exponentials of half 0, PV of half 0 with the exponentials of
+    // half 1), because a wavefront issues in order and a run of matrix instructions would
+    // otherwise hold back the vector instructions behind it for its whole length.
+    // Load i (of NL) of tile_load into the other LDS buffer, for a block that lies entirely
+    // inside the item's key range.
+    auto load_part = [&](int i) {
+        const uint32_t dst = next.lds_w + (BUFI ^ 1) * BUF + i * C::RPL * C::ROW;
+        load_to_lds_16(next.gk, next.koff[i], dst);
+        load_to_lds_16(next.gv, next.voff[i], dst + C::K_BYTES);
+    };
+    f32x16 s0, s1;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s0[v] = s1[v] = 0.f;
+    bf16x8 kf[2][C::KS];
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
-    // chunk 2*ks + half of row kb*32 + col sits at position (2*ks + half) ^ (col mod CPR)
-    const char *krow = lds_k + col * C::ROW;
-    const int kswz = col & (C::CPR - 1);
-    // All K fragments are requested first; with LOAD_NEXT the loads of the next step are then
-    // issued between the matrix instructions, where they cost no issue time of their own (a burst
-    // of them ahead of the step holds the wavefront for as long as the memory pipeline takes to
-    // accept 8 KiB of requests from each of the four wavefronts).
-    bf16x8 kf[C::KS][2];
-#pragma unroll
-    for (int ks = 0; ks < C::KS; ++ks)
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-            kf[ks][kb] = *reinterpret_cast<const bf16x8 *>(krow + kb * 32 * C::ROW + (((2 * ks + half) ^ kswz) * 16));
-    constexpr int EVERY = C::KS / C::NL;
-#pragma unroll
-    for (int ks = 0; ks < C::KS; ++ks) {
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-            s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[ks][kb], qf[ks], s[kb], 0, 0, 0);
-        if (LOAD_NEXT && ks % EVERY == 0) tile_load_part<D>(next, ks / EVERY);
-    }
-    if (LOAD_NEXT) {   // keep that order: 2*EVERY matrix instructions, then one K and one V load
-#pragma unroll
-        for (int i = 0; i < C::NL; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 2 * EVERY, 0);
-            __builtin_amdgcn_sched_group_barrier(0x010, 2, 0);
-        }
-    }
-    // A operand of O^T += V^T P^T: lane (row d = 32*db + col, half) needs keys
-    // {base + 4*half + 0..3} and {base + 8 + 4*half + 0..3} of its d.  ds_read_b64_tr_b16 works on
-    // groups of 16 lanes: lane s of a group supplies the address of 4 consecutive d of ONE key and
-    // receives element (i % 4) of lanes (i / 4) + 4j, j = 0..3.  With lane s pointing at key
-    // kk + s/4, elements d0 + 4*(s%4) .. +3, lane i ends up with keys kk..kk+3 at d = d0 + i.
-    // The first 32 keys are requested here, ahead of the softmax arithmetic that hides their latency.
-    const int s16 = col & 15;
-    const int d0 = (col >> 4) * 16;
-    // this lane's source row inside a 16-key group is 4*half + s16/4 (+8): its swizzle term is fixed
-    const int vswz = C::VSW * ((s16 >> 2) & 3);
-    const int vchunk = (2 * d0) / 16 + ((s16 & 3) >> 1);   // chunk of d0 + 4*(s16%4) for db = 0
-    const uint32_t vbase = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds_v)) +
-                           (half * 4 + (s16 >> 2)) * C::ROW + 8 * (s16 & 1);
+        for (int ks = 0; ks < C::KS; ++ks)
+            kf[kb][ks] = *reinterpret_cast<lds_bf16x8 *>(static_cast<uintptr_t>(kaddr[ks] + BUFI * BUF + kb * 32 * C::ROW));
     uint32_t vaddr[C::DB];
 #pragma unroll
-    for (int db = 0; db < C::DB; ++db) vaddr[db] = vbase + (((vchunk + 4 * db) ^ vswz) * 16);
+    for (int db = 0; db < C::DB; ++db) vaddr[db] = vaddr0[db];
     VGroup<C::DB> g0, g1, g2, g3;
-    v_issue<D, 0>(g0, vaddr);
-    v_issue<D, 1>(g1, vaddr);
-    if (masked) {
+
+    auto mask_half = [&](f32x16 &sv, int kb) {
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int32_t key = k0 + kb * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
-                if (key > pos) s[kb][v] = -INFINITY;
-            }
-    }
-    float mt = s[0][0];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) mt = fmaxf(mt, s[kb][v]);
-    {   // lane l <-> lane l ^ 32 without going through LDS
-        const uint32_t mi = __float_as_uint(mt);
-        auto sw = __builtin_amdgcn_permlane32_swap(mi, mi, false, false);
-        mt = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-    }
+        for (int v = 0; v < 16; ++v) {
+            const int32_t key = k0 + kb * 32 + (v >> 2) * 8 + half * 4 + (v & 3);
+            if (key > pos) sv[v] = -INFINITY;
+        }
+    };
     // The reference maximum m only has to be close to the true one: exponents up to kLazyLog2
     // above it are harmless in fp32 and bf16.  So m is raised (and l, O rescaled) only when some
-    // row's step maximum exceeds it by more than that -- after the first steps, almost never.
-    constexpr float kLazyLog2 = 8.f;
-    const bool raise = mt * c2 > m * c2 + kLazyLog2;  // m == -inf on the first step: always true
-    if (__builtin_amdgcn_ballot_w64(raise) != 0) {
-        const float m_new = fmaxf(m, mt);
-        const float m_fin = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = fast_exp2((m - m_fin) * c2);
-        l *= alpha;
+    // row's maximum over the 32 keys exceeds it by more than that -- after the first steps, almost never.
+    auto raise_check = [&](const f32x16 &sv) {
+        float mt = sv[0];
 #pragma unroll
-        for (int db = 0; db < C::DB; ++db)
+        for (int v = 1; v < 16; ++v) mt = fmaxf(mt, sv[v]);
+        {   // lane l <-> lane l ^ 32 without going through LDS
+            const uint32_t mi = __float_as_uint(mt);
+            auto sw = __builtin_amdgcn_permlane32_swap(mi, mi, false, false);
+            mt = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+        }
+        constexpr float kLazyLog2 = 8.f;
+        const bool raise = mt * c2 > m * c2 + kLazyLog2;  // m == -inf at first: always true
+        if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+            const float m_new = fmaxf(m, mt);
+            const float m_fin = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = fast_exp2((m - m_fin) * c2);
+            l *= alpha;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
-        m = m_new;
-    }
-    const float mc = (m == -INFINITY) ? 0.f : m * c2;
-    bf16x8 pf[2][2];
+            for (int db = 0; db < C::DB; ++db)
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v)
-            pf[kb][v >> 3][v & 7] = static_cast<__bf16>(fast_exp2(fmaf(s[kb][v], c2, -mc)));
-    // Row sum of the bf16-rounded weights (the very values the PV product uses, so numerator and
+                for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
+            m = m_new;
+        }
+    };
+    // Weights of one half, rounded to bf16 in the B-operand layout of the PV product, and their
+    // row sum taken from the rounded values (the very ones the product uses, so numerator and
     // denominator stay consistent), two per instruction.
-    {
-        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    auto weights = [&](const f32x16 &sv, bf16x8 (&pf)[2]) {
+        const float mc = (m == -INFINITY) ? 0.f : m * c2;
         const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+        for (int v = 0; v < 16; ++v) pf[v >> 3][v & 7] = static_cast<__bf16>(fast_exp2(fmaf(sv[v], c2, -mc)));
 #pragma unroll
-            for (int st = 0; st < 2; ++st)
+        for (int st = 0; st < 2; ++st)
 #pragma unroll
-                for (int e = 0; e < 8; e += 2) {
-                    const bf16x2 pr = {pf[kb][st][e], pf[kb][st][e + 1]};
-                    l = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, l, false);
-                }
+            for (int e = 0; e < 8; e += 2) {
+                const bf16x2 pr = {pf[st][e], pf[st][e + 1]};
+                l = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, l, false);
+            }
+    };
+    constexpr int PER = 2 * C::DB;          // LDS reads per V group
+    constexpr int HEAD = 3;                 // matrix instructions written ahead of a maximum check
+    static_assert(C::NL % 2 == 0, "the next step's loads are split over two phases");
+
+    // keys 0..31: S0 = K0 Q^T, with the first half of the next step's loads
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks) {
+        s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][ks], qf[ks], s0, 0, 0, 0);
+        if (LOAD_NEXT && ks % (2 * C::KS / C::NL) == 0) load_part(ks / (2 * C::KS / C::NL));
     }
-    constexpr int PER = 2 * C::DB;   // reads per group
+    v_issue<D, 0, BUFI>(g0, vaddr);
+    v_issue<D, 1, BUFI>(g1, vaddr);
+    // keys 32..63: S1 = K1 Q^T; its first instructions cover the latency of S0 for the check
+#pragma unroll
+    for (int ks = 0; ks < HEAD; ++ks) s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][ks], qf[ks], s1, 0, 0, 0);
+    if (masked) mask_half(s0, 0);
+    raise_check(s0);
+    bf16x8 pf0[2], pf1[2];
+#pragma unroll
+    for (int ks = HEAD; ks < C::KS; ++ks) s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][ks], qf[ks], s1, 0, 0, 0);
+    weights(s0, pf0);
+    // O^T += V0^T P0^T; the second group's instructions wait behind the check of S1
     v_wait<PER>(g0);
-    pv_group<D>(o, g0, pf[0][0]);
-    v_issue<D, 2>(g2, vaddr);
+    pv_group<D>(o, g0, pf0[0]);
+    v_issue<D, 2, BUFI>(g2, vaddr);
+    if (masked) mask_half(s1, 1);
+    raise_check(s1);
     v_wait<PER>(g1);
-    pv_group<D>(o, g1, pf[0][1]);
-    v_issue<D, 3>(g3, vaddr);
+    pv_group<D>(o, g1, pf0[1]);
+    v_issue<D, 3, BUFI>(g3, vaddr);
+    if (LOAD_NEXT) {
+#pragma unroll
+        for (int i = C::NL / 2; i < C::NL; ++i) load_part(i);
+    }
+    weights(s1, pf1);
     v_wait<PER>(g2);
-    pv_group<D>(o, g2, pf[1][0]);
+    pv_group<D>(o, g2, pf1[0]);
     v_wait<0>(g3);
-    pv_group<D>(o, g3, pf[1][1]);
+    pv_group<D>(o, g3, pf1[1]);
 }
 
 template <int D>
@@ -593,15 +598,45 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
         if ((step & 63) == 0 && step > 0) entries = load_entries(step);
         return __builtin_amdgcn_readlane(entries, step & 63);
     };
+    // Loop-invariant addresses.  K: chunk 2*ks + half of row (kb*32 +) col sits at chunk position
+    // (2*ks + half) ^ (col mod CPR).  V: the lane's source row inside a 16-key group is
+    // 4*half + s16/4 (+8), which fixes its swizzle term; it supplies the address of d0 + 4*(s16%4) + 32*db.
+    const uint32_t lds0 = static_cast<uint32_t>(reinterpret_cast<uintptr_t>(lds));
+    uint32_t kaddr[C::KS], vaddr[C::DB];
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks)
+        kaddr[ks] = lds0 + col * C::ROW + (((2 * ks + half) ^ (col & (C::CPR - 1))) * 16);
+    {
+        const int s16 = col & 15, d0 = (col >> 4) * 16;
+        const int vswz = C::VSW * ((s16 >> 2) & 3);
+        const int vchunk = (2 * d0) / 16 + ((s16 & 3) >> 1);
+#pragma unroll
+        for (int db = 0; db < C::DB; ++db)
+            vaddr[db] = lds0 + (half * 4 + (s16 >> 2)) * C::ROW + 8 * (s16 & 1) + (((vchunk + 4 * db) ^ vswz) * 16);
+    }
+    TileNext<D> next;
+    {
+        const int cpos = lane % C::CPR, r_in = lane / C::CPR;
+#pragma unroll
+        for (int i = 0; i < C::NL; ++i) {
+            const int row_b = i * C::RPL + r_in, row = wave * kBlockSize + row_b;
+            next.koff[i] = row_b * C::ROW + ((cpos ^ (row & (C::CPR - 1))) * 16);
+            next.voff[i] = row_b * C::ROW + ((cpos ^ (C::VSW * (row & 3))) * 16);
+        }
+        next.lds_w = __builtin_amdgcn_readfirstlane(lds0 + wave * kBlockSize * C::ROW);
+        next.gk = next.gv = nullptr;
+    }
+
     // Pipeline: while step s is computed from LDS buffer s&1, the direct loads of step s+1 fill the
     // other buffer.  That buffer was last read in step s-1, which every wavefront has left, and the
     // barrier at the end of step s (which waits for this wavefront's loads first) publishes it.
+    // The loop is written out for both buffers so that the buffer is an instruction offset.
     tile_load<D>(p, step_block(0), head, lds, lds + C::K_BYTES, wave, lane, it.kv_end - it.kv_begin);
     __syncthreads();
-    for (int32_t step = 0; step < nsteps; ++step) {
+    auto do_step = [&](int32_t step, auto bufi) {
+        constexpr int BUFI = decltype(bufi)::value;
         const int32_t k0 = it.kv_begin + step * kKvTile;
-        const char *buf = lds + (step & 1) * BUF;
-        char *nbuf = lds + ((step + 1) & 1) * BUF;
+        char *nbuf = lds + (BUFI ^ 1) * BUF;
         const bool more = step + 1 < nsteps;
         const int32_t blk_n = more ? step_block(step + 1) : -1;
         const int32_t keys_n = it.kv_end - (k0 + kKvTile);
@@ -610,16 +645,19 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
         const bool masked = k0 + kKvTile - 1 > wave_first_pos;
         if (active && blk_n >= 0 && keys_n >= kKvTile) {
             const size_t tile = ((size_t)blk_n * p.kv_heads + head / p.group) * (kBlockSize * D);
-            const TileNext next = {reinterpret_cast<const char *>(p.k_cache + tile),
-                                   reinterpret_cast<const char *>(p.v_cache + tile), nbuf, nbuf + C::K_BYTES, wave, lane};
-            tile_compute<D, true>(buf, buf + C::K_BYTES, qf, o, m, l, c2, k0, pos, half, col, masked, next);
+            next.gk = reinterpret_cast<const char *>(p.k_cache + tile);
+            next.gv = reinterpret_cast<const char *>(p.v_cache + tile);
+            tile_compute<D, true, BUFI>(kaddr, vaddr, qf, o, m, l, c2, k0, pos, half, masked, next);
         } else {
-            const TileNext none = {nullptr, nullptr, nullptr, nullptr, 0, 0};
             if (more) tile_load<D>(p, blk_n, head, nbuf, nbuf + C::K_BYTES, wave, lane, keys_n);
-            if (active)
-                tile_compute<D, false>(buf, buf + C::K_BYTES, qf, o, m, l, c2, k0, pos, half, col, masked, none);
+            if (active) tile_compute<D, false, BUFI>(kaddr, vaddr, qf, o, m, l, c2, k0, pos, half, masked, next);
         }
+        wait_loads_to_lds();
         __syncthreads();
+    };
+    for (int32_t step = 0; step < nsteps; step += 2) {
+        do_step(step, std::integral_constant<int, 0>());
+        if (step + 1 < nsteps) do_step(step + 1, std::integral_constant<int, 1>());
     }
 
     const float l_tot = l + __shfl_xor(l, 32);
