@@ -419,27 +419,52 @@ __device__ __forceinline__ void pv_group(f32x16 (&o)[TileCfg<D>::DB], const VGro
     }
 }
 
+// K fragments are read the same way (hand-placed, waited for by count).
+template <int OFF>
+__device__ __forceinline__ u32x4 lds_read_b128(uint32_t addr)
+{
+    u32x4 r;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+    return r;
+}
+template <int N>
+__device__ __forceinline__ void k_wait(u32x4 &f)
+{
+    asm volatile("s_waitcnt lgkmcnt(%[n])" : "+v"(f) : [n] "n"(N));
+}
+
 // One step of the matrix-core body for one wavefront: S^T = K Q^T over 64 keys, online softmax,
 // O^T += V^T P^T, from LDS buffer BUFI.  `masked` steps (wavefront-uniform) apply the causal limit
 // `pos` of the lane's row.  kaddr/vaddr are the lane's LDS addresses in buffer 0 (loop-invariant:
 // the buffer and the key group enter as instruction offsets); with LOAD_NEXT the wavefront's
 // share of the next step goes into the other buffer along the way.
+//
+// The 64 keys are handled as two halves of 32 whose phases overlap inside the wavefront, because
+// a wavefront issues in order and a run of matrix instructions holds back the vector
+// instructions written behind it: the weights of half 0 are computed between the QK
+// instructions of half 1, those of half 1 between the PV instructions of half 0.
+//
+// Softmax reference: weights are 2^(c2*(s - m)) for a per-row reference m that is some earlier
+// score of the row, not necessarily its maximum -- any reference gives the same result after
+// the final division as long as nothing overflows, and one that was once the row's maximum
+// cannot make the leading terms underflow.  So no maximum is taken in the common case: the
+// weights are computed against the current m, and only if a lane's partial row sum comes out
+// above 2^64 (or m is still unset) does the wavefront take the row maxima, raise m, rescale l
+// and O, and recompute the weights of that half.
 template <int D, bool LOAD_NEXT, int BUFI>
 __device__ __forceinline__ void tile_compute(const uint32_t (&kaddr)[TileCfg<D>::KS],
-                                             const uint32_t (&vaddr0)[TileCfg<D>::DB],
+                                             const uint32_t (&vaddr)[TileCfg<D>::DB],
                                              const bf16x8 (&qf)[TileCfg<D>::KS], f32x16 (&o)[TileCfg<D>::DB],
                                              float &m, float &l, float c2, int32_t k0, int32_t pos, int half,
                                              bool masked, const TileNext<D> &next)
 {
     using C = TileCfg<D>;
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-    typedef const __attribute__((address_space(3))) bf16x8 lds_bf16x8;
     constexpr int BUF = C::K_BYTES + C::V_BYTES;
-    // The 64 keys are handled as two halves of 32 whose phases overlap inside the wavefront: the
-    // softmax arithmetic of one half is written between matrix instructions of the other
-    // (QK of half 1 with the exponentials of half 0, PV of half 0 with the exponentials of
-    // half 1), because a wavefront issues in order and a run of matrix instructions would
-    // otherwise hold back the vector instructions behind it for its whole length.
+    constexpr int KB0 = BUFI * BUF;                 // K tile of this buffer
+    constexpr int PER = 2 * C::DB;                  // LDS reads per V group
+    static_assert(KB0 + 32 * C::ROW < 65536 && 2 * C::KS <= 16, "offset field, outstanding-read counter");
+
     // Load i (of NL) of tile_load into the other LDS buffer, for a block that lies entirely
     // inside the item's key range.
     auto load_part = [&](int i) {
@@ -447,20 +472,6 @@ __device__ __forceinline__ void tile_compute(const uint32_t (&kaddr)[TileCfg<D>:
         load_to_lds_16(next.gk, next.koff[i], dst);
         load_to_lds_16(next.gv, next.voff[i], dst + C::K_BYTES);
     };
-    f32x16 s0, s1;
-#pragma unroll
-    for (int v = 0; v < 16; ++v) s0[v] = s1[v] = 0.f;
-    bf16x8 kf[2][C::KS];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int ks = 0; ks < C::KS; ++ks)
-            kf[kb][ks] = *reinterpret_cast<lds_bf16x8 *>(static_cast<uintptr_t>(kaddr[ks] + BUFI * BUF + kb * 32 * C::ROW));
-    uint32_t vaddr[C::DB];
-#pragma unroll
-    for (int db = 0; db < C::DB; ++db) vaddr[db] = vaddr0[db];
-    VGroup<C::DB> g0, g1, g2, g3;
-
     auto mask_half = [&](f32x16 &sv, int kb) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
@@ -468,23 +479,32 @@ __device__ __forceinline__ void tile_compute(const uint32_t (&kaddr)[TileCfg<D>:
             if (key > pos) sv[v] = -INFINITY;
         }
     };
-    // The reference maximum m only has to be close to the true one: exponents up to kLazyLog2
-    // above it are harmless in fp32 and bf16.  So m is raised (and l, O rescaled) only when some
-    // row's maximum over the 32 keys exceeds it by more than that -- after the first steps, almost never.
-    auto raise_check = [&](const f32x16 &sv) {
-        float mt = sv[0];
+    // Weights j (two scores) of one half: rounded to bf16 in the B-operand layout of the PV
+    // product; their sum is taken from the rounded values (the very ones the product uses, so
+    // numerator and denominator stay consistent).
+    const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
+    auto weight_pair = [&](const f32x16 &sv, bf16x8 (&pf)[2], float mc, float &sum, int j) {
+        const bf16x2 pr = {static_cast<__bf16>(fast_exp2(fmaf(sv[2 * j], c2, -mc))),
+                           static_cast<__bf16>(fast_exp2(fmaf(sv[2 * j + 1], c2, -mc)))};
+        pf[j >> 2][(2 * j) & 7] = pr[0];
+        pf[j >> 2][(2 * j + 1) & 7] = pr[1];
+        sum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, sum, false);
+    };
+    // After the weights of a half: is the reference still good for every row of the wavefront?
+    auto settle = [&](const f32x16 &sv, bf16x8 (&pf)[2], float sum_a, float sum_b) {
+        float lh = sum_a + sum_b;
+        const bool redo = !(lh <= 0x1p64f) || m == -INFINITY;     // also catches inf and NaN
+        if (__builtin_amdgcn_ballot_w64(redo) != 0) {
+            float mt = sv[0];
 #pragma unroll
-        for (int v = 1; v < 16; ++v) mt = fmaxf(mt, sv[v]);
-        {   // lane l <-> lane l ^ 32 without going through LDS
-            const uint32_t mi = __float_as_uint(mt);
-            auto sw = __builtin_amdgcn_permlane32_swap(mi, mi, false, false);
-            mt = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-        }
-        constexpr float kLazyLog2 = 8.f;
-        const bool raise = mt * c2 > m * c2 + kLazyLog2;  // m == -inf at first: always true
-        if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+            for (int v = 1; v < 16; ++v) mt = fmaxf(mt, sv[v]);
+            {   // lane l <-> lane l ^ 32 without going through LDS
+                const uint32_t mi = __float_as_uint(mt);
+                auto sw = __builtin_amdgcn_permlane32_swap(mi, mi, false, false);
+                mt = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+            }
             const float m_new = fmaxf(m, mt);
-            const float m_fin = (m_new == -INFINITY) ? 0.f : m_new;
+            const float m_fin = (m_new == -INFINITY) ? 0.f : m_new;   // row without a visible key so far
             const float alpha = fast_exp2((m - m_fin) * c2);
             l *= alpha;
 #pragma unroll
@@ -492,59 +512,78 @@ __device__ __forceinline__ void tile_compute(const uint32_t (&kaddr)[TileCfg<D>:
 #pragma unroll
                 for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
             m = m_new;
+            const float mc = m_fin * c2;
+            float ra = 0.f, rb = 0.f;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) weight_pair(sv, pf, mc, (j & 1) ? rb : ra, j);
+            lh = ra + rb;
         }
+        l += lh;
     };
-    // Weights of one half, rounded to bf16 in the B-operand layout of the PV product, and their
-    // row sum taken from the rounded values (the very ones the product uses, so numerator and
-    // denominator stay consistent), two per instruction.
-    auto weights = [&](const f32x16 &sv, bf16x8 (&pf)[2]) {
-        const float mc = (m == -INFINITY) ? 0.f : m * c2;
-        const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
-#pragma unroll
-        for (int v = 0; v < 16; ++v) pf[v >> 3][v & 7] = static_cast<__bf16>(fast_exp2(fmaf(sv[v], c2, -mc)));
-#pragma unroll
-        for (int st = 0; st < 2; ++st)
-#pragma unroll
-            for (int e = 0; e < 8; e += 2) {
-                const bf16x2 pr = {pf[st][e], pf[st][e + 1]};
-                l = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, l, false);
-            }
-    };
-    constexpr int PER = 2 * C::DB;          // LDS reads per V group
-    constexpr int HEAD = 3;                 // matrix instructions written ahead of a maximum check
-    static_assert(C::NL % 2 == 0, "the next step's loads are split over two phases");
 
-    // keys 0..31: S0 = K0 Q^T, with the first half of the next step's loads
+    // ---- all K fragments of the step: half 0 first
+    u32x4 kf[2][C::KS];
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks) kf[0][ks] = lds_read_b128<KB0>(kaddr[ks]);
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks) kf[1][ks] = lds_read_b128<KB0 + 32 * C::ROW>(kaddr[ks]);
+
+    // ---- S0 = K0 Q^T (keys 0..31), with the next step's loads between the instructions
+    f32x16 s0, s1;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s0[v] = s1[v] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < C::KS; ++ks) {
-        s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0][ks], qf[ks], s0, 0, 0, 0);
-        if (LOAD_NEXT && ks % (2 * C::KS / C::NL) == 0) load_part(ks / (2 * C::KS / C::NL));
+        if (ks == 0) k_wait<2 * C::KS - 1>(kf[0][0]);
+        else if (ks == 1) k_wait<2 * C::KS - 2>(kf[0][1]);
+        else if (ks == 2) k_wait<2 * C::KS - 3>(kf[0][2]);
+        else if (ks == 3) k_wait<2 * C::KS - 4>(kf[0][3]);
+        else if (ks == 4) k_wait<2 * C::KS - 5>(kf[0][4 % C::KS]);
+        else if (ks == 5) k_wait<2 * C::KS - 6>(kf[0][5 % C::KS]);
+        else if (ks == 6) k_wait<2 * C::KS - 7>(kf[0][6 % C::KS]);
+        else k_wait<2 * C::KS - 8>(kf[0][7 % C::KS]);
+        s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[0][ks]), qf[ks], s0, 0, 0, 0);
+        if (LOAD_NEXT && ks % (C::KS / C::NL) == 0) load_part(ks / (C::KS / C::NL));
     }
+    VGroup<C::DB> g0, g1, g2, g3;
     v_issue<D, 0, BUFI>(g0, vaddr);
-    v_issue<D, 1, BUFI>(g1, vaddr);
-    // keys 32..63: S1 = K1 Q^T; its first instructions cover the latency of S0 for the check
-#pragma unroll
-    for (int ks = 0; ks < HEAD; ++ks) s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][ks], qf[ks], s1, 0, 0, 0);
     if (masked) mask_half(s0, 0);
-    raise_check(s0);
+
+    // ---- S1 = K1 Q^T (keys 32..63) with the weights of half 0
+    k_wait<PER>(kf[1][C::KS - 1]);   // only the V reads may still be under way
     bf16x8 pf0[2], pf1[2];
+    {
+        const float mc = (m == -INFINITY) ? 0.f : m * c2;
+        float sum_a = 0.f, sum_b = 0.f;
 #pragma unroll
-    for (int ks = HEAD; ks < C::KS; ++ks) s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[1][ks], qf[ks], s1, 0, 0, 0);
-    weights(s0, pf0);
-    // O^T += V0^T P0^T; the second group's instructions wait behind the check of S1
-    v_wait<PER>(g0);
-    pv_group<D>(o, g0, pf0[0]);
-    v_issue<D, 2, BUFI>(g2, vaddr);
-    if (masked) mask_half(s1, 1);
-    raise_check(s1);
-    v_wait<PER>(g1);
-    pv_group<D>(o, g1, pf0[1]);
-    v_issue<D, 3, BUFI>(g3, vaddr);
-    if (LOAD_NEXT) {
+        for (int ks = 0; ks < C::KS; ++ks) {
+            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[1][ks]), qf[ks], s1, 0, 0, 0);
 #pragma unroll
-        for (int i = C::NL / 2; i < C::NL; ++i) load_part(i);
+            for (int j = ks * 8 / C::KS; j < (ks + 1) * 8 / C::KS; ++j) weight_pair(s0, pf0, mc, (j & 1) ? sum_b : sum_a, j);
+        }
+        v_issue<D, 1, BUFI>(g1, vaddr);
+        settle(s0, pf0, sum_a, sum_b);
     }
-    weights(s1, pf1);
+    if (masked) mask_half(s1, 1);
+
+    // ---- O^T += V0^T P0^T with the weights of half 1
+    {
+        const float mc = (m == -INFINITY) ? 0.f : m * c2;
+        float sum_a = 0.f, sum_b = 0.f;
+        v_wait<PER>(g0);
+        pv_group<D>(o, g0, pf0[0]);
+        v_issue<D, 2, BUFI>(g2, vaddr);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) weight_pair(s1, pf1, mc, (j & 1) ? sum_b : sum_a, j);
+        v_wait<PER>(g1);
+        pv_group<D>(o, g1, pf0[1]);
+        v_issue<D, 3, BUFI>(g3, vaddr);
+#pragma unroll
+        for (int j = 4; j < 8; ++j) weight_pair(s1, pf1, mc, (j & 1) ? sum_b : sum_a, j);
+        settle(s1, pf1, sum_a, sum_b);
+    }
+
+    // ---- O^T += V1^T P1^T
     v_wait<PER>(g2);
     pv_group<D>(o, g2, pf1[0]);
     v_wait<0>(g3);

@@ -28,10 +28,12 @@ def errors(got_bits: np.ndarray, ref: np.ndarray):
     return float(np.abs(d).max()), float(np.sqrt((d * d).sum() / max((ref * ref).sum(), 1e-300)))
 
 
-def assert_close(got_bits, ref, what=""):
+def assert_close(got_bits, ref, what="", abs_scale: float = 1.0):
+    """abs_scale widens the absolute bound for cases whose outputs are far larger than those of
+    the paper's workloads (bf16 outputs and bf16 weights carry a relative error of 2^-8, 2^-9)."""
     assert not np.isnan(W.bf16_to_f64(got_bits)).any(), f"{what}: NaN in output"
     ma, rl = errors(got_bits, ref)
-    assert ma <= MAX_ABS_TOL and rl <= REL_L2_TOL, f"{what}: max-abs {ma:.3e} rel-L2 {rl:.3e}"
+    assert ma <= MAX_ABS_TOL * abs_scale and rl <= REL_L2_TOL, f"{what}: max-abs {ma:.3e} rel-L2 {rl:.3e}"
     return ma, rl
 
 
@@ -52,7 +54,7 @@ class DeviceBatch:
         self.out = torch.full((b.T, b.H, b.D), 0x7FFF, dtype=torch.int16, device="cuda")
 
 
-def gpu_run(ctx, b: W.Batch, append: bool = True, poison_ws: bool = True):
+def gpu_run(ctx, b: W.Batch, append: bool = True, poison_ws: bool = True, scale: float | None = None):
     """kv_append (optional) + attention on the GPU; returns (out bits, k_cache bits, v_cache bits)."""
     import torch
     db = DeviceBatch(b, "prior" if append else "ctx")
@@ -63,16 +65,17 @@ def gpu_run(ctx, b: W.Batch, append: bool = True, poison_ws: bool = True):
     if poison_ws:
         ws.fill_(0xFF)  # NaN patterns in the partial buffers
     ctx.mixed_paged_attention(db.q, db.k_cache, db.v_cache, db.block_table, b.chunk_starts,
-                              b.context_lens, db.out, ws, scale=b.scale)
+                              b.context_lens, db.out, ws, scale=b.scale if scale is None else scale)
     torch.cuda.synchronize()
     return to_host_u16(db.out), to_host_u16(db.k_cache), to_host_u16(db.v_cache)
 
 
-def oracle_run(b: W.Batch):
+def oracle_run(b: W.Batch, scale: float | None = None):
     """Oracle append + attention; returns (out float64, k_cache, v_cache)."""
     import oracle
     kc, vc = b.full_cache("prior")
     kn, vn = b.new_kv()
     oracle.kv_append(kn, vn, b.slot_map, kc, vc)
-    out = oracle.attention(b.q, kc, vc, b.block_table, b.chunk_starts, b.context_lens, b.scale)
+    out = oracle.attention(b.q, kc, vc, b.block_table, b.chunk_starts, b.context_lens,
+                           b.scale if scale is None else scale)
     return out, kc, vc

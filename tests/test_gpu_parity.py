@@ -113,6 +113,23 @@ def test_edge_shapes(mpa, ql, ctx):
         assert_close(out, ref, f"{b.name} {opts}")
 
 
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("scale", [1.0, 4.0, 16.0])
+def test_steep_softmax(mpa, scale, D):
+    """Scores spread over hundreds of powers of two (the scale is far above 1/sqrt(D)): a row's
+    largest score keeps growing as more keys are seen, so the tile body's softmax reference has
+    to be reset several times per row, also from weights that overflowed, and stale contributions
+    have to vanish.  Prompt tiles (split and unsplit) and generation rows.  A peaked softmax
+    returns single V rows, values up to about 4.5 where one bf16 step is 0.03: the absolute
+    bound scales with the largest expected output, the relative one stays as it is."""
+    ql, ctx = [700, 300, 1, 1, 130], [900, 300, 500, 64, 2000]
+    b = W.make_batch(f"steep-{scale}-{D}", 91, 4, D, 16, sum((c + 15) // 16 for c in ctx) + 3, ql, ctx)
+    ref, _, _ = oracle_run(b, scale=scale)
+    for opts in ({}, {"MPA_OPT_PP_SPLIT_TOKENS": 256, "MPA_OPT_TG_SPLIT_BLOCKS": 4}):
+        out, _, _ = gpu_run(ctx_for(mpa, b, **opts), b, scale=scale)
+        assert_close(out, ref, f"{b.name} {opts}", abs_scale=max(1.0, float(np.abs(ref).max())))
+
+
 def test_empty_batch_is_a_noop(mpa):
     c = mpa.Context(4, 64)
     lib = mpa.load()
