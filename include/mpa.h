@@ -69,8 +69,13 @@ typedef struct {
 enum {
     MPA_OPT_TG_SPLIT_BLOCKS = 1, /* KV blocks per generation-row work item; 0 = automatic     */
     MPA_OPT_PP_SPLIT_TOKENS = 2, /* keys per prompt-tile work item (multiple of 64); 0 = auto */
-    MPA_OPT_PP_ROWSTREAM = 3     /* 1 = run prompt rows through the row-streaming body
+    MPA_OPT_PP_ROWSTREAM = 3,    /* 1 = run prompt rows through the row-streaming body
                                     (slow; cross-check of the matrix-core body)               */
+    MPA_OPT_PP_RESIDENT_WGS = 4, /* work-groups that share the prompt-tile work (each takes
+                                    every n-th unit); 0 = automatic                           */
+    MPA_OPT_PP_TEAM_MIN_STEPS = 5 /* shortest key range, in 64-key steps, whose query tiles keep
+                                    pace with each other to share K/V through L2; 0 = automatic,
+                                    a huge value switches pacing off                          */
 };
 
 /* Create a context for one cache geometry.  Validates cfg; makes no HIP call.

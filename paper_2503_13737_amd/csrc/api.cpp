@@ -132,6 +132,14 @@ int mpa_set_option(mpa_ctx *ctx, int32_t option, int64_t value)
     case MPA_OPT_TG_SPLIT_BLOCKS: ctx->opt.tg_split_blocks = value; return MPA_OK;
     case MPA_OPT_PP_SPLIT_TOKENS: ctx->opt.pp_split_tokens = value; return MPA_OK;
     case MPA_OPT_PP_ROWSTREAM: ctx->opt.pp_rowstream = value ? 1 : 0; return MPA_OK;
+    case MPA_OPT_PP_RESIDENT_WGS:
+        if (value < 0) return MPA_ERR_INVALID_ARG;
+        ctx->opt.pp_resident_wgs = value;
+        return MPA_OK;
+    case MPA_OPT_PP_TEAM_MIN_STEPS:
+        if (value < 0) return MPA_ERR_INVALID_ARG;
+        ctx->opt.pp_team_min_steps = value;
+        return MPA_OK;
     default: return MPA_ERR_INVALID_ARG;
     }
 }
@@ -225,7 +233,7 @@ int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache, 
     };
 
     // stage the work list in pinned memory and copy it into the workspace on the stream
-    const size_t list_bytes = plan.off_acc;  // items + merge rows, padded
+    const size_t list_bytes = plan.off_acc;  // items, merge rows, teams, progress words; padded
     Staging &st = ctx->staging[ctx->next_slot];
     ctx->next_slot = (ctx->next_slot + 1) % kStagingSlots;
     hipError_t e;
@@ -246,6 +254,8 @@ int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache, 
     char *h = static_cast<char *>(st.host);
     std::memcpy(h + plan.off_items, plan.items.data(), plan.items.size() * sizeof(WorkItem));
     std::memcpy(h + plan.off_merge, plan.merge.data(), plan.merge.size() * sizeof(MergeRow));
+    std::memcpy(h + plan.off_teams, plan.teams.data(), plan.teams.size() * sizeof(TeamRef));
+    std::memset(h + plan.off_progress, 0xFF, (size_t)plan.progress_words * sizeof(uint32_t));  // kNotRunning
     hipStream_t s = (hipStream_t)stream;
     if ((e = hipMemcpyAsync(workspace, h, list_bytes, hipMemcpyHostToDevice, s)) != hipSuccess)
         return fail(e);
@@ -268,14 +278,17 @@ int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache, 
     p.items = reinterpret_cast<const WorkItem *>(ws + plan.off_items);
     p.n_tile_items = plan.n_tile_items;
     p.n_row_items = plan.n_row_items;
+    p.n_tile_wgs = plan.n_tile_wgs;
     p.part_acc = reinterpret_cast<float *>(ws + plan.off_acc);
     p.part_ml = reinterpret_cast<float *>(ws + plan.off_ml);
     p.merge = reinterpret_cast<const MergeRow *>(ws + plan.off_merge);
     p.n_merge = (int32_t)plan.merge.size();
+    p.teams = reinterpret_cast<const TeamRef *>(ws + plan.off_teams);
+    p.progress = reinterpret_cast<uint32_t *>(ws + plan.off_progress);
 
     const bool prof = (size_t)(2 * ctx->prof_used + 1) < ctx->prof_events.size();
     if (prof && (e = hipEventRecord(ctx->prof_events[2 * ctx->prof_used], s)) != hipSuccess) return fail(e);
-    int he = launch_attention(p, ctx->cfg.head_dim, stream);
+    int he = launch_attention(p, ctx->cfg.head_dim, true, stream);
     if (he != 0) return fail((hipError_t)he);
     if (prof) {
         if ((e = hipEventRecord(ctx->prof_events[2 * ctx->prof_used + 1], s)) != hipSuccess) return fail(e);

@@ -81,6 +81,8 @@ kv_append_kernel(const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_ne
 // tokens and accumulates p*v for its 8 elements, so the main loop has no traffic across
 // groups.  The groups are combined once at the end.
 // ------------------------------------------------------------------------------------------
+constexpr int kRowSets = 3;   // register sets of a row-streaming wavefront
+
 template <int D>
 struct RowCfg {
     static constexpr int LPR = D / 8;             // lanes per token row
@@ -162,7 +164,7 @@ __device__ __forceinline__ void consume(const KvRegs<D> &r, const float (&qf)[8]
     m = m_new;
 }
 
-template <int D>
+template <int D, int NS>
 __device__ __forceinline__ void row_body(const AttnParams &p, const WorkItem &it, int head, int lane)
 {
     using C = RowCfg<D>;
@@ -199,20 +201,19 @@ __device__ __forceinline__ void row_body(const AttnParams &p, const WorkItem &it
             if (tok0 + kBlockSize <= limit) consume<D, false>(r, qf, m, l, acc, tok0, limit, sub);
             else consume<D, true>(r, qf, m, l, acc, tok0, limit, sub);
         };
-        // three register sets rotate: two blocks (16 KiB) are in flight while one is consumed
-        KvRegs<D> r0, r1, r2;
-        issue_loads<D>(r0, p.k_cache, p.v_cache, blk_of(0), HK, kv_head, lane);
-        if (n > 1) issue_loads<D>(r1, p.k_cache, p.v_cache, blk_of(1), HK, kv_head, lane);
-        for (int j = 0; j < n; j += 3) {
-            if (j + 2 < n) issue_loads<D>(r2, p.k_cache, p.v_cache, blk_of(j + 2), HK, kv_head, lane);
-            step(r0, j);
-            if (j + 1 < n) {
-                if (j + 3 < n) issue_loads<D>(r0, p.k_cache, p.v_cache, blk_of(j + 3), HK, kv_head, lane);
-                step(r1, j + 1);
-            }
-            if (j + 2 < n) {
-                if (j + 4 < n) issue_loads<D>(r1, p.k_cache, p.v_cache, blk_of(j + 4), HK, kv_head, lane);
-                step(r2, j + 2);
+        // NS register sets rotate: NS-1 blocks (8 KiB each at D=128) are in flight while one is consumed
+        KvRegs<D> r[NS];
+#pragma unroll
+        for (int s = 0; s < NS - 1; ++s)
+            if (s < n) issue_loads<D>(r[s], p.k_cache, p.v_cache, blk_of(s), HK, kv_head, lane);
+        for (int j = 0; j < n; j += NS) {
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                if (j + s < n) {
+                    if (j + s + NS - 1 < n)
+                        issue_loads<D>(r[(s + NS - 1) % NS], p.k_cache, p.v_cache, blk_of(j + s + NS - 1), HK, kv_head, lane);
+                    step(r[s], j + s);
+                }
             }
         }
     }
@@ -296,42 +297,6 @@ struct TileCfg {
     static constexpr int VSW = CPR / 4;                 // 4 for D = 128, 2 for D = 64
 };
 
-// Wavefront `wave` brings KV block `blk` (keys wave*16 .. wave*16+15 of the 64-key tile) of both
-// operands from HBM straight into LDS (global_load_lds_dwordx4: lane l's 16 bytes land at
-// base + 16*l, no registers involved, nothing is waited for here).  Lane l of load i serves row
-// i*RPL + l/CPR of the block at chunk position l % CPR, so it fetches chunk (l % CPR) ^ swz(row).
-// keys_valid counts the keys of the tile that lie inside the item's range: rows at or past it are
-// not loaded; the V rows among them are zeroed instead (their scores are masked, but 0 * NaN
-// would poison the PV product), the K rows may hold anything.
-template <int D>
-__device__ __forceinline__ void tile_load(const AttnParams &p, int32_t blk, int head, char *lds_k, char *lds_v,
-                                          int wave, int lane, int32_t keys_valid)
-{
-    using C = TileCfg<D>;
-    typedef const __attribute__((address_space(1))) void *gptr;
-    typedef __attribute__((address_space(3))) void *lptr;
-    const int pos = lane % C::CPR;
-    const int r_in = lane / C::CPR;
-    const size_t tile = ((size_t)(blk < 0 ? 0 : blk) * p.kv_heads + head / p.group) * (kBlockSize * D);
-    const char *gk = reinterpret_cast<const char *>(p.k_cache + tile);
-    const char *gv = reinterpret_cast<const char *>(p.v_cache + tile);
-#pragma unroll
-    for (int i = 0; i < C::NL; ++i) {
-        const int row_b = i * C::RPL + r_in;            // row inside the block
-        const int row = wave * kBlockSize + row_b;      // row inside the tile
-        const int ck = pos ^ (row & (C::CPR - 1));
-        const int cv = pos ^ (C::VSW * (row & 3));
-        char *dk = lds_k + (wave * kBlockSize + i * C::RPL) * C::ROW;   // wave-uniform destinations
-        char *dv = lds_v + (wave * kBlockSize + i * C::RPL) * C::ROW;
-        if (blk >= 0 && row < keys_valid) {
-            __builtin_amdgcn_global_load_lds((gptr)(gk + row_b * C::ROW + ck * 16), (lptr)dk, 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((gptr)(gv + row_b * C::ROW + cv * 16), (lptr)dv, 16, 0, 0);
-        } else {
-            *reinterpret_cast<u32x4 *>(dv + lane * 16) = u32x4{0u, 0u, 0u, 0u};
-        }
-    }
-}
-
 // Everything a wavefront needs to issue its share of the next step's loads from inside
 // tile_compute.  Only gk/gv change from step to step, and they are wavefront-uniform, so the
 // loads address memory as scalar base + per-lane 32-bit offset and the loop spends no vector
@@ -357,6 +322,32 @@ __device__ __forceinline__ void load_to_lds_16(const char *base, uint32_t off, u
                  : "m0");
 }
 __device__ __forceinline__ void wait_loads_to_lds() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Wavefront `wave` brings its KV block (keys wave*16 .. wave*16+15 of the 64-key tile, block base
+// in n.gk / n.gv) of both operands into LDS buffer `bufi`: NL loads per operand, lane l of load i
+// serving row i*RPL + l/CPR of the block at chunk position l % CPR (the swizzles are in
+// n.koff / n.voff).  keys_valid counts the keys of the tile that lie inside the item's range:
+// rows at or past it (all rows if !have_block) are not loaded; the V rows among them are zeroed
+// instead (their scores are masked, but 0 * NaN would poison the PV product), the K rows may hold
+// anything.  Nothing is waited for here.
+template <int D>
+__device__ __forceinline__ void tile_load(const TileNext<D> &n, int bufi, bool have_block, int32_t keys_valid,
+                                          int wave, int lane)
+{
+    using C = TileCfg<D>;
+    typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
+#pragma unroll
+    for (int i = 0; i < C::NL; ++i) {
+        const int row = wave * kBlockSize + i * C::RPL + lane / C::CPR;   // row inside the tile
+        const uint32_t dst = n.lds_w + bufi * (C::K_BYTES + C::V_BYTES) + i * C::RPL * C::ROW;
+        if (have_block && row < keys_valid) {
+            load_to_lds_16(n.gk, n.koff[i], dst);
+            load_to_lds_16(n.gv, n.voff[i], dst + C::K_BYTES);
+        } else {
+            *reinterpret_cast<lds_u32x4 *>(static_cast<uintptr_t>(dst + C::K_BYTES + lane * 16)) = u32x4{0u, 0u, 0u, 0u};
+        }
+    }
+}
 
 // The V operand is read with hand-placed instructions and waits.  The compiler makes every LDS read
 // it knows about wait for all outstanding direct-to-LDS loads, which would stall each step half
@@ -521,12 +512,10 @@ __device__ __forceinline__ void tile_compute(const uint32_t (&kaddr)[TileCfg<D>:
         l += lh;
     };
 
-    // ---- all K fragments of the step: half 0 first
+    // ---- K fragments of half 0 (those of half 1 follow once these registers are being consumed)
     u32x4 kf[2][C::KS];
 #pragma unroll
     for (int ks = 0; ks < C::KS; ++ks) kf[0][ks] = lds_read_b128<KB0>(kaddr[ks]);
-#pragma unroll
-    for (int ks = 0; ks < C::KS; ++ks) kf[1][ks] = lds_read_b128<KB0 + 32 * C::ROW>(kaddr[ks]);
 
     // ---- S0 = K0 Q^T (keys 0..31), with the next step's loads between the instructions
     f32x16 s0, s1;
@@ -534,17 +523,19 @@ __device__ __forceinline__ void tile_compute(const uint32_t (&kaddr)[TileCfg<D>:
     for (int v = 0; v < 16; ++v) s0[v] = s1[v] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < C::KS; ++ks) {
-        if (ks == 0) k_wait<2 * C::KS - 1>(kf[0][0]);
-        else if (ks == 1) k_wait<2 * C::KS - 2>(kf[0][1]);
-        else if (ks == 2) k_wait<2 * C::KS - 3>(kf[0][2]);
-        else if (ks == 3) k_wait<2 * C::KS - 4>(kf[0][3]);
-        else if (ks == 4) k_wait<2 * C::KS - 5>(kf[0][4 % C::KS]);
-        else if (ks == 5) k_wait<2 * C::KS - 6>(kf[0][5 % C::KS]);
-        else if (ks == 6) k_wait<2 * C::KS - 7>(kf[0][6 % C::KS]);
-        else k_wait<2 * C::KS - 8>(kf[0][7 % C::KS]);
+        if (ks == 0) k_wait<C::KS - 1>(kf[0][0]);
+        else if (ks == 1) k_wait<C::KS - 2>(kf[0][1]);
+        else if (ks == 2) k_wait<C::KS - 3>(kf[0][2]);
+        else if (ks == 3) k_wait<C::KS - 4>(kf[0][3]);
+        else if (ks == 4) k_wait<(C::KS - 5 < 0 ? 0 : C::KS - 5)>(kf[0][4 % C::KS]);
+        else if (ks == 5) k_wait<(C::KS - 6 < 0 ? 0 : C::KS - 6)>(kf[0][5 % C::KS]);
+        else if (ks == 6) k_wait<(C::KS - 7 < 0 ? 0 : C::KS - 7)>(kf[0][6 % C::KS]);
+        else k_wait<0>(kf[0][7 % C::KS]);
         s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[0][ks]), qf[ks], s0, 0, 0, 0);
         if (LOAD_NEXT && ks % (C::KS / C::NL) == 0) load_part(ks / (C::KS / C::NL));
     }
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks) kf[1][ks] = lds_read_b128<KB0 + 32 * C::ROW>(kaddr[ks]);
     VGroup<C::DB> g0, g1, g2, g3;
     v_issue<D, 0, BUFI>(g0, vaddr);
     if (masked) mask_half(s0, 0);
@@ -590,8 +581,29 @@ __device__ __forceinline__ void tile_compute(const uint32_t (&kaddr)[TileCfg<D>:
     pv_group<D>(o, g3, pf1[1]);
 }
 
+// Pacing of a team (see TeamRef): every kPaceEvery steps wavefront 0 publishes the work-group's
+// progress and reads the team's; a member more than kPaceGap steps ahead of a running team mate
+// that is still within kPaceFar steps (pacing keeps a bunch together, it does not wait for one
+// that started later or fell far behind: the wait would cost more than the shared fetches save) pauses
+// for one to three steps' time, the longer the further ahead it is -- a bounded pause, so a mate
+// that never advances (not resident, or stuck behind us in a queue) costs time, not progress.
+// The other wavefronts are held by the step's barrier.
+constexpr int kPaceEvery = 4;
+constexpr uint32_t kPaceGap = 6;
+constexpr uint32_t kPaceFar = 14;
+
+__device__ __forceinline__ uint32_t progress_load(const uint32_t *w)
+{
+    return __hip_atomic_load(w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void progress_store(uint32_t *w, uint32_t v)
+{
+    __hip_atomic_store(w, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 template <int D>
-__device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &it, int head, char *lds)
+__device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &it, const TeamRef &team, int head,
+                                          char *lds)
 {
     using C = TileCfg<D>;
     constexpr int BUF = C::K_BYTES + C::V_BYTES;
@@ -633,6 +645,9 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
     };
     int32_t entries = load_entries(0);
 
+    uint32_t *const pace = team.base >= 0 ? p.progress + team.base + (size_t)head * team.stride : nullptr;
+    if (pace && threadIdx.x == 0) progress_store(pace + team.member, 0u);
+
     auto step_block = [&](int32_t step) {
         if ((step & 63) == 0 && step > 0) entries = load_entries(step);
         return __builtin_amdgcn_readlane(entries, step & 63);
@@ -670,28 +685,52 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
     // other buffer.  That buffer was last read in step s-1, which every wavefront has left, and the
     // barrier at the end of step s (which waits for this wavefront's loads first) publishes it.
     // The loop is written out for both buffers so that the buffer is an instruction offset.
-    tile_load<D>(p, step_block(0), head, lds, lds + C::K_BYTES, wave, lane, it.kv_end - it.kv_begin);
+    auto point_at = [&](int32_t blk) {   // the wavefront's block of the next load
+        const size_t tile = ((size_t)(blk < 0 ? 0 : blk) * p.kv_heads + head / p.group) * (kBlockSize * D);
+        next.gk = reinterpret_cast<const char *>(p.k_cache + tile);
+        next.gv = reinterpret_cast<const char *>(p.v_cache + tile);
+    };
+    {
+        const int32_t blk0 = step_block(0);
+        point_at(blk0);
+        tile_load<D>(next, 0, blk0 >= 0, it.kv_end - it.kv_begin, wave, lane);
+    }
+    wait_loads_to_lds();
     __syncthreads();
     auto do_step = [&](int32_t step, auto bufi) {
         constexpr int BUFI = decltype(bufi)::value;
         const int32_t k0 = it.kv_begin + step * kKvTile;
-        char *nbuf = lds + (BUFI ^ 1) * BUF;
         const bool more = step + 1 < nsteps;
         const int32_t blk_n = more ? step_block(step + 1) : -1;
         const int32_t keys_n = it.kv_end - (k0 + kKvTile);
         // otherwise every key of the step is above all rows of this wavefront
         const bool active = k0 <= wave_last_pos;
         const bool masked = k0 + kKvTile - 1 > wave_first_pos;
+        const bool pace_now = pace && (step % kPaceEvery) == kPaceEvery - 1;   // uniform
+        uint32_t mates = kNotRunning;
+        if (pace_now && wave == 0) {
+            if (lane == 0) progress_store(pace + team.member, (uint32_t)step + 1u);
+            if (lane < team.size) mates = progress_load(pace + lane);
+        }
+        if (more) point_at(blk_n);
         if (active && blk_n >= 0 && keys_n >= kKvTile) {
-            const size_t tile = ((size_t)blk_n * p.kv_heads + head / p.group) * (kBlockSize * D);
-            next.gk = reinterpret_cast<const char *>(p.k_cache + tile);
-            next.gv = reinterpret_cast<const char *>(p.v_cache + tile);
             tile_compute<D, true, BUFI>(kaddr, vaddr, qf, o, m, l, c2, k0, pos, half, masked, next);
         } else {
-            if (more) tile_load<D>(p, blk_n, head, nbuf, nbuf + C::K_BYTES, wave, lane, keys_n);
+            if (more) tile_load<D>(next, BUFI ^ 1, blk_n >= 0, keys_n, wave, lane);
             if (active) tile_compute<D, false, BUFI>(kaddr, vaddr, qf, o, m, l, c2, k0, pos, half, masked, next);
         }
         wait_loads_to_lds();
+        if (pace_now && wave == 0) {
+            asm volatile("" : "+v"(mates));   // use it only here, where all loads have landed anyway
+            const uint32_t mine = (uint32_t)step + 1u;
+            const uint32_t ahead = (mates != kNotRunning && mates < mine && mates + kPaceFar >= mine) ? mine - mates : 0u;
+            // pause in proportion to the lead: about one step's time (s_sleep counts in units of 64
+            // cycles) for each kPaceGap/2 steps beyond the gap; straight-line code on purpose (a
+            // loop here costs the register allocator of the whole kernel 20 registers)
+            if (__builtin_amdgcn_ballot_w64(ahead > kPaceGap) != 0) __builtin_amdgcn_s_sleep(48);
+            if (__builtin_amdgcn_ballot_w64(ahead > kPaceGap + kPaceGap / 2) != 0) __builtin_amdgcn_s_sleep(48);
+            if (__builtin_amdgcn_ballot_w64(ahead > 2 * kPaceGap) != 0) __builtin_amdgcn_s_sleep(48);
+        }
         __syncthreads();
     };
     for (int32_t step = 0; step < nsteps; step += 2) {
@@ -699,29 +738,39 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
         if (step + 1 < nsteps) do_step(step + 1, std::integral_constant<int, 1>());
     }
 
+    if (pace && threadIdx.x == 0) progress_store(pace + team.member, kNotRunning);
+
     const float l_tot = l + __shfl_xor(l, 32);
-    if (r_tile < it.q_rows) {
-        if (it.part_row < 0) {
-            const float inv = 1.f / l_tot;
-            uint16_t *orow = p.out + ((size_t)(it.q_row0 + r_tile) * H + head) * D;
+    {
+        // The lane's row and output addresses are worked out afresh from the thread index (made opaque,
+        // so that nothing computed before the loop is kept alive through it for this).
+        uint32_t tid = threadIdx.x;
+        asm volatile("" : "+v"(tid));
+        const int half = (tid >> 5) & 1;
+        const int r_tile = (int)(tid >> 6) * 32 + (int)(tid & 31);
+        if (r_tile < it.q_rows) {
+            if (it.part_row < 0) {
+                const float inv = 1.f / l_tot;
+                uint16_t *orow = p.out + ((size_t)(it.q_row0 + r_tile) * H + head) * D;
 #pragma unroll
-            for (int db = 0; db < C::DB; ++db)
+                for (int db = 0; db < C::DB; ++db)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    u32x2 w = {pack_bf16(o[db][4 * g] * inv, o[db][4 * g + 1] * inv),
-                               pack_bf16(o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv)};
-                    *reinterpret_cast<u32x2 *>(orow + db * 32 + g * 8 + half * 4) = w;
-                }
-        } else {
-            const size_t prow = (size_t)(it.part_row + r_tile) * H + head;
-            float *arow = p.part_acc + prow * D;
+                    for (int g = 0; g < 4; ++g) {
+                        u32x2 w = {pack_bf16(o[db][4 * g] * inv, o[db][4 * g + 1] * inv),
+                                   pack_bf16(o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv)};
+                        *reinterpret_cast<u32x2 *>(orow + db * 32 + g * 8 + half * 4) = w;
+                    }
+            } else {
+                const size_t prow = (size_t)(it.part_row + r_tile) * H + head;
+                float *arow = p.part_acc + prow * D;
 #pragma unroll
-            for (int db = 0; db < C::DB; ++db)
+                for (int db = 0; db < C::DB; ++db)
 #pragma unroll
-                for (int g = 0; g < 4; ++g)
-                    *reinterpret_cast<float4 *>(arow + db * 32 + g * 8 + half * 4) =
-                        make_float4(o[db][4 * g], o[db][4 * g + 1], o[db][4 * g + 2], o[db][4 * g + 3]);
-            if (half == 0) *reinterpret_cast<float2 *>(p.part_ml + prow * 2) = make_float2(m * c2, l_tot);
+                    for (int g = 0; g < 4; ++g)
+                        *reinterpret_cast<float4 *>(arow + db * 32 + g * 8 + half * 4) =
+                            make_float4(o[db][4 * g], o[db][4 * g + 1], o[db][4 * g + 2], o[db][4 * g + 3]);
+                if (half == 0) *reinterpret_cast<float2 *>(p.part_ml + prow * 2) = make_float2(m * c2, l_tot);
+            }
         }
     }
 }
@@ -752,13 +801,26 @@ attention_kernel(const AttnParams p)
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int H = p.heads;
-    const int64_t n_tile_wg = (int64_t)p.n_tile_items * H;
+    const int64_t n_tile_wg = p.n_tile_wgs;
     if ((int64_t)blockIdx.x < n_tile_wg) {
+        // Tile units (item, head) are dealt round-robin to the tile work-groups.  With as many
+        // work-groups as units each takes one; with fewer (mixed batches: half of the resident
+        // slots, so that generation rows stream through the other half from the start) each
+        // walks its share, longest units first.
         __shared__ __attribute__((aligned(16))) char lds[2 * (TileCfg<D>::K_BYTES + TileCfg<D>::V_BYTES)];
-        const int32_t item = (int32_t)(blockIdx.x / H);
-        const int head = (int)(blockIdx.x % H);
-        const WorkItem it = load_item(p.items + item);
-        tile_body<D>(p, it, head, lds);
+        const int64_t n_units = (int64_t)p.n_tile_items * H;
+        for (int64_t u = blockIdx.x; u < n_units; u += n_tile_wg) {
+            const int32_t item = (int32_t)(u / H);
+            const int head = (int)(u % H);
+            const WorkItem it = load_item(p.items + item);
+            TeamRef team;
+            team.base = __builtin_amdgcn_readfirstlane(p.teams[item].base);
+            team.member = __builtin_amdgcn_readfirstlane(p.teams[item].member);
+            team.size = __builtin_amdgcn_readfirstlane(p.teams[item].size);
+            team.stride = __builtin_amdgcn_readfirstlane(p.teams[item].stride);
+            tile_body<D>(p, it, team, head, lds);
+            __syncthreads();   // the next unit's first loads overwrite the tile buffers
+        }
         return;
     }
     const int hg = (H + kWaves - 1) / kWaves;
@@ -767,7 +829,24 @@ attention_kernel(const AttnParams p)
     const int head = (int)(idx % hg) * kWaves + wave;
     if (head >= H) return;
     const WorkItem it = load_item(p.items + item);
-    row_body<D>(p, it, head, lane);
+    row_body<D, kRowSets>(p, it, head, lane);
+}
+
+// Row items alone, for launches beside a tile-only launch of attention_kernel: without the tile
+// body's 254 registers several of these work-groups fit next to a resident tile work-group.
+template <int D>
+__global__ void __launch_bounds__(kThreads, 2)
+row_kernel(const AttnParams p)
+{
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int H = p.heads;
+    const int hg = (H + kWaves - 1) / kWaves;
+    const int32_t item = p.n_tile_items + (int32_t)(blockIdx.x / hg);
+    const int head = (int)(blockIdx.x % hg) * kWaves + wave;
+    if (head >= H) return;
+    const WorkItem it = load_item(p.items + item);
+    row_body<D, kRowSets>(p, it, head, lane);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -828,10 +907,23 @@ int launch_kv_append(const void *k_new, const void *v_new, const int64_t *slot_m
     return (int)hipGetLastError();
 }
 
-int launch_attention(const AttnParams &p, int32_t D, void *stream)
+int launch_rows(const AttnParams &p, int32_t D, void *stream)
 {
     const int hg = (p.heads + kWaves - 1) / kWaves;
-    const int64_t grid = (int64_t)p.n_tile_items * p.heads + (int64_t)p.n_row_items * hg;
+    const int64_t grid = (int64_t)p.n_row_items * hg;
+    if (grid == 0) return 0;
+    if (grid > 0x7FFFFFFF) return (int)hipErrorInvalidConfiguration;
+    if (D == 128)
+        hipLaunchKernelGGL(row_kernel<128>, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, p);
+    else
+        hipLaunchKernelGGL(row_kernel<64>, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, p);
+    return (int)hipGetLastError();
+}
+
+int launch_attention(const AttnParams &p, int32_t D, bool with_rows, void *stream)
+{
+    const int hg = (p.heads + kWaves - 1) / kWaves;
+    const int64_t grid = (int64_t)p.n_tile_wgs + (with_rows ? (int64_t)p.n_row_items * hg : 0);
     if (grid == 0) return 0;
     if (grid > 0x7FFFFFFF) return (int)hipErrorInvalidConfiguration;
     if (D == 128)

@@ -28,6 +28,20 @@ struct WorkItem {
 };
 static_assert(sizeof(WorkItem) == 32, "work item layout");
 
+// Tile items that walk the same keys of the same sequence (the q-tiles of a chunk over one key
+// range) form a team per head: while they stay within a few steps of each other one fetch of a
+// K/V tile from HBM serves all of them through L2.  Each member publishes the number of steps it
+// has finished in progress[base + head * stride + member] (kNotRunning before its first and after
+// its last step), and members that get ahead of a running team mate pause briefly.
+struct TeamRef {
+    int32_t base;      // first word of the team's [heads][stride] progress array, or -1: no team
+    int32_t member;    // this item's index in the team
+    int32_t size;      // members (<= kTeamMax)
+    int32_t stride;    // words per head
+};
+constexpr uint32_t kNotRunning = 0xFFFFFFFFu;
+constexpr int kTeamMax = 64;   // one progress word per lane of the checking wavefront
+
 // One output row whose keys were split over several items.
 struct MergeRow {
     int32_t out_row;   // row in out
@@ -44,17 +58,23 @@ struct PlanOptions {
     int64_t tg_split_blocks = 0;  // 0 = automatic
     int64_t pp_split_tokens = 0;  // 0 = automatic
     int64_t pp_rowstream = 0;
+    int64_t pp_resident_wgs = 0;  // 0 = automatic
+    int64_t pp_team_min_steps = 0; // shortest key range (in 64-key steps) whose q-tiles form a team; 0 = automatic
 };
 
 struct Plan {
     std::vector<WorkItem> items;  // tile items first, then row items; each group longest first
     std::vector<MergeRow> merge;
+    std::vector<TeamRef> teams;   // one per tile item
+    int64_t progress_words = 0;   // all set to kNotRunning before every launch
     int32_t n_tile_items = 0;
     int32_t n_row_items = 0;
+    int32_t n_tile_wgs = 0;       // work-groups that share the n_tile_items * heads tile units
     int64_t part_rows = 0;
 
     // workspace layout (byte offsets)
-    size_t off_items = 0, off_merge = 0, off_acc = 0, off_ml = 0, total_bytes = 0;
+    // [items | merge | teams | progress] are written by the host before every launch
+    size_t off_items = 0, off_merge = 0, off_teams = 0, off_progress = 0, off_acc = 0, off_ml = 0, total_bytes = 0;
 };
 
 // Returns MPA_OK or MPA_ERR_BAD_BATCH.
@@ -77,16 +97,22 @@ struct AttnParams {
     const WorkItem *items;
     int32_t n_tile_items;
     int32_t n_row_items;
+    int32_t n_tile_wgs;  // the first n_tile_wgs work-groups take tile units wg, wg + n_tile_wgs, ...
     float *part_acc;  // [part_rows, H, D]
     float *part_ml;   // [part_rows, H, 2]  (running max in base-2 units, running sum)
     const MergeRow *merge;
     int32_t n_merge;
+    const TeamRef *teams;   // [n_tile_items]
+    uint32_t *progress;
 };
 
 // Kernel launchers (kernels.hip).  Return the raw hipError_t as int.
 int launch_kv_append(const void *k_new, const void *v_new, const int64_t *slot_map, int32_t T,
                      int32_t H, int32_t D, void *k_cache, void *v_cache, void *stream);
-int launch_attention(const AttnParams &p, int32_t D, void *stream);
+// attention_kernel over the tile work-groups and, if with_rows, the row items behind them.
+int launch_attention(const AttnParams &p, int32_t D, bool with_rows, void *stream);
+// row_kernel over the row items (for a launch beside launch_attention(..., false, ...)).
+int launch_rows(const AttnParams &p, int32_t D, void *stream);
 int launch_merge(const AttnParams &p, int32_t D, void *stream);
 
 }  // namespace mpa

@@ -28,6 +28,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 constexpr int64_t kRowItemTarget = 256 * 8 * 6;
 constexpr int64_t kMinRowSplitBlocks = 8;
 constexpr int64_t kMinTileSplitSteps = 8;   // 512 keys
+constexpr int64_t kTeamMinSteps = 16;       // shorter ranges do not drift apart far enough to matter
 
 int64_t auto_row_split_blocks(const PlanOptions &opt, int64_t total_blocks)
 {
@@ -43,48 +44,93 @@ int64_t auto_row_split_blocks(const PlanOptions &opt, int64_t total_blocks)
 // occupies one of the kTileSlots resident work-groups; generation rows keep the memory pipe busy
 // for `row_us` anyway), and the longest range within a few percent of the best score wins.
 constexpr int64_t kTileSlots = 512;      // 2 resident work-groups per compute unit
-constexpr double kStepUs = 1.4;          // one 64-key step of a 128-row tile, measured
-constexpr double kPieceOverheadSteps = 3.0;
+constexpr double kStepUs = 1.9;          // one 64-key step of a 128-row tile with the chip full, measured
+constexpr double kPieceOverheadSteps = 5.0;  // item and Q loads, first tile, partial result, its share of the merge
 constexpr double kRowBytesPerUs = 6.0e6; // generation rows stream at about 6 TB/s
 
-double tile_makespan_us(const std::vector<int64_t> &tile_steps, int64_t heads, int64_t len_steps)
+// Pieces of one candidate, longest first: (length in steps incl. overhead, how many).
+typedef std::vector<std::pair<double, int64_t>> PieceList;
+
+void pieces_of(const std::vector<int64_t> &tile_steps_desc, int64_t len_steps, PieceList *out)
 {
-    std::vector<double> pieces;
-    for (int64_t st : tile_steps) {
-        int64_t n = ceil_div(st, len_steps);
-        int64_t each = ceil_div(st, n);
-        for (int64_t i = 0; i < n; ++i) pieces.push_back((double)std::min(each, st - i * each) + kPieceOverheadSteps);
-    }
-    std::sort(pieces.begin(), pieces.end(), std::greater<double>());
-    // longest first onto the least loaded of kTileSlots slots; every piece H times
-    std::priority_queue<double, std::vector<double>, std::greater<double>> slots;
-    for (int64_t i = 0; i < kTileSlots; ++i) slots.push(0.0);
-    double makespan = 0.0;
-    for (double pc : pieces)
-        for (int64_t h = 0; h < heads; ++h) {
-            double t = slots.top() + pc;
-            slots.pop();
-            slots.push(t);
-            makespan = std::max(makespan, t);
+    out->clear();
+    PieceList tails;
+    for (int64_t st : tile_steps_desc) {   // descending, so the full-length pieces come out sorted
+        const int64_t n = ceil_div(st, len_steps);
+        const int64_t each = ceil_div(st, n);
+        const int64_t last = st - (n - 1) * each;
+        const int64_t n_full = last == each ? n : n - 1;
+        if (n_full > 0) {
+            if (!out->empty() && out->back().first == (double)each + kPieceOverheadSteps) out->back().second += n_full;
+            else out->push_back({(double)each + kPieceOverheadSteps, n_full});
         }
-    return makespan * kStepUs;
+        if (last != each) tails.push_back({(double)last + kPieceOverheadSteps, 1});
+    }
+    // `each` shrinks with st only up to rounding (ceil(st/n) with n growing): restore the order
+    out->insert(out->end(), tails.begin(), tails.end());
+    std::sort(out->begin(), out->end(), [](const std::pair<double, int64_t> &a, const std::pair<double, int64_t> &b) {
+        return a.first > b.first;
+    });
 }
 
-int64_t auto_tile_split_tokens(const PlanOptions &opt, const std::vector<int64_t> &tile_steps, double row_us)
+// Estimate of the launch's length for one candidate.  Every piece exists once per head and
+// occupies one of kTileSlots resident work-groups.  Longest-first list scheduling of nearly
+// equal pieces proceeds in rounds of kTileSlots pieces, and a round lasts as long as its longest
+// piece: the estimate is the sum of the round leaders (exact for equal pieces, an upper bound of
+// the greedy schedule otherwise) but never less than the mean load.  O(pieces), no simulation:
+// the planner runs on the host in front of every launch.
+double tile_makespan_us(const PieceList &pieces, int64_t heads)
+{
+    double sum = 0.0, rounds = 0.0;
+    int64_t placed = 0;   // pieces (x heads) placed so far
+    for (const auto &pc : pieces) {
+        const int64_t n = pc.second * heads;
+        sum += pc.first * (double)n;
+        // rounds that start inside this run of equal pieces: at positions that are multiples of kTileSlots
+        const int64_t first = ceil_div(placed, kTileSlots), last = ceil_div(placed + n, kTileSlots);
+        rounds += pc.first * (double)(last - first);
+        placed += n;
+    }
+    return std::max(rounds, sum / (double)kTileSlots) * kStepUs;
+}
+
+int64_t auto_tile_split_tokens(const PlanOptions &opt, std::vector<int64_t> tile_steps, double row_us)
 {
     if (opt.pp_split_tokens > 0) return ceil_div(opt.pp_split_tokens, kKvTile) * kKvTile;
     if (tile_steps.empty()) return kKvTile;
-    const int64_t longest = *std::max_element(tile_steps.begin(), tile_steps.end());
+    std::sort(tile_steps.begin(), tile_steps.end(), std::greater<int64_t>());
+    const int64_t longest = tile_steps.front();
+    // Candidate range lengths: the longest tile cut into 1, 2, 3, 4, 6, 8, 12, 16, ... ranges
+    // (steps of about 1.4 x), and the shortest lengths that still fit all pieces into exactly
+    // 1, 2, 3, 4, 6, 8 rounds of resident work-groups -- the launch's length jumps there.
     std::vector<int64_t> cands;
-    for (int64_t n = 1; n <= 64; ++n) {
-        int64_t len = std::max<int64_t>(ceil_div(longest, n), kMinTileSplitSteps);
-        if (cands.empty() || len < cands.back()) cands.push_back(len);
+    for (int64_t n = 1; n <= 64; n = (n < 4) ? n + 1 : ((n & (n - 1)) == 0 ? n + n / 2 : (n / 3) * 4)) {
+        const int64_t len = std::max<int64_t>(ceil_div(longest, n), kMinTileSplitSteps);
+        cands.push_back(len);
         if (len == kMinTileSplitSteps) break;
     }
+    auto pieces_at = [&](int64_t len) {
+        int64_t n = 0;
+        for (int64_t st : tile_steps) n += ceil_div(st, len);
+        return n * opt.heads;
+    };
+    for (int64_t rounds : {1, 2, 3, 4, 6, 8}) {
+        int64_t lo = kMinTileSplitSteps, hi = longest;   // smallest len with pieces_at(len) <= rounds * slots
+        if (pieces_at(hi) > rounds * kTileSlots) continue;
+        while (lo < hi) {
+            const int64_t mid = (lo + hi) / 2;
+            if (pieces_at(mid) <= rounds * kTileSlots) hi = mid; else lo = mid + 1;
+        }
+        cands.push_back(lo);
+    }
+    std::sort(cands.begin(), cands.end(), std::greater<int64_t>());
+    cands.erase(std::unique(cands.begin(), cands.end()), cands.end());
     std::vector<double> score(cands.size());
+    PieceList pieces;
     double best = 1e300;
     for (size_t i = 0; i < cands.size(); ++i) {
-        score[i] = std::max(tile_makespan_us(tile_steps, opt.heads, cands[i]), row_us);
+        pieces_of(tile_steps, cands[i], &pieces);
+        score[i] = std::max(tile_makespan_us(pieces, opt.heads), row_us);
         best = std::min(best, score[i]);
     }
     for (size_t i = 0; i < cands.size(); ++i)
@@ -99,6 +145,10 @@ void finish_layout(const PlanOptions &opt, Plan *p)
     off = align_up(off + p->items.size() * sizeof(WorkItem), 256);
     p->off_merge = off;
     off = align_up(off + p->merge.size() * sizeof(MergeRow), 256);
+    p->off_teams = off;
+    off = align_up(off + p->teams.size() * sizeof(TeamRef), 256);
+    p->off_progress = off;
+    off = align_up(off + (size_t)p->progress_words * sizeof(uint32_t), 256);
     p->off_acc = off;
     off = align_up(off + (size_t)p->part_rows * opt.heads * opt.head_dim * sizeof(float), 256);
     p->off_ml = off;
@@ -111,10 +161,12 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
 {
     plan->items.clear();
     plan->merge.clear();
+    plan->teams.clear();
+    plan->progress_words = 0;
     plan->part_rows = 0;
     if (S < 0) return MPA_ERR_BAD_BATCH;
     if (S == 0) {
-        plan->n_tile_items = plan->n_row_items = 0;
+        plan->n_tile_items = plan->n_row_items = plan->n_tile_wgs = 0;
         finish_layout(opt, plan);
         return MPA_OK;
     }
@@ -140,11 +192,11 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
 
     std::vector<WorkItem> tiles, rows;
     auto emit = [&](std::vector<WorkItem> &dst, int32_t kind, int32_t seq, int32_t q_row0,
-                    int32_t q_rows, int32_t q_pos0, int64_t split_len, int64_t granule) {
+                    int32_t q_rows, int32_t q_pos0, int64_t split_len, int64_t granule, bool fixed_len) {
         const int64_t kv_len = (int64_t)q_pos0 + q_rows;  // keys visible to the last row
         int64_t nsplit = ceil_div(kv_len, split_len);
-        // equal ranges, each a whole number of granules
-        int64_t len = ceil_div(ceil_div(kv_len, nsplit), granule) * granule;
+        // equal ranges, each a whole number of granules -- or the given length as it is
+        int64_t len = fixed_len ? split_len : ceil_div(ceil_div(kv_len, nsplit), granule) * granule;
         nsplit = ceil_div(kv_len, len);
         int32_t part0 = -1;
         if (nsplit > 1) {
@@ -175,11 +227,17 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
         int32_t prior = ctx[i] - q_len;
         if (q_len == 1 || opt.pp_rowstream) {
             for (int32_t j = 0; j < q_len; ++j)
-                emit(rows, kRowItem, i, cs[i] + j, 1, prior + j, row_split * kBlockSize, kBlockSize);
+                emit(rows, kRowItem, i, cs[i] + j, 1, prior + j, row_split * kBlockSize, kBlockSize, false);
         } else {
+            // All tiles of a chunk cut their keys at the same positions (equal ranges of the
+            // chunk's whole context), so that the tiles over one range walk the same K/V blocks
+            // from the same first key and can share them (see TeamRef); a tile simply has fewer
+            // ranges when its rows end earlier.
+            const int64_t n_seq = ceil_div((int64_t)ctx[i], tile_split);
+            const int64_t len_seq = ceil_div(ceil_div((int64_t)ctx[i], n_seq), kKvTile) * kKvTile;
             for (int32_t r0 = 0; r0 < q_len; r0 += kTileRows) {
                 int32_t nr = std::min<int32_t>(kTileRows, q_len - r0);
-                emit(tiles, kTileItem, i, cs[i] + r0, nr, prior + r0, tile_split, kKvTile);
+                emit(tiles, kTileItem, i, cs[i] + r0, nr, prior + r0, len_seq, kKvTile, true);
             }
         }
     }
@@ -193,19 +251,65 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
     // adjacent (one launch position apart per head, hence on the same XCD and resident together)
     // so that one tile's fetch serves the others from L2; groups go longest first.
     {
+        // emit() produced the tiles sequence by sequence, tile by tile, range by range
+        struct Key { int64_t group_cost; int32_t seq, kv_begin, q_row0; WorkItem w; };
         std::map<std::pair<int32_t, int32_t>, int64_t> group_cost;
         for (const WorkItem &w : tiles) group_cost[{w.seq, w.kv_begin}] += cost(w);
-        std::stable_sort(tiles.begin(), tiles.end(), [&](const WorkItem &a, const WorkItem &b) {
-            const std::pair<int32_t, int32_t> ka{a.seq, a.kv_begin}, kb{b.seq, b.kv_begin};
-            if (ka == kb) return a.q_row0 < b.q_row0;
-            const int64_t ca = group_cost[ka], cb = group_cost[kb];
-            if (ca != cb) return ca > cb;
-            return ka < kb;
+        std::vector<Key> keyed;
+        keyed.reserve(tiles.size());
+        for (const WorkItem &w : tiles) keyed.push_back(Key{group_cost[{w.seq, w.kv_begin}], w.seq, w.kv_begin, w.q_row0, w});
+        std::sort(keyed.begin(), keyed.end(), [](const Key &a, const Key &b) {
+            if (a.group_cost != b.group_cost) return a.group_cost > b.group_cost;
+            if (a.seq != b.seq) return a.seq < b.seq;
+            if (a.kv_begin != b.kv_begin) return a.kv_begin < b.kv_begin;
+            return a.q_row0 < b.q_row0;
         });
+        for (size_t i = 0; i < tiles.size(); ++i) tiles[i] = keyed[i].w;
     }
     std::stable_sort(rows.begin(), rows.end(), longer);
     plan->n_tile_items = (int32_t)tiles.size();
     plan->n_row_items = (int32_t)rows.size();
+    // Work-groups for the tile units.  Alone, every unit gets its own and the hardware deals them
+    // out as slots free up.  Next to a substantial amount of generation rows the tiles get three
+    // quarters of the resident slots and keep them for the whole launch, while the rows stream
+    // through the rest from the first microsecond: measured 8-10 % shorter launches on
+    // prompt-heavy mixed batches than tiles first, rows after (more is not to be had this way: a
+    // streaming wavefront that shares its SIMD with a matrix-core wavefront gets about a third of
+    // the issue slots it needs).
+    {
+        const int64_t units = (int64_t)tiles.size() * opt.heads;
+        int64_t steps = 0;
+        for (int64_t st : tile_steps) steps += st;
+        const double tile_us = (double)steps * opt.heads * kStepUs / (double)kTileSlots;
+        int64_t wgs = units;
+        if (opt.pp_resident_wgs > 0) wgs = std::min(units, opt.pp_resident_wgs);
+        else if (!rows.empty() && row_us > 0.15 * tile_us) wgs = std::min(units, kTileSlots * 3 / 4);
+        plan->n_tile_wgs = (int32_t)wgs;
+    }
+    // Teams: runs of adjacent tiles with the same (sequence, first key) -- see TeamRef.
+    // Pacing pays when the tiles' K/V fetches compete with the generation rows for HBM (measured:
+    // 2-5 % shorter launches on prompt-heavy mixed batches, 3-5 % longer ones on prompts alone,
+    // where the pauses cost more than the re-fetches), so teams exist in the shared-slot mode
+    // above, or when the option asks for them.
+    {
+        const int64_t min_steps = opt.pp_team_min_steps > 0 ? opt.pp_team_min_steps : kTeamMinSteps;
+        const bool want = opt.pp_team_min_steps > 0 || plan->n_tile_wgs < (int64_t)tiles.size() * opt.heads;
+        plan->teams.assign(tiles.size(), TeamRef{-1, 0, 1, 0});
+        for (size_t i = 0; want && i < tiles.size();) {
+            size_t j = i + 1;
+            while (j < tiles.size() && j - i < (size_t)kTeamMax && tiles[j].seq == tiles[i].seq &&
+                   tiles[j].kv_begin == tiles[i].kv_begin)
+                ++j;
+            const int64_t steps = ceil_div((int64_t)tiles[i].kv_end - tiles[i].kv_begin, kKvTile);
+            if (j - i >= 2 && steps >= min_steps) {
+                const int32_t size = (int32_t)(j - i), stride = (size + 15) / 16 * 16;
+                for (size_t k = i; k < j; ++k)
+                    plan->teams[k] = TeamRef{(int32_t)plan->progress_words, (int32_t)(k - i), size, stride};
+                plan->progress_words += (int64_t)stride * opt.heads;
+            }
+            i = j;
+        }
+    }
     plan->items = std::move(tiles);
     plan->items.insert(plan->items.end(), rows.begin(), rows.end());
     finish_layout(opt, plan);
@@ -233,6 +337,9 @@ size_t plan_bytes_upper_bound(const PlanOptions &opt, int64_t max_seqs, int64_t 
     size_t off = 0;
     off = align_up(off + (size_t)items * sizeof(WorkItem), 256);
     off = align_up(off + (size_t)merge_rows * sizeof(MergeRow), 256);
+    off = align_up(off + (size_t)n_tiles * tile_ns * sizeof(TeamRef), 256);
+    // a team of n tiles holds heads * round_up(n, 16) words; teams have at least two members
+    off = align_up(off + (size_t)n_tiles * tile_ns * opt.heads * 8 * sizeof(uint32_t), 256);
     off = align_up(off + (size_t)part_rows * opt.heads * opt.head_dim * sizeof(float), 256);
     off = align_up(off + (size_t)part_rows * opt.heads * 2 * sizeof(float), 256);
     return off;

@@ -66,6 +66,21 @@ def test_forced_tile_splits_agree(mpa, pp_split):
     assert_close(out, ref, f"pp_split={pp_split}")
 
 
+@pytest.mark.parametrize("resident", [1, 3, 7])
+@pytest.mark.parametrize("team_min_steps", [0, 1])
+def test_few_resident_tile_work_groups_and_pacing(mpa, resident, team_min_steps):
+    """A handful of work-groups walk all prompt-tile units one after the other (the launch mode of
+    prompt-heavy mixed batches), with and without the q-tiles of a range keeping pace with each
+    other: same results as one work-group per unit."""
+    ql, ctx = [600, 300, 1, 1, 1], [1500, 300, 700, 64, 2000]
+    b = W.make_batch("resident", 123, 4, 128, 16, sum((c + 15) // 16 for c in ctx) + 3, ql, ctx)
+    ref, _, _ = oracle_run(b)
+    for split in (0, 256):
+        out, _, _ = gpu_run(ctx_for(mpa, b, MPA_OPT_PP_RESIDENT_WGS=resident, MPA_OPT_PP_TEAM_MIN_STEPS=team_min_steps,
+                                    MPA_OPT_PP_SPLIT_TOKENS=split), b)
+        assert_close(out, ref, f"{b.name} resident={resident} pacing={team_min_steps} split={split}")
+
+
 def test_rowstream_body_on_prompt_rows(mpa):
     b = W.config1()
     ref, _, _ = oracle_run(b)

@@ -36,6 +36,45 @@ def test_random_batches_plan_invariants(seed):
     assert c.workspace_bytes(b.S, b.T, int(b.context_lens.max())) >= need
 
 
+def test_tiles_of_a_chunk_cut_their_keys_at_common_positions():
+    """All q-tiles of a chunk use the same range boundaries (multiples of one length), so the tiles
+    over one range start at the same key and can share its K/V; a tile has fewer ranges when its
+    rows end earlier."""
+    c = mpa.Context(8, 128)
+    for split in (0, 256, 1024):
+        c.set_option(mpa.MPA_OPT_PP_SPLIT_TOKENS, split)
+        cs, cl = np.array([0, 1000, 1300], dtype=np.int32), np.array([9000, 5000], dtype=np.int32)
+        items, counts = c.plan_describe(cs, cl)
+        tiles = items[: counts[0]]
+        for seq in (0, 1):
+            t = tiles[tiles[:, 0] == seq]
+            begins = np.unique(t[:, 4])
+            if len(begins) > 1:
+                step = begins[1] - begins[0]
+                assert step % 64 == 0 and (begins % step == 0).all()
+                full = t[t[:, 5] - t[:, 4] == step]
+                assert len(full) > 0 and ((t[:, 5] - t[:, 4]) <= step).all()
+            # every tile starts its first range at key 0 and its ranges are contiguous
+            for row0 in np.unique(t[:, 1]):
+                r = t[t[:, 1] == row0]
+                r = r[np.argsort(r[:, 4])]
+                assert r[0, 4] == 0 and (r[1:, 4] == r[:-1, 5]).all()
+
+
+def test_resident_and_pacing_options_do_not_change_the_work_list():
+    b = W.random_ragged(77, H=12, D=128, n_pp=2, n_tg=4, max_q=600, max_prior=4000, max_ctx=3000)
+    c = mpa.Context(12, 128)
+    base, counts0 = c.plan_describe(b.chunk_starts, b.context_lens)
+    for opt, val in ((mpa.MPA_OPT_PP_RESIDENT_WGS, 5), (mpa.MPA_OPT_PP_TEAM_MIN_STEPS, 1)):
+        c.set_option(opt, val)
+        items, counts = c.plan_describe(b.chunk_starts, b.context_lens)
+        assert np.array_equal(items, base) and np.array_equal(counts, counts0)
+        need = c.workspace_bytes_for_batch(b.chunk_starts, b.context_lens)
+        assert c.workspace_bytes(b.S, b.T, int(b.context_lens.max())) >= need
+    with pytest.raises(mpa.MpaError):
+        c.set_option(mpa.MPA_OPT_PP_RESIDENT_WGS, -1)
+
+
 def test_workspace_bound_is_monotone():
     c = mpa.Context(40, 128)
     a = c.workspace_bytes(64, 64, 2048)
