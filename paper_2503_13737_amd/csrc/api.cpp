@@ -288,7 +288,7 @@ int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache, 
 
     const bool prof = (size_t)(2 * ctx->prof_used + 1) < ctx->prof_events.size();
     if (prof && (e = hipEventRecord(ctx->prof_events[2 * ctx->prof_used], s)) != hipSuccess) return fail(e);
-    int he = launch_attention(p, ctx->cfg.head_dim, true, stream);
+    int he = launch_attention(p, ctx->cfg.head_dim, stream);
     if (he != 0) return fail((hipError_t)he);
     if (prof) {
         if ((e = hipEventRecord(ctx->prof_events[2 * ctx->prof_used + 1], s)) != hipSuccess) return fail(e);

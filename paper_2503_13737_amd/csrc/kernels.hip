@@ -257,13 +257,13 @@ __device__ __forceinline__ void row_body(const AttnParams &p, const WorkItem &it
 // Matrix-core body: one work-group (4 wavefronts), one head, a tile of up to 128 query rows
 // (32 per wavefront), a contiguous key range walked in steps of 64 keys.
 //
-// Per step the work-group stages K [64 keys][D] and V transposed [D][64 keys] in LDS.  Each
-// wavefront computes S^T = K Q^T with 32x32x16 bf16 MFMAs (A = K rows from LDS, B = Q^T from
-// registers), so a lane owns ONE query row (lane % 32) and 32 of the 64 keys: the row maximum
-// and sum are in-lane reductions plus one exchange with lane ^ 32.  The exponentials, packed to
-// bf16 in the very registers they were produced in, are the B operand of O^T += V^T P^T, whose
-// result again has the query row on the lane, so the running rescale needs no cross-lane
-// traffic either.
+// Per step the work-group holds K [64 keys][D] and V [64 keys][D] row-major in LDS, loaded
+// straight from HBM, two buffers.  Each wavefront computes S^T = K Q^T with 32x32x16 bf16 MFMAs
+// (A = K rows from LDS, B = Q^T from registers), so a lane owns ONE query row (lane % 32) and 32
+// of the 64 keys: row sums (and, when needed, row maxima) are in-lane reductions plus one
+// exchange with lane ^ 32.  The weights, packed to bf16 in the very registers they were produced
+// in, are the B operand of O^T += V^T P^T (A = V through the transposing LDS read), whose result
+// again has the query row on the lane, so the occasional rescale needs no cross-lane traffic.
 //
 // Register layouts of v_mfma_f32_32x32x16_bf16 (lane l, half = l / 32):
 //   A: row l % 32, k = 8*half .. 8*half+7        B: column l % 32, k = 8*half .. 8*half+7
@@ -606,7 +606,6 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
                                           char *lds)
 {
     using C = TileCfg<D>;
-    constexpr int BUF = C::K_BYTES + C::V_BYTES;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int half = lane >> 5;
@@ -832,23 +831,6 @@ attention_kernel(const AttnParams p)
     row_body<D, kRowSets>(p, it, head, lane);
 }
 
-// Row items alone, for launches beside a tile-only launch of attention_kernel: without the tile
-// body's 254 registers several of these work-groups fit next to a resident tile work-group.
-template <int D>
-__global__ void __launch_bounds__(kThreads, 2)
-row_kernel(const AttnParams p)
-{
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const int H = p.heads;
-    const int hg = (H + kWaves - 1) / kWaves;
-    const int32_t item = p.n_tile_items + (int32_t)(blockIdx.x / hg);
-    const int head = (int)(blockIdx.x % hg) * kWaves + wave;
-    if (head >= H) return;
-    const WorkItem it = load_item(p.items + item);
-    row_body<D, kRowSets>(p, it, head, lane);
-}
-
 // ------------------------------------------------------------------------------------------
 // Merge: one wavefront per (merge row, head).
 // ------------------------------------------------------------------------------------------
@@ -907,23 +889,10 @@ int launch_kv_append(const void *k_new, const void *v_new, const int64_t *slot_m
     return (int)hipGetLastError();
 }
 
-int launch_rows(const AttnParams &p, int32_t D, void *stream)
+int launch_attention(const AttnParams &p, int32_t D, void *stream)
 {
     const int hg = (p.heads + kWaves - 1) / kWaves;
-    const int64_t grid = (int64_t)p.n_row_items * hg;
-    if (grid == 0) return 0;
-    if (grid > 0x7FFFFFFF) return (int)hipErrorInvalidConfiguration;
-    if (D == 128)
-        hipLaunchKernelGGL(row_kernel<128>, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, p);
-    else
-        hipLaunchKernelGGL(row_kernel<64>, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, p);
-    return (int)hipGetLastError();
-}
-
-int launch_attention(const AttnParams &p, int32_t D, bool with_rows, void *stream)
-{
-    const int hg = (p.heads + kWaves - 1) / kWaves;
-    const int64_t grid = (int64_t)p.n_tile_wgs + (with_rows ? (int64_t)p.n_row_items * hg : 0);
+    const int64_t grid = (int64_t)p.n_tile_wgs + (int64_t)p.n_row_items * hg;
     if (grid == 0) return 0;
     if (grid > 0x7FFFFFFF) return (int)hipErrorInvalidConfiguration;
     if (D == 128)

@@ -109,10 +109,7 @@ struct AttnParams {
 // Kernel launchers (kernels.hip).  Return the raw hipError_t as int.
 int launch_kv_append(const void *k_new, const void *v_new, const int64_t *slot_map, int32_t T,
                      int32_t H, int32_t D, void *k_cache, void *v_cache, void *stream);
-// attention_kernel over the tile work-groups and, if with_rows, the row items behind them.
-int launch_attention(const AttnParams &p, int32_t D, bool with_rows, void *stream);
-// row_kernel over the row items (for a launch beside launch_attention(..., false, ...)).
-int launch_rows(const AttnParams &p, int32_t D, void *stream);
+int launch_attention(const AttnParams &p, int32_t D, void *stream);
 int launch_merge(const AttnParams &p, int32_t D, void *stream);
 
 }  // namespace mpa
