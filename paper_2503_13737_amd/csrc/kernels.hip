@@ -313,7 +313,9 @@ struct TileNext {
 // LDS at lds_dst + 16 * lane (lds_dst wavefront-uniform; the instruction takes it from M0).
 // Written by hand because the compiler's selection of this instruction always forms a 64-bit
 // address per lane.  It is invisible to the compiler's bookkeeping of outstanding memory
-// operations: whoever needs the data waits for vmcnt(0) explicitly.
+// operations: whoever needs the data waits for vmcnt(0) explicitly.  M0 is written and consumed
+// inside the statement and named as clobbered; nothing else in these kernels uses M0 (LDS
+// instructions of this architecture take none).
 __device__ __forceinline__ void load_to_lds_16(const char *base, uint32_t off, uint32_t lds_dst)
 {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
