@@ -71,6 +71,9 @@ class DeviceWorkload:
         self.block_table = torch.from_numpy(np.ascontiguousarray(b.block_table)).to(dev)
         self.out = torch.zeros((b.T, b.H, b.D), dtype=torch.int16, device=dev)
         self.ctx = mpa.Context(b.H, b.D, num_kv_heads=b.HK)
+        # every timed step plans its batch anew, as the first layer of a model iteration does
+        # (the library would otherwise reuse the work list of the identical previous call)
+        self.ctx.set_option(mpa.MPA_OPT_PLAN_CACHE, 0)
         self.ws = torch.empty(self.ctx.workspace_bytes_for_batch(b.chunk_starts, b.context_lens),
                               dtype=torch.uint8, device=dev)
 

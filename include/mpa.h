@@ -73,9 +73,13 @@ enum {
                                     (slow; cross-check of the matrix-core body)               */
     MPA_OPT_PP_RESIDENT_WGS = 4, /* work-groups that share the prompt-tile work (each takes
                                     every n-th unit); 0 = automatic                           */
-    MPA_OPT_PP_TEAM_MIN_STEPS = 5 /* shortest key range, in 64-key steps, whose query tiles keep
+    MPA_OPT_PP_TEAM_MIN_STEPS = 5, /* shortest key range, in 64-key steps, whose query tiles keep
                                     pace with each other to share K/V through L2; 0 = automatic,
                                     a huge value switches pacing off                          */
+    MPA_OPT_PLAN_CACHE = 6       /* 1 (default) = a call whose chunk_starts / context_lens equal
+                                    the previous call's reuses its work list (the layers of one
+                                    model iteration all present the same batch); 0 = plan anew
+                                    on every call                                             */
 };
 
 /* Create a context for one cache geometry.  Validates cfg; makes no HIP call.
@@ -172,7 +176,10 @@ int mpa_profile_read(mpa_ctx *ctx, float *ms, int32_t cap, int32_t *n_out);
  * Writes up to `cap` work items as 8 int32 each
  *   {seq, q_row0, q_rows, q_pos0, kv_begin, kv_end, part_row, kind}
  * and returns the total number of items (which may exceed cap), or a negative status.
- * counts (optional, 4 int32): {prompt-tile items, row items, merge rows, partial rows}.
+ * kind & 0xFF: 0 = a row for all heads on the streaming body, 1 = a tile of prompt rows for all
+ * heads on the matrix-core body, 2 = one generation row for the query heads of K/V head
+ * kind >> 8 on the matrix-core body (grouped K/V heads, group size >= 4).
+ * counts (optional, 4 int32): {matrix-core items, row items, merge rows, partial rows}.
  */
 int64_t mpa_plan_describe(const mpa_ctx *ctx, const int32_t *chunk_starts,
                           const int32_t *context_lens, int32_t num_seqs, int32_t *items,

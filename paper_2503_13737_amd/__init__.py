@@ -26,6 +26,7 @@ MPA_OPT_PP_SPLIT_TOKENS = 2
 MPA_OPT_PP_ROWSTREAM = 3
 MPA_OPT_PP_RESIDENT_WGS = 4
 MPA_OPT_PP_TEAM_MIN_STEPS = 5
+MPA_OPT_PLAN_CACHE = 6
 
 EXPORTS = [
     "mpa_create", "mpa_destroy", "mpa_set_option", "mpa_last_hip_error", "mpa_status_string",

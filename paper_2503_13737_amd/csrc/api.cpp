@@ -29,7 +29,11 @@ struct mpa_ctx {
     int last_hip = 0;
     Staging staging[kStagingSlots];
     int next_slot = 0;
-    Plan plan;  // reused between calls to keep its vectors' capacity
+    Plan plan;  // the plan of the last batch; reused as it is when the next batch is the same
+                // (all layers of one model iteration present the same batch)
+    std::vector<int32_t> plan_key;   // chunk_starts then context_lens of that batch
+    bool plan_valid = false;         // cleared by mpa_set_option
+    bool plan_cache = true;
     std::vector<hipEvent_t> prof_events;  // start/stop pairs
     int32_t prof_used = 0;                // pairs recorded in the current series
     std::mutex mu;
@@ -128,6 +132,7 @@ int mpa_set_option(mpa_ctx *ctx, int32_t option, int64_t value)
 {
     if (!ctx || value < 0) return MPA_ERR_INVALID_ARG;
     std::lock_guard<std::mutex> g(ctx->mu);
+    ctx->plan_valid = false;   // the cached plan was made under the old options
     switch (option) {
     case MPA_OPT_TG_SPLIT_BLOCKS: ctx->opt.tg_split_blocks = value; return MPA_OK;
     case MPA_OPT_PP_SPLIT_TOKENS: ctx->opt.pp_split_tokens = value; return MPA_OK;
@@ -136,6 +141,7 @@ int mpa_set_option(mpa_ctx *ctx, int32_t option, int64_t value)
         if (value < 0) return MPA_ERR_INVALID_ARG;
         ctx->opt.pp_resident_wgs = value;
         return MPA_OK;
+    case MPA_OPT_PLAN_CACHE: ctx->plan_cache = value != 0; return MPA_OK;
     case MPA_OPT_PP_TEAM_MIN_STEPS:
         if (value < 0) return MPA_ERR_INVALID_ARG;
         ctx->opt.pp_team_min_steps = value;
@@ -174,7 +180,7 @@ int64_t mpa_plan_describe(const mpa_ctx *ctx, const int32_t *chunk_starts,
     const int64_t n = (int64_t)p.items.size();
     if (cap > 0) std::memcpy(items, p.items.data(), (size_t)(n < cap ? n : cap) * sizeof(WorkItem));
     if (counts) {
-        counts[0] = p.n_tile_items;
+        counts[0] = p.n_tile_items + p.n_group_items;
         counts[1] = p.n_row_items;
         counts[2] = (int32_t)p.merge.size();
         counts[3] = (int32_t)p.part_rows;
@@ -218,8 +224,18 @@ int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache, 
 
     std::lock_guard<std::mutex> g(ctx->mu);
     Plan &plan = ctx->plan;
-    int rc = build_plan(ctx->opt, chunk_starts, context_lens, num_seqs, &plan);
-    if (rc != MPA_OK) return rc;
+    const size_t n_key = 2 * (size_t)num_seqs + 1;
+    const bool same = ctx->plan_cache && ctx->plan_valid && ctx->plan_key.size() == n_key &&
+                      std::memcmp(ctx->plan_key.data(), chunk_starts, ((size_t)num_seqs + 1) * sizeof(int32_t)) == 0 &&
+                      std::memcmp(ctx->plan_key.data() + num_seqs + 1, context_lens, (size_t)num_seqs * sizeof(int32_t)) == 0;
+    if (!same) {
+        ctx->plan_valid = false;
+        int rc = build_plan(ctx->opt, chunk_starts, context_lens, num_seqs, &plan);
+        if (rc != MPA_OK) return rc;
+        ctx->plan_key.assign(chunk_starts, chunk_starts + num_seqs + 1);
+        ctx->plan_key.insert(ctx->plan_key.end(), context_lens, context_lens + num_seqs);
+        ctx->plan_valid = true;
+    }
     if (chunk_starts[num_seqs] != num_tokens) return MPA_ERR_BAD_BATCH;
     for (int32_t i = 0; i < num_seqs; ++i)
         if ((int64_t)(context_lens[i] + kBlockSize - 1) / kBlockSize > block_table_stride)
@@ -277,6 +293,7 @@ int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache, 
     p.out = static_cast<uint16_t *>(out);
     p.items = reinterpret_cast<const WorkItem *>(ws + plan.off_items);
     p.n_tile_items = plan.n_tile_items;
+    p.n_group_items = plan.n_group_items;
     p.n_row_items = plan.n_row_items;
     p.n_tile_wgs = plan.n_tile_wgs;
     p.part_acc = reinterpret_cast<float *>(ws + plan.off_acc);

@@ -603,6 +603,10 @@ __device__ __forceinline__ void progress_store(uint32_t *w, uint32_t v)
     __hip_atomic_store(w, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+// `head` is the query head of a tile item (its rows are consecutive tokens), or the first query
+// head of the group of a group item (its rows are the group's heads, all at the token q_row0):
+// row r of the item is row (q_row0 * H + head) + r * rstride of q / out seen as [T * H, D], and
+// likewise in the partial buffers.
 template <int D>
 __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &it, const TeamRef &team, int head,
                                           char *lds)
@@ -613,14 +617,18 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
     const int half = lane >> 5;
     const int col = lane & 31;
     const int H = p.heads;
+    const bool grouped = (it.kind & 0xFF) == kGroupItem;       // uniform
+    const int rows = grouped ? p.group : it.q_rows;
+    const int rstride = grouped ? 1 : H;
+    const int kv_head = head / p.group;
 
     // this lane's query row
     const int r_tile = wave * 32 + col;
-    const int r_eff = min(r_tile, it.q_rows - 1);
-    const int32_t pos = it.q_pos0 + r_eff;
+    const int r_eff = min(r_tile, rows - 1);
+    const int32_t pos = grouped ? it.q_pos0 : it.q_pos0 + r_eff;
     bf16x8 qf[C::KS];
     {
-        const uint16_t *qrow = p.q + ((size_t)(it.q_row0 + r_eff) * H + head) * D + half * 8;
+        const uint16_t *qrow = p.q + ((size_t)it.q_row0 * H + head + (size_t)r_eff * rstride) * D + half * 8;
 #pragma unroll
         for (int ks = 0; ks < C::KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qrow + ks * 16);
     }
@@ -633,8 +641,10 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
         for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
 
     const int32_t *tab = p.block_table + (size_t)it.seq * p.table_stride;
-    const int32_t wave_first_pos = it.q_pos0 + min(wave * 32, it.q_rows - 1);
-    const int32_t wave_last_pos = it.q_pos0 + min(wave * 32 + 31, it.q_rows - 1);
+    // a wavefront without rows of its own only helps to load (its limits make every step inactive)
+    const bool has_rows = wave * 32 < rows;
+    const int32_t wave_first_pos = grouped ? it.q_pos0 : it.q_pos0 + min(wave * 32, rows - 1);
+    const int32_t wave_last_pos = !has_rows ? -1 : grouped ? it.q_pos0 : it.q_pos0 + min(wave * 32 + 31, rows - 1);
 
     // Block-table entries of this wavefront's blocks for 64 steps at a time, one per lane.
     const int32_t nsteps = (it.kv_end - it.kv_begin + kKvTile - 1) / kKvTile;
@@ -687,7 +697,7 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
     // barrier at the end of step s (which waits for this wavefront's loads first) publishes it.
     // The loop is written out for both buffers so that the buffer is an instruction offset.
     auto point_at = [&](int32_t blk) {   // the wavefront's block of the next load
-        const size_t tile = ((size_t)(blk < 0 ? 0 : blk) * p.kv_heads + head / p.group) * (kBlockSize * D);
+        const size_t tile = ((size_t)(blk < 0 ? 0 : blk) * p.kv_heads + kv_head) * (kBlockSize * D);
         next.gk = reinterpret_cast<const char *>(p.k_cache + tile);
         next.gv = reinterpret_cast<const char *>(p.v_cache + tile);
     };
@@ -749,10 +759,15 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
         asm volatile("" : "+v"(tid));
         const int half = (tid >> 5) & 1;
         const int r_tile = (int)(tid >> 6) * 32 + (int)(tid & 31);
-        if (r_tile < it.q_rows) {
+        int32_t kind = it.kind;
+        asm volatile("" : "+s"(kind));
+        const bool grouped = (kind & 0xFF) == kGroupItem;
+        const int rows = grouped ? p.group : it.q_rows;
+        const int rstride = grouped ? 1 : H;
+        if (r_tile < rows) {
             if (it.part_row < 0) {
                 const float inv = 1.f / l_tot;
-                uint16_t *orow = p.out + ((size_t)(it.q_row0 + r_tile) * H + head) * D;
+                uint16_t *orow = p.out + ((size_t)it.q_row0 * H + head + (size_t)r_tile * rstride) * D;
 #pragma unroll
                 for (int db = 0; db < C::DB; ++db)
 #pragma unroll
@@ -762,7 +777,7 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
                         *reinterpret_cast<u32x2 *>(orow + db * 32 + g * 8 + half * 4) = w;
                     }
             } else {
-                const size_t prow = (size_t)(it.part_row + r_tile) * H + head;
+                const size_t prow = (size_t)it.part_row * H + head + (size_t)r_tile * rstride;
                 float *arow = p.part_acc + prow * D;
 #pragma unroll
                 for (int db = 0; db < C::DB; ++db)
@@ -802,32 +817,37 @@ attention_kernel(const AttnParams p)
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int H = p.heads;
-    const int64_t n_tile_wg = p.n_tile_wgs;
-    if ((int64_t)blockIdx.x < n_tile_wg) {
+    const int32_t n_tile_wg = p.n_tile_wgs;
+    if ((int32_t)blockIdx.x < n_tile_wg) {
         // Tile units (item, head) are dealt round-robin to the tile work-groups.  With as many
         // work-groups as units each takes one; with fewer (mixed batches: half of the resident
         // slots, so that generation rows stream through the other half from the start) each
         // walks its share, longest units first.
         __shared__ __attribute__((aligned(16))) char lds[2 * (TileCfg<D>::K_BYTES + TileCfg<D>::V_BYTES)];
-        const int64_t n_units = (int64_t)p.n_tile_items * H;
-        for (int64_t u = blockIdx.x; u < n_units; u += n_tile_wg) {
-            const int32_t item = (int32_t)(u / H);
-            const int head = (int)(u % H);
+        const int32_t n_tile_units = p.n_tile_items * H;   // the launcher checks that this fits
+        const int32_t n_units = n_tile_units + p.n_group_items;
+        for (int32_t u = (int32_t)blockIdx.x; u < n_units; u += n_tile_wg) {
+            // a tile item is one unit per head; a group item is one unit and names its K/V head
+            const bool is_tile = u < n_tile_units;
+            const int32_t item = is_tile ? u / H : p.n_tile_items + (u - n_tile_units);
             const WorkItem it = load_item(p.items + item);
-            TeamRef team;
-            team.base = __builtin_amdgcn_readfirstlane(p.teams[item].base);
-            team.member = __builtin_amdgcn_readfirstlane(p.teams[item].member);
-            team.size = __builtin_amdgcn_readfirstlane(p.teams[item].size);
-            team.stride = __builtin_amdgcn_readfirstlane(p.teams[item].stride);
+            const int head = is_tile ? u % H : (it.kind >> 8) * p.group;
+            TeamRef team = {-1, 0, 1, 0};
+            if (is_tile) {
+                team.base = __builtin_amdgcn_readfirstlane(p.teams[item].base);
+                team.member = __builtin_amdgcn_readfirstlane(p.teams[item].member);
+                team.size = __builtin_amdgcn_readfirstlane(p.teams[item].size);
+                team.stride = __builtin_amdgcn_readfirstlane(p.teams[item].stride);
+            }
             tile_body<D>(p, it, team, head, lds);
             __syncthreads();   // the next unit's first loads overwrite the tile buffers
         }
         return;
     }
     const int hg = (H + kWaves - 1) / kWaves;
-    const int64_t idx = (int64_t)blockIdx.x - n_tile_wg;
-    const int32_t item = p.n_tile_items + (int32_t)(idx / hg);
-    const int head = (int)(idx % hg) * kWaves + wave;
+    const int32_t idx = (int32_t)blockIdx.x - n_tile_wg;
+    const int32_t item = p.n_tile_items + p.n_group_items + idx / hg;
+    const int head = (idx % hg) * kWaves + wave;
     if (head >= H) return;
     const WorkItem it = load_item(p.items + item);
     row_body<D, kRowSets>(p, it, head, lane);
@@ -896,7 +916,8 @@ int launch_attention(const AttnParams &p, int32_t D, void *stream)
     const int hg = (p.heads + kWaves - 1) / kWaves;
     const int64_t grid = (int64_t)p.n_tile_wgs + (int64_t)p.n_row_items * hg;
     if (grid == 0) return 0;
-    if (grid > 0x7FFFFFFF) return (int)hipErrorInvalidConfiguration;
+    const int64_t units = (int64_t)p.n_tile_items * p.heads + p.n_group_items;
+    if (grid > 0x7FFFFFFF || units > 0x7FFFFFFF) return (int)hipErrorInvalidConfiguration;
     if (D == 128)
         hipLaunchKernelGGL(attention_kernel<128>, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, p);
     else

@@ -12,7 +12,10 @@ constexpr int kKvTile = 64;      // keys staged per step of the matrix-core body
 constexpr int kThreads = 256;    // work-group size of the attention kernel (4 wavefronts)
 constexpr int kWaves = kThreads / 64;
 
-enum ItemKind : int32_t { kRowItem = 0, kTileItem = 1 };
+// kGroupItem: a generation row of a grouped-K/V-head layer on the matrix-core body -- the "rows" of
+// the tile are the H/HK query heads that share one K/V head (its index sits in kind >> 8), all at
+// the position of the one token q_row0; q_rows stays 1 (one token) in the work list.
+enum ItemKind : int32_t { kRowItem = 0, kTileItem = 1, kGroupItem = 2 };
 
 // One unit of work.  A tile item is executed by one work-group per head; a row item by one
 // wavefront per head (a work-group covers kWaves consecutive heads).
@@ -63,13 +66,14 @@ struct PlanOptions {
 };
 
 struct Plan {
-    std::vector<WorkItem> items;  // tile items first, then row items; each group longest first
+    std::vector<WorkItem> items;  // tile items, then group items, then row items; each kind longest first
     std::vector<MergeRow> merge;
     std::vector<TeamRef> teams;   // one per tile item
     int64_t progress_words = 0;   // all set to kNotRunning before every launch
     int32_t n_tile_items = 0;
+    int32_t n_group_items = 0;
     int32_t n_row_items = 0;
-    int32_t n_tile_wgs = 0;       // work-groups that share the n_tile_items * heads tile units
+    int32_t n_tile_wgs = 0;       // work-groups that share the n_tile_items * heads + n_group_items units
     int64_t part_rows = 0;
 
     // workspace layout (byte offsets)
@@ -96,6 +100,7 @@ struct AttnParams {
     uint16_t *out;
     const WorkItem *items;
     int32_t n_tile_items;
+    int32_t n_group_items;
     int32_t n_row_items;
     int32_t n_tile_wgs;  // the first n_tile_wgs work-groups take tile units wg, wg + n_tile_wgs, ...
     float *part_acc;  // [part_rows, H, D]

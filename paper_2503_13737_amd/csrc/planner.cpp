@@ -29,6 +29,12 @@ constexpr int64_t kRowItemTarget = 256 * 8 * 6;
 constexpr int64_t kMinRowSplitBlocks = 8;
 constexpr int64_t kMinTileSplitSteps = 8;   // 512 keys
 constexpr int64_t kTeamMinSteps = 16;       // shorter ranges do not drift apart far enough to matter
+// Grouped K/V heads: from this group size on a generation row runs on the matrix-core body, one
+// work-group per (row, K/V head, key range) with the group's query heads as the rows of the tile;
+// below it the streaming body (one wavefront per query head) is cheaper.
+constexpr int64_t kGroupMin = 4;
+constexpr int64_t kGroupItemTarget = 1024;  // work-groups wanted from the group items of a batch
+constexpr int64_t kMinGroupSplitSteps = 4;
 
 int64_t auto_row_split_blocks(const PlanOptions &opt, int64_t total_blocks)
 {
@@ -166,7 +172,7 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
     plan->part_rows = 0;
     if (S < 0) return MPA_ERR_BAD_BATCH;
     if (S == 0) {
-        plan->n_tile_items = plan->n_row_items = plan->n_tile_wgs = 0;
+        plan->n_tile_items = plan->n_group_items = plan->n_row_items = plan->n_tile_wgs = 0;
         finish_layout(opt, plan);
         return MPA_OK;
     }
@@ -186,11 +192,17 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
             }
         }
     }
+    const int64_t group = opt.heads / opt.kv_heads;
+    const bool rows_on_tiles = group >= kGroupMin && !opt.pp_rowstream;   // generation rows become group items
     const int64_t row_split = auto_row_split_blocks(opt, row_blocks);
+    // key range of a group item, in keys: enough items for the chip, whole 64-key steps
+    const int64_t group_split =
+        std::max<int64_t>(ceil_div(ceil_div(row_blocks * kBlockSize * opt.kv_heads, kGroupItemTarget), kKvTile),
+                          kMinGroupSplitSteps) * kKvTile;
     const double row_us = (double)row_blocks * kBlockSize * 4.0 * opt.head_dim * opt.kv_heads / kRowBytesPerUs;
     const int64_t tile_split = auto_tile_split_tokens(opt, tile_steps, row_us);
 
-    std::vector<WorkItem> tiles, rows;
+    std::vector<WorkItem> tiles, groups, rows;
     auto emit = [&](std::vector<WorkItem> &dst, int32_t kind, int32_t seq, int32_t q_row0,
                     int32_t q_rows, int32_t q_pos0, int64_t split_len, int64_t granule, bool fixed_len) {
         const int64_t kv_len = (int64_t)q_pos0 + q_rows;  // keys visible to the last row
@@ -225,7 +237,18 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
     for (int32_t i = 0; i < S; ++i) {
         int32_t q_len = cs[i + 1] - cs[i];
         int32_t prior = ctx[i] - q_len;
-        if (q_len == 1 || opt.pp_rowstream) {
+        if (q_len == 1 && rows_on_tiles) {
+            // ranges, partial rows and the merge row once; one item per K/V head over each range
+            std::vector<WorkItem> one;
+            const int64_t len = opt.tg_split_blocks > 0 ? ceil_div(opt.tg_split_blocks * kBlockSize, kKvTile) * kKvTile
+                                                        : group_split;
+            emit(one, kGroupItem, i, cs[i], 1, prior, len, kKvTile, false);
+            for (int32_t kvh = 0; kvh < opt.kv_heads; ++kvh)
+                for (WorkItem w : one) {
+                    w.kind = kGroupItem | (kvh << 8);
+                    groups.push_back(w);
+                }
+        } else if (q_len == 1 || opt.pp_rowstream) {
             for (int32_t j = 0; j < q_len; ++j)
                 emit(rows, kRowItem, i, cs[i] + j, 1, prior + j, row_split * kBlockSize, kBlockSize, false);
         } else {
@@ -267,7 +290,9 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
         for (size_t i = 0; i < tiles.size(); ++i) tiles[i] = keyed[i].w;
     }
     std::stable_sort(rows.begin(), rows.end(), longer);
+    std::stable_sort(groups.begin(), groups.end(), longer);
     plan->n_tile_items = (int32_t)tiles.size();
+    plan->n_group_items = (int32_t)groups.size();
     plan->n_row_items = (int32_t)rows.size();
     // Work-groups for the tile units.  Alone, every unit gets its own and the hardware deals them
     // out as slots free up.  Next to a substantial amount of generation rows the tiles get three
@@ -277,7 +302,7 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
     // streaming wavefront that shares its SIMD with a matrix-core wavefront gets about a third of
     // the issue slots it needs).
     {
-        const int64_t units = (int64_t)tiles.size() * opt.heads;
+        const int64_t units = (int64_t)tiles.size() * opt.heads + (int64_t)groups.size();
         int64_t steps = 0;
         for (int64_t st : tile_steps) steps += st;
         const double tile_us = (double)steps * opt.heads * kStepUs / (double)kTileSlots;
@@ -293,7 +318,8 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
     // above, or when the option asks for them.
     {
         const int64_t min_steps = opt.pp_team_min_steps > 0 ? opt.pp_team_min_steps : kTeamMinSteps;
-        const bool want = opt.pp_team_min_steps > 0 || plan->n_tile_wgs < (int64_t)tiles.size() * opt.heads;
+        const bool want = opt.pp_team_min_steps > 0 ||
+                          plan->n_tile_wgs < (int64_t)tiles.size() * opt.heads + (int64_t)groups.size();
         plan->teams.assign(tiles.size(), TeamRef{-1, 0, 1, 0});
         for (size_t i = 0; want && i < tiles.size();) {
             size_t j = i + 1;
@@ -311,6 +337,7 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
         }
     }
     plan->items = std::move(tiles);
+    plan->items.insert(plan->items.end(), groups.begin(), groups.end());
     plan->items.insert(plan->items.end(), rows.begin(), rows.end());
     finish_layout(opt, plan);
     return MPA_OK;
@@ -330,8 +357,14 @@ size_t plan_bytes_upper_bound(const PlanOptions &opt, int64_t max_seqs, int64_t 
     // every row may be a generation task; alternatively rows group into tiles
     const int64_t n_rows_as_items = std::max(max_seqs, max_tokens);
     const int64_t n_tiles = max_tokens / 2 + max_seqs;  // a tile has >= 2 rows unless it is a remainder
-    const int64_t items = n_rows_as_items * row_ns + n_tiles * tile_ns;
-    const int64_t part_rows = n_rows_as_items * row_ns + (max_tokens + 0) * tile_ns;
+    // as group items a row has one item per K/V head and 256-key range (fewer keys per range only if forced)
+    const int64_t group_len = opt.tg_split_blocks > 0
+                                  ? ceil_div(opt.tg_split_blocks * kBlockSize, kKvTile) * kKvTile
+                                  : kMinGroupSplitSteps * kKvTile;
+    const int64_t group_ns = opt.heads / opt.kv_heads >= kGroupMin ? ceil_div(max_ctx, group_len) * opt.kv_heads : 0;
+    const int64_t items = n_rows_as_items * std::max(row_ns, group_ns) + n_tiles * tile_ns;
+    const int64_t group_ranges = group_ns > 0 ? ceil_div(max_ctx, group_len) : 0;   // partial rows per token
+    const int64_t part_rows = n_rows_as_items * std::max(row_ns, group_ranges) + (max_tokens + 0) * tile_ns;
     const int64_t merge_rows = max_tokens;
     Plan p;
     size_t off = 0;

@@ -84,26 +84,34 @@ def test_kv_append_rejects_bad_arguments_without_gpu():
     assert lib.mpa_kv_append(None, fake, fake, fake, 3, fake, fake, None) == mpa.MPA_ERR_INVALID_ARG
 
 
-def check_plan_covers(b, items, counts, H):
-    """Every (row, key) pair under the causal mask is covered exactly once."""
+def check_plan_covers(b, items, counts, H, HK=None):
+    """Every (row, head, key) triple under the causal mask is covered exactly once.  Items of kind
+    0 and 1 cover all heads, an item of kind 2 the query heads of K/V head kind >> 8."""
+    HK = H if HK is None else HK
+    G = H // HK
     ql, pr = b.q_lens, b.priors
     for i in range(b.S):
         for j in range(int(ql[i])):
             row, pos = int(b.chunk_starts[i]) + j, int(pr[i]) + j
-            cover = []
-            for it in items:
-                seq, q_row0, q_rows, q_pos0, kb, ke, part, kind = it
-                if q_row0 <= row < q_row0 + q_rows:
-                    assert seq == i and q_pos0 + (row - q_row0) == pos
-                    lo, hi = kb, min(ke, pos + 1)
-                    if hi > lo:
-                        cover.append((lo, hi, part))
-            cover.sort()
-            assert cover[0][0] == 0 and cover[-1][1] == pos + 1
-            for a, bb in zip(cover, cover[1:]):
-                assert a[1] == bb[0]
-            if len(cover) > 1:
-                assert all(c[2] >= 0 for c in cover)
+            for kvh in range(HK):   # heads of one K/V head are always covered together
+                cover = []
+                for it in items:
+                    seq, q_row0, q_rows, q_pos0, kb, ke, part, kind = (int(x) for x in it)
+                    if (kind & 0xFF) == 2 and (kind >> 8) != kvh:
+                        continue
+                    if (kind & 0xFF) == 2:
+                        assert G >= 4 and q_rows == 1 and 0 <= (kind >> 8) < HK
+                    if q_row0 <= row < q_row0 + q_rows:
+                        assert seq == i and q_pos0 + (row - q_row0) == pos
+                        lo, hi = kb, min(ke, pos + 1)
+                        if hi > lo:
+                            cover.append((lo, hi, part))
+                cover.sort()
+                assert cover[0][0] == 0 and cover[-1][1] == pos + 1
+                for a, bb in zip(cover, cover[1:]):
+                    assert a[1] == bb[0]
+                if len(cover) > 1:
+                    assert all(c[2] >= 0 for c in cover)
 
 
 @pytest.mark.parametrize("opts", [{}, {mpa.MPA_OPT_TG_SPLIT_BLOCKS: 1}, {mpa.MPA_OPT_PP_SPLIT_TOKENS: 64},

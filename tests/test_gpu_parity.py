@@ -111,6 +111,23 @@ def test_grouped_kv_heads(mpa, seed, D, H, HK):
         assert_close(out, ref, f"{b.name} H={H} HK={HK} {opts}")
 
 
+@pytest.mark.parametrize("H,HK,D", [(8, 2, 128), (32, 1, 64), (40, 8, 128), (16, 4, 64)])
+def test_generation_rows_of_grouped_heads_on_the_matrix_core_body(mpa, H, HK, D):
+    """Group sizes 4, 5, 32: a generation row runs as one tile per K/V head whose rows are the
+    group's query heads.  Contexts of one key, block and step boundaries, long ones with forced
+    short ranges (several partials per row), next to a prompt chunk."""
+    ql = [1, 1, 1, 1, 1, 1, 1, 150]
+    ctx = [1, 16, 64, 65, 129, 1000, 2500, 400]
+    b = W.make_batch(f"gqa-rows-{H}-{HK}", 321, H, D, 16, sum((c + 15) // 16 for c in ctx) + 3, ql, ctx, Hkv=HK)
+    ref, _, _ = oracle_run(b)
+    for opts in ({}, {"MPA_OPT_TG_SPLIT_BLOCKS": 4}, {"MPA_OPT_TG_SPLIT_BLOCKS": 9, "MPA_OPT_PP_RESIDENT_WGS": 5}):
+        out, _, _ = gpu_run(ctx_for(mpa, b, **opts), b)
+        assert_close(out, ref, f"{b.name} {opts}")
+        for i in range(b.S):
+            r0, r1 = b.chunk_starts[i], b.chunk_starts[i + 1]
+            assert_close(out[r0:r1], ref[r0:r1], f"{b.name} {opts} seq {i}")
+
+
 @pytest.mark.parametrize("ql,ctx", [
     ([1], [1]),                      # single key
     ([1], [16]), ([1], [17]),        # block boundary

@@ -60,6 +60,28 @@ def test_one_context_alternating_batches(mpa):
             assert_close(to_host_u16(db.out), ref, f"{b.name} rep {rep}")
 
 
+def test_reused_work_list_same_batch_then_same_sizes_other_lengths(mpa):
+    """A call with the previous call's chunk_starts / context_lens reuses its work list (fresh
+    workspace, poisoned, each time); a batch of the same sizes but other context lengths, and an
+    option change, must not."""
+    import torch
+    ql = [200, 1, 1, 1]
+    ctx_a, ctx_b = [700, 300, 64, 1500], [700, 301, 64, 900]
+    ba = W.make_batch("reuse-a", 41, 4, 128, 16, 200, ql, ctx_a)
+    bb = W.make_batch("reuse-b", 42, 4, 128, 16, 200, ql, ctx_b)
+    ctx = mpa.Context(4, 128)
+    refs = {id(b): oracle_run(b)[0] for b in (ba, bb)}
+    for step, b in enumerate((ba, ba, bb, bb, ba)):
+        if step == 3:
+            ctx.set_option(mpa.MPA_OPT_TG_SPLIT_BLOCKS, 2)
+        db = DeviceBatch(b, "prior")
+        ws = torch.empty(ctx.workspace_bytes_for_batch(b.chunk_starts, b.context_lens), dtype=torch.uint8, device="cuda")
+        ws.fill_(0xFF)
+        run_on(ctx, db, b, ws)
+        torch.cuda.synchronize()
+        assert_close(to_host_u16(db.out), refs[id(b)], f"{b.name} call {step}")
+
+
 def test_run_to_run_bit_identical_on_split_heavy_batch(mpa):
     import torch
     b = W.random_ragged(9100, H=5, D=128, n_pp=2, n_tg=4, max_q=400, max_prior=3000, max_ctx=4000)

@@ -75,6 +75,29 @@ def test_resident_and_pacing_options_do_not_change_the_work_list():
         c.set_option(mpa.MPA_OPT_PP_RESIDENT_WGS, -1)
 
 
+@pytest.mark.parametrize("H,HK", [(8, 2), (16, 2), (8, 1), (12, 4), (8, 4)])
+def test_grouped_heads_plan(H, HK):
+    """From group size 4 on generation rows become matrix-core items, one per K/V head and key
+    range (kind 2); below it they stay row items.  Coverage, partial rows and bounds as usual."""
+    b = W.random_ragged(900 + H + HK, H=H, D=128, n_pp=1, n_tg=5, max_q=300, max_prior=1500, max_ctx=4000, Hkv=HK)
+    c = mpa.Context(H, 128, num_kv_heads=HK)
+    for split in (0, 3):
+        c.set_option(mpa.MPA_OPT_TG_SPLIT_BLOCKS, split)
+        items, counts = c.plan_describe(b.chunk_starts, b.context_lens)
+        kinds = items[:, 7] & 0xFF
+        assert counts[0] + counts[1] == len(items)
+        if H // HK >= 4:
+            assert counts[1] == 0 and (kinds == 2).sum() > 0 and (items[kinds == 2][:, 4] % 64 == 0).all()
+            # group items sit between the prompt tiles and the (absent) row items
+            first = int(np.argmax(kinds == 2))
+            assert (kinds[:first] == 1).all() and (kinds[first:] == 2).all()
+        else:
+            assert (kinds != 2).all() and counts[1] > 0
+        check_plan_covers(b, items, counts, H, HK)
+        need = c.workspace_bytes_for_batch(b.chunk_starts, b.context_lens)
+        assert c.workspace_bytes(b.S, b.T, int(b.context_lens.max())) >= need
+
+
 def test_workspace_bound_is_monotone():
     c = mpa.Context(40, 128)
     a = c.workspace_bytes(64, 64, 2048)
