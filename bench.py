@@ -30,6 +30,9 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix, published
 
 def make_workload(name: str):
     import workloads as W
+    if name.startswith(("cfg2@bs", "cfg3@bs")):   # the same batch on KV blocks of 32, 64, 128 tokens
+        bs = int(name.split("@bs")[1])
+        return W.config2(bs) if name.startswith("cfg2") else W.config3(bs=bs)
     if name == "cfg3":
         return W.config3()
     if name == "cfg2":
@@ -70,7 +73,7 @@ class DeviceWorkload:
         self.q = torch.from_numpy(b.q.view(np.int16)).to(dev)
         self.block_table = torch.from_numpy(np.ascontiguousarray(b.block_table)).to(dev)
         self.out = torch.zeros((b.T, b.H, b.D), dtype=torch.int16, device=dev)
-        self.ctx = mpa.Context(b.H, b.D, num_kv_heads=b.HK)
+        self.ctx = mpa.Context(b.H, b.D, block_size=b.bs, num_kv_heads=b.HK)
         # every timed step plans its batch anew, as the first layer of a model iteration does
         # (the library would otherwise reuse the work list of the identical previous call)
         self.ctx.set_option(mpa.MPA_OPT_PLAN_CACHE, 0)

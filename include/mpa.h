@@ -61,7 +61,7 @@ typedef struct {
     int32_t num_kv_heads; /* HK, K/V heads; divides H.  Query head h reads K/V head h / (H/HK)
                              (grouped-query attention); HK == H is multi-head attention       */
     int32_t head_dim;     /* D: 64 or 128                                                     */
-    int32_t block_size;   /* bs: 16                                                           */
+    int32_t block_size;   /* bs, tokens per KV block: 16, 32, 64 or 128                       */
     int32_t dtype;        /* MPA_BF16                                                         */
 } mpa_config;
 

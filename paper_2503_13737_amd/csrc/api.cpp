@@ -65,13 +65,15 @@ int mpa_create(mpa_ctx **out, const mpa_config *cfg)
     if (cfg->num_kv_heads <= 0) return MPA_ERR_INVALID_ARG;
     if (cfg->num_kv_heads > cfg->num_heads || cfg->num_heads % cfg->num_kv_heads != 0) return MPA_ERR_UNSUPPORTED;
     if (cfg->head_dim != 64 && cfg->head_dim != 128) return MPA_ERR_UNSUPPORTED;
-    if (cfg->block_size != kBlockSize) return MPA_ERR_UNSUPPORTED;
+    if (cfg->block_size != 16 && cfg->block_size != 32 && cfg->block_size != 64 && cfg->block_size != 128)
+        return MPA_ERR_UNSUPPORTED;
     mpa_ctx *c = new (std::nothrow) mpa_ctx();
     if (!c) return MPA_ERR_INVALID_ARG;
     c->cfg = *cfg;
     c->opt.heads = cfg->num_heads;
     c->opt.kv_heads = cfg->num_kv_heads;
     c->opt.head_dim = cfg->head_dim;
+    c->opt.block_size = cfg->block_size;
     *out = c;
     return MPA_OK;
 }
@@ -198,6 +200,7 @@ int mpa_kv_append(mpa_ctx *ctx, const void *k_new, const void *v_new, const int6
         !aligned(slot_map, 8))
         return MPA_ERR_INVALID_ARG;
     int e = launch_kv_append(k_new, v_new, slot_map, num_tokens, ctx->cfg.num_kv_heads, ctx->cfg.head_dim,
+                             ctx->cfg.block_size,
                              k_cache, v_cache, stream);
     if (e != 0) {
         ctx->last_hip = e;
@@ -238,7 +241,7 @@ int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache, 
     }
     if (chunk_starts[num_seqs] != num_tokens) return MPA_ERR_BAD_BATCH;
     for (int32_t i = 0; i < num_seqs; ++i)
-        if ((int64_t)(context_lens[i] + kBlockSize - 1) / kBlockSize > block_table_stride)
+        if (((int64_t)context_lens[i] + ctx->cfg.block_size - 1) / ctx->cfg.block_size > block_table_stride)
             return MPA_ERR_BAD_BATCH;
     if (!workspace || !aligned(workspace, 256) || workspace_bytes < plan.total_bytes)
         return MPA_ERR_WORKSPACE;
@@ -285,6 +288,7 @@ int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache, 
     p.v_cache = static_cast<const uint16_t *>(v_cache);
     p.block_table = block_table;
     p.table_stride = block_table_stride;
+    p.page_shift = ctx->cfg.block_size == 16 ? 0 : ctx->cfg.block_size == 32 ? 1 : ctx->cfg.block_size == 64 ? 2 : 3;
     p.heads = ctx->cfg.num_heads;
     p.kv_heads = ctx->cfg.num_kv_heads;
     p.group = ctx->cfg.num_heads / ctx->cfg.num_kv_heads;

@@ -47,13 +47,27 @@ __device__ __forceinline__ float group_sum(float x)
     return x;
 }
 
+// Page j (16 tokens) of a sequence as one word (see kPage): table entry j >> shift, page j & mask.
+__device__ __forceinline__ int32_t page_word(const int32_t *table_row, int32_t j, int32_t page_shift)
+{
+    return (table_row[j >> page_shift] << kPageBits) | (j & ((1 << page_shift) - 1));
+}
+// First element of that page for one K/V head in a cache laid out [blocks][heads][block_size][D].
+template <int D>
+__device__ __forceinline__ size_t page_offset(int32_t word, int32_t kv_heads, int32_t kv_head, int32_t page_shift)
+{
+    const size_t blk = (size_t)(word >> kPageBits);
+    const size_t sub = (size_t)(word & ((1 << kPageBits) - 1));
+    return (((blk * kv_heads + kv_head) << page_shift) + sub) * (size_t)(kPage * D);
+}
+
 // ------------------------------------------------------------------------------------------
 // KV append: one thread moves 16 bytes of K and 16 bytes of V.
 // ------------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(256)
 kv_append_kernel(const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_new,
                  const int64_t *__restrict__ slot_map, int32_t T, int32_t H, int32_t vec_per_row,
-                 uint4 *__restrict__ k_cache, uint4 *__restrict__ v_cache)
+                 int32_t block_size, uint4 *__restrict__ k_cache, uint4 *__restrict__ v_cache)
 {
     const int64_t per_token = (int64_t)H * vec_per_row;
     const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -64,9 +78,9 @@ kv_append_kernel(const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_ne
     const int32_t c = rem - h * vec_per_row;
     const int64_t slot = slot_map[t];
     if (slot < 0) return;
-    const int64_t blk = slot / kBlockSize;
-    const int32_t off = (int32_t)(slot - blk * kBlockSize);
-    const int64_t dst = ((blk * H + h) * kBlockSize + off) * vec_per_row + c;
+    const int64_t blk = slot / block_size;
+    const int32_t off = (int32_t)(slot - blk * block_size);
+    const int64_t dst = ((blk * H + h) * block_size + off) * vec_per_row + c;
     k_cache[dst] = k_new[gid];
     v_cache[dst] = v_new[gid];
 }
@@ -87,7 +101,7 @@ template <int D>
 struct RowCfg {
     static constexpr int LPR = D / 8;             // lanes per token row
     static constexpr int TPL = 64 / LPR;          // tokens per 1 KiB load
-    static constexpr int NL = kBlockSize / TPL;   // loads per (block, head) tile
+    static constexpr int NL = kPage / TPL;        // loads per page of one head
 };
 
 template <int D>
@@ -98,10 +112,10 @@ struct KvRegs {
 
 template <int D>
 __device__ __forceinline__ void issue_loads(KvRegs<D> &r, const uint16_t *__restrict__ k_cache,
-                                            const uint16_t *__restrict__ v_cache, int32_t blk,
-                                            int32_t HK, int32_t kv_head, int lane)
+                                            const uint16_t *__restrict__ v_cache, int32_t page,
+                                            int32_t HK, int32_t kv_head, int32_t page_shift, int lane)
 {
-    const size_t tile = ((size_t)blk * HK + kv_head) * (kBlockSize * D);
+    const size_t tile = page_offset<D>(page, HK, kv_head, page_shift);
     const u32x4 *kp = reinterpret_cast<const u32x4 *>(k_cache + tile) + lane;
     const u32x4 *vp = reinterpret_cast<const u32x4 *>(v_cache + tile) + lane;
 #pragma unroll
@@ -187,31 +201,32 @@ __device__ __forceinline__ void row_body(const AttnParams &p, const WorkItem &it
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
     const int32_t limit = min(it.kv_end, it.q_pos0 + 1);   // keys [kv_begin, limit)
-    const int32_t b0 = it.kv_begin / kBlockSize;
-    const int32_t nblk = (limit - it.kv_begin + kBlockSize - 1) / kBlockSize;
-    const int32_t *tab = p.block_table + (size_t)it.seq * p.table_stride + b0;
+    const int32_t b0 = it.kv_begin / kPage;   // pages from here on ("blk" below is a page word)
+    const int32_t nblk = (limit - it.kv_begin + kPage - 1) / kPage;
+    const int32_t *tab = p.block_table + (size_t)it.seq * p.table_stride;
+    const int32_t page_shift = p.page_shift;
 
     for (int32_t g0 = 0; g0 < nblk; g0 += 64) {
         const int32_t n = min(64, nblk - g0);
-        // 64 table entries at a time, one per lane, broadcast from registers as needed
-        const int32_t mine = (lane < n) ? tab[g0 + lane] : 0;
+        // 64 pages at a time, one per lane, broadcast from registers as needed
+        const int32_t mine = (lane < n) ? page_word(tab, b0 + g0 + lane, page_shift) : 0;
         auto blk_of = [&](int j) { return __builtin_amdgcn_readlane(mine, j); };
         auto step = [&](const KvRegs<D> &r, int j) {
-            const int32_t tok0 = it.kv_begin + (g0 + j) * kBlockSize;
-            if (tok0 + kBlockSize <= limit) consume<D, false>(r, qf, m, l, acc, tok0, limit, sub);
+            const int32_t tok0 = it.kv_begin + (g0 + j) * kPage;
+            if (tok0 + kPage <= limit) consume<D, false>(r, qf, m, l, acc, tok0, limit, sub);
             else consume<D, true>(r, qf, m, l, acc, tok0, limit, sub);
         };
         // NS register sets rotate: NS-1 blocks (8 KiB each at D=128) are in flight while one is consumed
         KvRegs<D> r[NS];
 #pragma unroll
         for (int s = 0; s < NS - 1; ++s)
-            if (s < n) issue_loads<D>(r[s], p.k_cache, p.v_cache, blk_of(s), HK, kv_head, lane);
+            if (s < n) issue_loads<D>(r[s], p.k_cache, p.v_cache, blk_of(s), HK, kv_head, page_shift, lane);
         for (int j = 0; j < n; j += NS) {
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
                 if (j + s < n) {
                     if (j + s + NS - 1 < n)
-                        issue_loads<D>(r[(s + NS - 1) % NS], p.k_cache, p.v_cache, blk_of(j + s + NS - 1), HK, kv_head, lane);
+                        issue_loads<D>(r[(s + NS - 1) % NS], p.k_cache, p.v_cache, blk_of(j + s + NS - 1), HK, kv_head, page_shift, lane);
                     step(r[s], j + s);
                 }
             }
@@ -293,7 +308,7 @@ struct TileCfg {
     static constexpr int V_BYTES = TILE_BYTES;
     static constexpr int CPR = D / 8;                   // 16-byte chunks per key row
     static constexpr int RPL = 64 / CPR;                // key rows covered by one wavefront-wide load
-    static constexpr int NL = kBlockSize / RPL;         // loads per wavefront per operand and block
+    static constexpr int NL = kPage / RPL;              // loads per wavefront per operand and page
     static constexpr int VSW = CPR / 4;                 // 4 for D = 128, 2 for D = 64
 };
 
@@ -340,7 +355,7 @@ __device__ __forceinline__ void tile_load(const TileNext<D> &n, int bufi, bool h
     typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
 #pragma unroll
     for (int i = 0; i < C::NL; ++i) {
-        const int row = wave * kBlockSize + i * C::RPL + lane / C::CPR;   // row inside the tile
+        const int row = wave * kPage + i * C::RPL + lane / C::CPR;   // row inside the tile
         const uint32_t dst = n.lds_w + bufi * (C::K_BYTES + C::V_BYTES) + i * C::RPL * C::ROW;
         if (have_block && row < keys_valid) {
             load_to_lds_16(n.gk, n.koff[i], dst);
@@ -648,11 +663,11 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
 
     // Block-table entries of this wavefront's blocks for 64 steps at a time, one per lane.
     const int32_t nsteps = (it.kv_end - it.kv_begin + kKvTile - 1) / kKvTile;
-    const int32_t nblk_item = (it.kv_end - it.kv_begin + kBlockSize - 1) / kBlockSize;
-    const int32_t *tab_w = tab + it.kv_begin / kBlockSize + wave;
-    auto load_entries = [&](int32_t step0) {
+    const int32_t npages_item = (it.kv_end - it.kv_begin + kPage - 1) / kPage;
+    const int32_t page0 = it.kv_begin / kPage;
+    auto load_entries = [&](int32_t step0) {   // page word of this wavefront's page in step step0 + lane
         const int32_t b = (step0 + lane) * kWaves + wave;
-        return (b < nblk_item) ? tab_w[(step0 + lane) * kWaves] : -1;
+        return (b < npages_item) ? page_word(tab, page0 + b, p.page_shift) : -1;
     };
     int32_t entries = load_entries(0);
 
@@ -684,11 +699,11 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
         const int cpos = lane % C::CPR, r_in = lane / C::CPR;
 #pragma unroll
         for (int i = 0; i < C::NL; ++i) {
-            const int row_b = i * C::RPL + r_in, row = wave * kBlockSize + row_b;
+            const int row_b = i * C::RPL + r_in, row = wave * kPage + row_b;
             next.koff[i] = row_b * C::ROW + ((cpos ^ (row & (C::CPR - 1))) * 16);
             next.voff[i] = row_b * C::ROW + ((cpos ^ (C::VSW * (row & 3))) * 16);
         }
-        next.lds_w = __builtin_amdgcn_readfirstlane(lds0 + wave * kBlockSize * C::ROW);
+        next.lds_w = __builtin_amdgcn_readfirstlane(lds0 + wave * kPage * C::ROW);
         next.gk = next.gv = nullptr;
     }
 
@@ -697,7 +712,7 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
     // barrier at the end of step s (which waits for this wavefront's loads first) publishes it.
     // The loop is written out for both buffers so that the buffer is an instruction offset.
     auto point_at = [&](int32_t blk) {   // the wavefront's block of the next load
-        const size_t tile = ((size_t)(blk < 0 ? 0 : blk) * p.kv_heads + kv_head) * (kBlockSize * D);
+        const size_t tile = page_offset<D>(blk < 0 ? 0 : blk, p.kv_heads, kv_head, p.page_shift);
         next.gk = reinterpret_cast<const char *>(p.k_cache + tile);
         next.gv = reinterpret_cast<const char *>(p.v_cache + tile);
     };
@@ -899,14 +914,14 @@ merge_kernel(const AttnParams p)
 }  // namespace
 
 int launch_kv_append(const void *k_new, const void *v_new, const int64_t *slot_map, int32_t T,
-                     int32_t H, int32_t D, void *k_cache, void *v_cache, void *stream)
+                     int32_t H, int32_t D, int32_t block_size, void *k_cache, void *v_cache, void *stream)
 {
     const int32_t vec_per_row = D / 8;
     const int64_t total = (int64_t)T * H * vec_per_row;
     if (total == 0) return 0;
     const int64_t blocks = (total + 255) / 256;
     hipLaunchKernelGGL(kv_append_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
-                       (const uint4 *)k_new, (const uint4 *)v_new, slot_map, T, H, vec_per_row,
+                       (const uint4 *)k_new, (const uint4 *)v_new, slot_map, T, H, vec_per_row, block_size,
                        (uint4 *)k_cache, (uint4 *)v_cache);
     return (int)hipGetLastError();
 }

@@ -6,7 +6,12 @@
 
 namespace mpa {
 
-constexpr int kBlockSize = 16;   // tokens per KV block
+// The kernels walk the cache in pages of 16 tokens.  A KV block holds 1, 2, 4 or 8 pages
+// (block sizes 16, 32, 64, 128); page j of a sequence is page j % pages_per_block of the block
+// in table entry j / pages_per_block.  In registers a page is named by one word,
+// (block id << kPageBits) | page inside the block; -1 = none.
+constexpr int kPage = 16;
+constexpr int kPageBits = 3;
 constexpr int kTileRows = 128;   // query rows of one prompt tile (matrix-core body)
 constexpr int kKvTile = 64;      // keys staged per step of the matrix-core body
 constexpr int kThreads = 256;    // work-group size of the attention kernel (4 wavefronts)
@@ -58,6 +63,7 @@ struct PlanOptions {
     int32_t heads = 0;
     int32_t kv_heads = 0;
     int32_t head_dim = 0;
+    int32_t block_size = 16;      // tokens per KV block
     int64_t tg_split_blocks = 0;  // 0 = automatic
     int64_t pp_split_tokens = 0;  // 0 = automatic
     int64_t pp_rowstream = 0;
@@ -93,6 +99,7 @@ struct AttnParams {
     const uint16_t *v_cache;
     const int32_t *block_table;
     int32_t table_stride;
+    int32_t page_shift; // log2(pages per KV block)
     int32_t heads;      // query heads
     int32_t kv_heads;   // K/V heads; query head h reads K/V head h / (heads / kv_heads)
     int32_t group;      // heads / kv_heads
@@ -113,7 +120,7 @@ struct AttnParams {
 
 // Kernel launchers (kernels.hip).  Return the raw hipError_t as int.
 int launch_kv_append(const void *k_new, const void *v_new, const int64_t *slot_map, int32_t T,
-                     int32_t H, int32_t D, void *k_cache, void *v_cache, void *stream);
+                     int32_t H, int32_t D, int32_t block_size, void *k_cache, void *v_cache, void *stream);
 int launch_attention(const AttnParams &p, int32_t D, void *stream);
 int launch_merge(const AttnParams &p, int32_t D, void *stream);
 

@@ -26,7 +26,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // Target number of concurrently schedulable units: 256 compute units, 8 wavefronts each,
 // several items per wavefront slot so the tail of the launch stays short.
 constexpr int64_t kRowItemTarget = 256 * 8 * 6;
-constexpr int64_t kMinRowSplitBlocks = 8;
+constexpr int64_t kMinRowSplitTokens = 128;
 constexpr int64_t kMinTileSplitSteps = 8;   // 512 keys
 constexpr int64_t kTeamMinSteps = 16;       // shorter ranges do not drift apart far enough to matter
 // Grouped K/V heads: from this group size on a generation row runs on the matrix-core body, one
@@ -36,11 +36,14 @@ constexpr int64_t kGroupMin = 4;
 constexpr int64_t kGroupItemTarget = 1024;  // work-groups wanted from the group items of a batch
 constexpr int64_t kMinGroupSplitSteps = 4;
 
-int64_t auto_row_split_blocks(const PlanOptions &opt, int64_t total_blocks)
+// Key range of a row item in tokens: whole KV blocks, at least kMinRowSplitTokens, few enough
+// items for every wavefront slot to see several.
+int64_t auto_row_split_tokens(const PlanOptions &opt, int64_t total_tokens)
 {
-    if (opt.tg_split_blocks > 0) return opt.tg_split_blocks;
-    int64_t s = ceil_div(total_blocks * opt.heads, kRowItemTarget);
-    return std::max<int64_t>(s, kMinRowSplitBlocks);
+    const int64_t bs = opt.block_size;
+    if (opt.tg_split_blocks > 0) return opt.tg_split_blocks * bs;
+    const int64_t want = std::max<int64_t>(ceil_div(total_tokens * opt.heads, kRowItemTarget), kMinRowSplitTokens);
+    return ceil_div(want, bs) * bs;
 }
 
 // Key-range length for prompt tiles.  `tile_steps` holds, per tile, the number of 64-key steps
@@ -177,14 +180,15 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
         return MPA_OK;
     }
     if (cs[0] != 0) return MPA_ERR_BAD_BATCH;
-    int64_t row_blocks = 0;
+    const int64_t bs = opt.block_size;
+    int64_t row_tokens = 0;   // keys visited by generation rows, in whole blocks
     std::vector<int64_t> tile_steps;
     for (int32_t i = 0; i < S; ++i) {
         int64_t q_len = (int64_t)cs[i + 1] - cs[i];
         if (q_len < 1 || ctx[i] < q_len) return MPA_ERR_BAD_BATCH;
         int64_t prior = ctx[i] - q_len;
         if (q_len == 1 || opt.pp_rowstream) {
-            for (int64_t j = 0; j < q_len; ++j) row_blocks += ceil_div(prior + j + 1, kBlockSize);
+            for (int64_t j = 0; j < q_len; ++j) row_tokens += ceil_div(prior + j + 1, bs) * bs;
         } else {
             for (int64_t r0 = 0; r0 < q_len; r0 += kTileRows) {
                 int64_t rows = std::min<int64_t>(kTileRows, q_len - r0);
@@ -194,12 +198,12 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
     }
     const int64_t group = opt.heads / opt.kv_heads;
     const bool rows_on_tiles = group >= kGroupMin && !opt.pp_rowstream;   // generation rows become group items
-    const int64_t row_split = auto_row_split_blocks(opt, row_blocks);
+    const int64_t row_split = auto_row_split_tokens(opt, row_tokens);
     // key range of a group item, in keys: enough items for the chip, whole 64-key steps
     const int64_t group_split =
-        std::max<int64_t>(ceil_div(ceil_div(row_blocks * kBlockSize * opt.kv_heads, kGroupItemTarget), kKvTile),
+        std::max<int64_t>(ceil_div(ceil_div(row_tokens * opt.kv_heads, kGroupItemTarget), kKvTile),
                           kMinGroupSplitSteps) * kKvTile;
-    const double row_us = (double)row_blocks * kBlockSize * 4.0 * opt.head_dim * opt.kv_heads / kRowBytesPerUs;
+    const double row_us = (double)row_tokens * 4.0 * opt.head_dim * opt.kv_heads / kRowBytesPerUs;
     const int64_t tile_split = auto_tile_split_tokens(opt, tile_steps, row_us);
 
     std::vector<WorkItem> tiles, groups, rows;
@@ -240,7 +244,7 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
         if (q_len == 1 && rows_on_tiles) {
             // ranges, partial rows and the merge row once; one item per K/V head over each range
             std::vector<WorkItem> one;
-            const int64_t len = opt.tg_split_blocks > 0 ? ceil_div(opt.tg_split_blocks * kBlockSize, kKvTile) * kKvTile
+            const int64_t len = opt.tg_split_blocks > 0 ? ceil_div(opt.tg_split_blocks * bs, kKvTile) * kKvTile
                                                         : group_split;
             emit(one, kGroupItem, i, cs[i], 1, prior, len, kKvTile, false);
             for (int32_t kvh = 0; kvh < opt.kv_heads; ++kvh)
@@ -250,7 +254,7 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
                 }
         } else if (q_len == 1 || opt.pp_rowstream) {
             for (int32_t j = 0; j < q_len; ++j)
-                emit(rows, kRowItem, i, cs[i] + j, 1, prior + j, row_split * kBlockSize, kBlockSize, false);
+                emit(rows, kRowItem, i, cs[i] + j, 1, prior + j, row_split, bs, false);
         } else {
             // All tiles of a chunk cut their keys at the same positions (equal ranges of the
             // chunk's whole context), so that the tiles over one range walk the same K/V blocks
@@ -348,18 +352,19 @@ size_t plan_bytes_upper_bound(const PlanOptions &opt, int64_t max_seqs, int64_t 
 {
     if (max_seqs <= 0 || max_tokens <= 0 || max_ctx <= 0) return 256;
     // Ranges are never shorter than the minimum split (or the forced one), so:
-    const int64_t row_split = opt.tg_split_blocks > 0 ? opt.tg_split_blocks : kMinRowSplitBlocks;
+    const int64_t bs = opt.block_size;
+    const int64_t row_split = opt.tg_split_blocks > 0 ? opt.tg_split_blocks * bs : ceil_div(kMinRowSplitTokens, bs) * bs;
     const int64_t tile_split = opt.pp_split_tokens > 0
                                    ? ceil_div(opt.pp_split_tokens, kKvTile) * kKvTile
                                    : kMinTileSplitSteps * kKvTile;
-    const int64_t row_ns = ceil_div(ceil_div(max_ctx, kBlockSize), row_split);
+    const int64_t row_ns = ceil_div(max_ctx, row_split);
     const int64_t tile_ns = ceil_div(max_ctx, tile_split);
     // every row may be a generation task; alternatively rows group into tiles
     const int64_t n_rows_as_items = std::max(max_seqs, max_tokens);
     const int64_t n_tiles = max_tokens / 2 + max_seqs;  // a tile has >= 2 rows unless it is a remainder
     // as group items a row has one item per K/V head and 256-key range (fewer keys per range only if forced)
     const int64_t group_len = opt.tg_split_blocks > 0
-                                  ? ceil_div(opt.tg_split_blocks * kBlockSize, kKvTile) * kKvTile
+                                  ? ceil_div(opt.tg_split_blocks * bs, kKvTile) * kKvTile
                                   : kMinGroupSplitSteps * kKvTile;
     const int64_t group_ns = opt.heads / opt.kv_heads >= kGroupMin ? ceil_div(max_ctx, group_len) * opt.kv_heads : 0;
     const int64_t items = n_rows_as_items * std::max(row_ns, group_ns) + n_tiles * tile_ns;

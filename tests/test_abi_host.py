@@ -30,7 +30,8 @@ def test_library_exports_every_declared_symbol():
 
 def test_create_validates_config():
     for kw, status in [(dict(num_heads=4, head_dim=96), mpa.MPA_ERR_UNSUPPORTED),
-                       (dict(num_heads=4, head_dim=64, block_size=32), mpa.MPA_ERR_UNSUPPORTED),
+                       (dict(num_heads=4, head_dim=64, block_size=48), mpa.MPA_ERR_UNSUPPORTED),
+                       (dict(num_heads=4, head_dim=64, block_size=8), mpa.MPA_ERR_UNSUPPORTED),
                        (dict(num_heads=4, head_dim=64, num_kv_heads=3), mpa.MPA_ERR_UNSUPPORTED),
                        (dict(num_heads=4, head_dim=64, num_kv_heads=8), mpa.MPA_ERR_UNSUPPORTED),
                        (dict(num_heads=4, head_dim=64, dtype=7), mpa.MPA_ERR_UNSUPPORTED),

@@ -16,7 +16,7 @@ def mpa():
 
 
 def ctx_for(mpa, b, **opts):
-    c = mpa.Context(b.H, b.D, num_kv_heads=b.HK)
+    c = mpa.Context(b.H, b.D, block_size=b.bs, num_kv_heads=b.HK)
     for k, v in opts.items():
         c.set_option(getattr(mpa, k), v)
     return c
@@ -122,6 +122,25 @@ def test_generation_rows_of_grouped_heads_on_the_matrix_core_body(mpa, H, HK, D)
     ref, _, _ = oracle_run(b)
     for opts in ({}, {"MPA_OPT_TG_SPLIT_BLOCKS": 4}, {"MPA_OPT_TG_SPLIT_BLOCKS": 9, "MPA_OPT_PP_RESIDENT_WGS": 5}):
         out, _, _ = gpu_run(ctx_for(mpa, b, **opts), b)
+        assert_close(out, ref, f"{b.name} {opts}")
+        for i in range(b.S):
+            r0, r1 = b.chunk_starts[i], b.chunk_starts[i + 1]
+            assert_close(out[r0:r1], ref[r0:r1], f"{b.name} {opts} seq {i}")
+
+
+@pytest.mark.parametrize("bs", [32, 64, 128])
+@pytest.mark.parametrize("D,H,HK", [(128, 4, 4), (64, 8, 2)])
+def test_block_sizes(mpa, bs, D, H, HK):
+    """KV blocks of 32, 64 and 128 tokens (2, 4, 8 pages of 16): append bit-exact, attention over
+    prompt chunks that start inside a block, generation rows ending on every kind of boundary,
+    forced short ranges; with grouped heads the generation rows take the matrix-core body."""
+    ql = [300, 77, 1, 1, 1, 1, 1, 1]
+    ctx = [700, 77 + 3 * bs + 5, 1, bs, bs + 1, 5 * bs - 1, 2000, 16]
+    b = W.make_batch(f"bs{bs}", 555 + bs, H, D, bs, sum((c + bs - 1) // bs for c in ctx) + 3, ql, ctx, Hkv=HK)
+    ref, okc, ovc = oracle_run(b)
+    for opts in ({}, {"MPA_OPT_PP_SPLIT_TOKENS": 128, "MPA_OPT_TG_SPLIT_BLOCKS": 1}, {"MPA_OPT_TG_SPLIT_BLOCKS": 3}):
+        out, kc, vc = gpu_run(ctx_for(mpa, b, **opts), b)
+        assert np.array_equal(kc, okc) and np.array_equal(vc, ovc)
         assert_close(out, ref, f"{b.name} {opts}")
         for i in range(b.S):
             r0, r1 = b.chunk_starts[i], b.chunk_starts[i + 1]

@@ -98,6 +98,26 @@ def test_grouped_heads_plan(H, HK):
         assert c.workspace_bytes(b.S, b.T, int(b.context_lens.max())) >= need
 
 
+@pytest.mark.parametrize("bs", [32, 64, 128])
+def test_block_sizes_plan(bs):
+    """Row items cover whole KV blocks of the configured size; tiles and group items whole
+    64-key steps; coverage and bounds as usual."""
+    for H, HK in ((4, 4), (8, 2)):
+        b = W.random_ragged(1200 + bs + H, H=H, D=128, bs=bs, n_pp=2, n_tg=5, max_q=300, max_prior=2000, max_ctx=5000,
+                            Hkv=HK)
+        c = mpa.Context(H, 128, block_size=bs, num_kv_heads=HK)
+        for split in (0, 1, 3):
+            c.set_option(mpa.MPA_OPT_TG_SPLIT_BLOCKS, split)
+            items, counts = c.plan_describe(b.chunk_starts, b.context_lens)
+            kinds = items[:, 7] & 0xFF
+            assert (items[kinds == 0][:, 4] % bs == 0).all() and (items[kinds != 0][:, 4] % 64 == 0).all()
+            if split and (kinds == 0).any():
+                assert ((items[kinds == 0][:, 5] - items[kinds == 0][:, 4]) <= split * bs).all()
+            check_plan_covers(b, items, counts, H, HK)
+            need = c.workspace_bytes_for_batch(b.chunk_starts, b.context_lens)
+            assert c.workspace_bytes(b.S, b.T, int(b.context_lens.max())) >= need
+
+
 def test_workspace_bound_is_monotone():
     c = mpa.Context(40, 128)
     a = c.workspace_bytes(64, 64, 2048)

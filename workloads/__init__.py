@@ -300,23 +300,25 @@ def config1() -> Batch:
     return make_batch("cfg1-tiny-mixed", config_seed(1), 4, 64, 16, 64, ql, ctx)
 
 
-def config2() -> Batch:
-    """13B-shaped layer, generation only: 64 sequences, contexts uniform on [256, 2048]."""
+def config2(bs: int = 16) -> Batch:
+    """13B-shaped layer, generation only: 64 sequences, contexts uniform on [256, 2048].
+    bs: tokens per KV block (the pool keeps its size in tokens)."""
     s = config_seed(2)
     ctx = uniform_ints(64, 256, 2048, s * 4 + 3)
-    return make_batch("cfg2-13b-tg", s, 40, 128, 16, 32768, np.ones(64, dtype=np.int64), ctx)
+    return make_batch("cfg2-13b-tg" + (f"-bs{bs}" if bs != 16 else ""), s, 40, 128, bs, 32768 * 16 // bs,
+                      np.ones(64, dtype=np.int64), ctx)
 
 
-def config3(prior: int | None = None) -> Batch:
+def config3(prior: int | None = None, bs: int = 16) -> Batch:
     """13B-shaped layer, mixed: one 512-token chunk at prior context uniform on [0, 4096] plus
-    48 generation rows with contexts uniform on [512, 4096]."""
+    48 generation rows with contexts uniform on [512, 4096].  bs: tokens per KV block."""
     s = config_seed(3)
     if prior is None:
         prior = int(uniform_ints(1, 0, 4096, s * 4 + 3)[0])
     ctx_tg = uniform_ints(48, 512, 4096, s * 4 + 2)
     ql = np.concatenate([[512], np.ones(48, dtype=np.int64)])
     ctx = np.concatenate([[prior + 512], ctx_tg])
-    return make_batch("cfg3-13b-mixed", s, 40, 128, 16, 32768, ql, ctx)
+    return make_batch("cfg3-13b-mixed" + (f"-bs{bs}" if bs != 16 else ""), s, 40, 128, bs, 32768 * 16 // bs, ql, ctx)
 
 
 def config4() -> Batch:
