@@ -722,6 +722,13 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
         tile_load<D>(next, 0, blk0 >= 0, it.kv_end - it.kv_begin, wave, lane);
     }
     wait_loads_to_lds();
+    // Everything the compiler loaded from memory for this item (Q fragments, table entries) is
+    // consumed once here, so that its waits for those loads sit here and not at their first use
+    // inside the step loop: there a vmcnt wait would also wait for the hand-issued loads of the
+    // next step, which the compiler does not count, and serialise them with the products.
+#pragma unroll
+    for (int ks = 0; ks < C::KS; ++ks) asm volatile("" : "+v"(qf[ks]));
+    asm volatile("" : "+v"(entries));
     __syncthreads();
     auto do_step = [&](int32_t step, auto bufi) {
         constexpr int BUFI = decltype(bufi)::value;

@@ -23,9 +23,12 @@ namespace {
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// Target number of concurrently schedulable units: 256 compute units, 8 wavefronts each,
-// several items per wavefront slot so the tail of the launch stays short.
-constexpr int64_t kRowItemTarget = 256 * 8 * 6;
+// Row items wanted from a batch: two per wavefront slot (256 compute units, 8 wavefronts each).
+// Every item costs a partial result and a share of the merge, so few long ranges beat many short
+// ones as long as the slots stay filled; beyond kMaxRowSplitTokens a range's own tail shows
+// (measured over configs 2-5: best at 3.4-6 K items, ranges of 40-128 blocks of 16).
+constexpr int64_t kRowItemTarget = 256 * 8 * 2;
+constexpr int64_t kMaxRowSplitTokens = 1536;
 constexpr int64_t kMinRowSplitTokens = 128;
 constexpr int64_t kMinTileSplitSteps = 8;   // 512 keys
 constexpr int64_t kTeamMinSteps = 16;       // shorter ranges do not drift apart far enough to matter
@@ -42,7 +45,8 @@ int64_t auto_row_split_tokens(const PlanOptions &opt, int64_t total_tokens)
 {
     const int64_t bs = opt.block_size;
     if (opt.tg_split_blocks > 0) return opt.tg_split_blocks * bs;
-    const int64_t want = std::max<int64_t>(ceil_div(total_tokens * opt.heads, kRowItemTarget), kMinRowSplitTokens);
+    const int64_t want = std::min(std::max<int64_t>(ceil_div(total_tokens * opt.heads, kRowItemTarget), kMinRowSplitTokens),
+                                  kMaxRowSplitTokens);
     return ceil_div(want, bs) * bs;
 }
 
