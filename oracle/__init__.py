@@ -32,9 +32,11 @@ def _load():
         lib.mpa_oracle_threads.restype = i
         lib.mpa_oracle_kv_append.argtypes = [p, p, p, i, i, i, i, p, p]
         lib.mpa_oracle_kv_append.restype = None
-        lib.mpa_oracle_attention.argtypes = [p, p, p, p, i, p, p, i, i, i, i, i, d, p]
+        lib.mpa_oracle_attention.argtypes = [p, p, p, p, i, p, p, i, i, i, i, i, d, i, p]
         lib.mpa_oracle_attention.restype = i
-        lib.mpa_oracle_attention_rows.argtypes = [p, p, p, p, i, p, p, i, i, i, i, i, d, p, p, i, p]
+        lib.mpa_oracle_attention_rows.argtypes = [p, p, p, p, i, p, p, i, i, i, i, i, d, i, p, p, i, p]
+        lib.mpa_oracle_widen.argtypes = [p, ctypes.c_int64, i, p]
+        lib.mpa_oracle_widen.restype = None
         lib.mpa_oracle_attention_rows.restype = i
         _lib = lib
     return _lib
@@ -61,7 +63,19 @@ def kv_append(k_new, v_new, slot_map, k_cache, v_cache):
                                  T, H, D, bs, k_cache.ctypes.data, v_cache.ctypes.data)
 
 
-def attention(q, k_cache, v_cache, block_table, chunk_starts, context_lens, scale) -> np.ndarray:
+DTYPES = {"bf16": 1, "fp16": 2}
+
+
+def widen(bits, dtype: str = "bf16") -> np.ndarray:
+    """The float64 values of 16-bit patterns as the oracle reads them."""
+    bits = _c(bits, np.uint16)
+    out = np.empty(bits.shape, dtype=np.float64)
+    _load().mpa_oracle_widen(ctypes.c_void_p(bits.ctypes.data), ctypes.c_int64(bits.size), DTYPES[dtype],
+                             ctypes.c_void_p(out.ctypes.data))
+    return out
+
+
+def attention(q, k_cache, v_cache, block_table, chunk_starts, context_lens, scale, dtype: str = "bf16") -> np.ndarray:
     """Returns out [T,H,D] float64."""
     T, H, D = q.shape
     bs = k_cache.shape[2]
@@ -74,13 +88,14 @@ def attention(q, k_cache, v_cache, block_table, chunk_starts, context_lens, scal
     rc = _load().mpa_oracle_attention(q.ctypes.data, k_cache.ctypes.data, v_cache.ctypes.data,
                                       block_table.ctypes.data, block_table.shape[1],
                                       chunk_starts.ctypes.data, context_lens.ctypes.data,
-                                      S, H, k_cache.shape[1], D, bs, float(scale), out.ctypes.data)
+                                      S, H, k_cache.shape[1], D, bs, float(scale), DTYPES[dtype], out.ctypes.data)
     if rc != 0:
         raise ValueError("malformed batch")
     return out
 
 
-def attention_rows(q, k_cache, v_cache, block_table, chunk_starts, context_lens, scale, rows, heads) -> np.ndarray:
+def attention_rows(q, k_cache, v_cache, block_table, chunk_starts, context_lens, scale, rows, heads,
+                   dtype: str = "bf16") -> np.ndarray:
     """Selected (row, head) pairs only; returns [n, D] float64."""
     T, H, D = q.shape
     bs = k_cache.shape[2]
@@ -93,7 +108,7 @@ def attention_rows(q, k_cache, v_cache, block_table, chunk_starts, context_lens,
     rc = _load().mpa_oracle_attention_rows(q.ctypes.data, k_cache.ctypes.data, v_cache.ctypes.data,
                                            block_table.ctypes.data, block_table.shape[1],
                                            chunk_starts.ctypes.data, context_lens.ctypes.data,
-                                           S, H, k_cache.shape[1], D, bs, float(scale), rows.ctypes.data,
+                                           S, H, k_cache.shape[1], D, bs, float(scale), DTYPES[dtype], rows.ctypes.data,
                                            heads.ctypes.data, rows.size, out.ctypes.data)
     if rc != 0:
         raise ValueError("malformed batch or row list")

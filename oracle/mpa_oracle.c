@@ -24,7 +24,9 @@
  *     paper also serves, Sec. 6.1): with HK K/V heads, query head h reads K/V head h / (H/HK).
  *     HK == H is ordinary multi-head attention.
  *
- * Inputs are bf16 bit patterns widened exactly to double; outputs stay in double.
+ * Inputs are 16-bit floating-point bit patterns, bf16 (dtype 1: the upper half of an IEEE single)
+ * or fp16 (dtype 2: IEEE half, the precision of the paper's own experiments, Sec. 5), widened
+ * exactly to double; outputs stay in double.
  * Layouts: q [T,H,D]; k_new/v_new [T,HK,D]; caches [NB,HK,bs,D]; block_table [S,stride].
  *
  * Pins (tests/test_oracle_pins.py): dense brute force with an explicit masked score matrix,
@@ -42,12 +44,30 @@
 #include <omp.h>
 #endif
 
-static double widen(uint16_t b)
+enum { ORACLE_BF16 = 1, ORACLE_FP16 = 2 };
+
+/* The value of a 16-bit pattern.  fp16: 1 sign, 5 exponent (bias 15), 10 fraction bits;
+ * exponent 0 = subnormal (fraction * 2^-24), 31 = infinity / NaN. */
+static double widen(uint16_t b, int dtype)
 {
+    if (dtype == ORACLE_FP16) {
+        const int sign = b >> 15, e = (b >> 10) & 31, f = b & 1023;
+        double v;
+        if (e == 0) v = ldexp((double)f, -24);
+        else if (e == 31) v = f ? NAN : INFINITY;
+        else v = ldexp(1.0 + (double)f / 1024.0, e - 15);
+        return sign ? -v : v;
+    }
     uint32_t u = (uint32_t)b << 16;
     float f;
     memcpy(&f, &u, 4);
     return (double)f;
+}
+
+/* For the pins: out[i] = value of in[i]. */
+void mpa_oracle_widen(const uint16_t *in, int64_t n, int dtype, double *out)
+{
+    for (int64_t i = 0; i < n; ++i) out[i] = widen(in[i], dtype);
 }
 
 int mpa_oracle_threads(void)
@@ -80,7 +100,7 @@ void mpa_oracle_kv_append(const uint16_t *k_new, const uint16_t *v_new, const in
 /* One output row: query row `row` of q (belonging to sequence i, absolute position p), head h. */
 static void one_row(const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache,
                     const int32_t *table_i, int row, int p, int h, int H, int HK, int D, int bs,
-                    double scale, double *s, double *out_row)
+                    double scale, int dtype, double *s, double *out_row)
 {
     const uint16_t *qv = q + ((size_t)row * H + h) * D;
     const int hk = h / (H / HK); /* the K/V head this query head reads */
@@ -88,7 +108,7 @@ static void one_row(const uint16_t *q, const uint16_t *k_cache, const uint16_t *
     for (int t = 0; t <= p; ++t) {
         const uint16_t *kv = k_cache + (((size_t)table_i[t / bs] * HK + hk) * bs + t % bs) * D;
         double dot = 0.0;
-        for (int d = 0; d < D; ++d) dot += widen(qv[d]) * widen(kv[d]);
+        for (int d = 0; d < D; ++d) dot += widen(qv[d], dtype) * widen(kv[d], dtype);
         s[t] = scale * dot;
         if (s[t] > m) m = s[t];
     }
@@ -100,7 +120,7 @@ static void one_row(const uint16_t *q, const uint16_t *k_cache, const uint16_t *
     for (int d = 0; d < D; ++d) out_row[d] = 0.0;
     for (int t = 0; t <= p; ++t) {
         const uint16_t *vv = v_cache + (((size_t)table_i[t / bs] * HK + hk) * bs + t % bs) * D;
-        for (int d = 0; d < D; ++d) out_row[d] += s[t] * widen(vv[d]);
+        for (int d = 0; d < D; ++d) out_row[d] += s[t] * widen(vv[d], dtype);
     }
     for (int d = 0; d < D; ++d) out_row[d] /= Z;
 }
@@ -109,10 +129,10 @@ static void one_row(const uint16_t *q, const uint16_t *k_cache, const uint16_t *
 int mpa_oracle_attention(const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache,
                          const int32_t *block_table, int stride, const int32_t *chunk_starts,
                          const int32_t *context_lens, int S, int H, int HK, int D, int bs,
-                         double scale, double *out)
+                         double scale, int dtype, double *out)
 {
     int max_ctx = 0;
-    if (HK < 1 || H % HK != 0) return -1;
+    if (HK < 1 || H % HK != 0 || (dtype != ORACLE_BF16 && dtype != ORACLE_FP16)) return -1;
     for (int i = 0; i < S; ++i) {
         int q_len = chunk_starts[i + 1] - chunk_starts[i];
         if (q_len < 1 || context_lens[i] < q_len) return -1;
@@ -134,7 +154,7 @@ int mpa_oracle_attention(const uint16_t *q, const uint16_t *k_cache, const uint1
                 int prior = context_lens[i] - q_len;
                 int p = prior + (row - chunk_starts[i]);
                 one_row(q, k_cache, v_cache, block_table + (size_t)i * stride, row, p, h, H, HK, D,
-                        bs, scale, s, out + ((size_t)row * H + h) * D);
+                        bs, scale, dtype, s, out + ((size_t)row * H + h) * D);
             }
         free(s);
     }
@@ -146,11 +166,11 @@ int mpa_oracle_attention(const uint16_t *q, const uint16_t *k_cache, const uint1
 int mpa_oracle_attention_rows(const uint16_t *q, const uint16_t *k_cache, const uint16_t *v_cache,
                               const int32_t *block_table, int stride, const int32_t *chunk_starts,
                               const int32_t *context_lens, int S, int H, int HK, int D, int bs,
-                              double scale, const int32_t *rows, const int32_t *heads, int n,
+                              double scale, int dtype, const int32_t *rows, const int32_t *heads, int n,
                               double *out)
 {
     int max_ctx = 0;
-    if (HK < 1 || H % HK != 0) return -1;
+    if (HK < 1 || H % HK != 0 || (dtype != ORACLE_BF16 && dtype != ORACLE_FP16)) return -1;
     for (int i = 0; i < S; ++i) {
         int q_len = chunk_starts[i + 1] - chunk_starts[i];
         if (q_len < 1 || context_lens[i] < q_len) return -1;
@@ -168,7 +188,7 @@ int mpa_oracle_attention_rows(const uint16_t *q, const uint16_t *k_cache, const 
             int q_len = chunk_starts[i + 1] - chunk_starts[i];
             int p = context_lens[i] - q_len + (row - chunk_starts[i]);
             one_row(q, k_cache, v_cache, block_table + (size_t)i * stride, row, p, heads[x], H, HK,
-                    D, bs, scale, s, out + (size_t)x * D);
+                    D, bs, scale, dtype, s, out + (size_t)x * D);
         }
         free(s);
     }

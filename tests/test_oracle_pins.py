@@ -377,3 +377,47 @@ def test_grouped_kv_append_writes_kv_heads_only():
     oracle.kv_append(kn, vn, b.slot_map, kc, vc)
     k2, v2 = b.full_cache("ctx")
     assert np.array_equal(kc, k2) and np.array_equal(vc, v2)
+
+
+# ---------------------------------------------------------------- fp16 storage (the paper's precision)
+def test_fp16_decode_matches_the_library_for_every_pattern():
+    bits = np.arange(65536, dtype=np.uint16)
+    got, ref = oracle.widen(bits, "fp16"), bits.view(np.float16).astype(np.float64)
+    ok = ~np.isnan(ref)
+    assert np.array_equal(np.isnan(got), np.isnan(ref)) and np.array_equal(got[ok], ref[ok])
+    assert np.array_equal(np.signbit(got[ok]), np.signbit(ref[ok]))
+    # and bf16 against the upper half of a single
+    ref_bf = (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    got_bf = oracle.widen(bits, "bf16")
+    ok = ~np.isnan(ref_bf)
+    assert np.array_equal(got_bf[ok], ref_bf[ok])
+
+
+def test_generator_fp16_rounding_matches_the_library():
+    rng = np.random.default_rng(11)
+    x = (rng.standard_normal(100000) * 10.0 ** rng.integers(-9, 5, 100000)).astype(np.float32)
+    edge = np.array([0.0, -0.0, 65504, 65519.9, 65520, 1e-8, 5.96e-8, 2.98e-8, 2.99e-8, 6.1e-5, 6.0e-5,
+                     1.0009765625, 1.00048828125, 1.00146484375], dtype=np.float32)
+    x = np.concatenate([x, edge, -edge])
+    with np.errstate(over="ignore"):
+        ref = x.astype(np.float16).view(np.uint16)
+    assert np.array_equal(W.round_16(x, "fp16"), ref)
+    b = W.make_batch("fp16-gen", 5, 2, 64, 16, 40, [5, 1], [20, 33], dtype="fp16")
+    vals = W.to_f64(b.q, "fp16")
+    assert abs(vals.std() - 1.0) < 0.05 and abs(vals.mean()) < 0.05
+
+
+@pytest.mark.parametrize("L,prior,H,D,bs", [(5, 0, 2, 16, 4), (100, 63, 3, 64, 16), (70, 16, 1, 128, 32)])
+def test_brute_force_dense_fp16(L, prior, H, D, bs):
+    k = W.normal_bf16((L, H, D), 300 + L, dtype="fp16")
+    v = W.normal_bf16((L, H, D), 301 + L, dtype="fp16")
+    n = L - prior
+    q = W.normal_bf16((n, H, D), 400 + L, dtype="fp16")
+    NB = (L + bs - 1) // bs + 3
+    kc, vc, tab = W.paginate([(k, v)], bs, NB, 7)
+    got = oracle.attention(q, kc, vc, tab, np.array([0, n]), np.array([L]), 1 / math.sqrt(D), dtype="fp16")
+    ref = dense_causal(W.to_f64(q, "fp16"), W.to_f64(k, "fp16"), W.to_f64(v, "fp16"), 1 / math.sqrt(D), prior)
+    assert np.abs(got - ref).max() < 1e-12
+    # the same bits read as bf16 are other numbers: the format switch is not a no-op
+    other = oracle.attention(q, kc, vc, tab, np.array([0, n]), np.array([L]), 1 / math.sqrt(D), dtype="bf16")
+    assert np.abs(other - ref).max() > 1e-3

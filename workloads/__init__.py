@@ -56,27 +56,41 @@ def _load():
         build()
         lib = ctypes.CDLL(_LIB_PATH)
         u64, p = ctypes.c_uint64, ctypes.c_void_p
-        lib.mpagen_fill_normal_bf16.argtypes = [p, u64, u64, u64]
-        lib.mpagen_fill_normal_bf16.restype = None
-        lib.mpagen_fill_normal_bf16_segments.argtypes = [p, u64, u64, u64, p]
-        lib.mpagen_fill_normal_bf16_segments.restype = None
+        lib.mpagen_fill_normal_16.argtypes = [p, u64, u64, u64, ctypes.c_int]
+        lib.mpagen_fill_normal_16.restype = None
+        lib.mpagen_fill_normal_16_segments.argtypes = [p, u64, u64, u64, p, ctypes.c_int]
+        lib.mpagen_fill_normal_16_segments.restype = None
+        lib.mpagen_round_16.argtypes = [p, p, u64, ctypes.c_int]
+        lib.mpagen_round_16.restype = None
         lib.mpagen_fill_bits.argtypes = [p, u64, u64, u64]
         lib.mpagen_fill_bits.restype = None
         _lib = lib
     return _lib
 
 
-def normal_bf16(shape, seed: int, offset: int = 0) -> np.ndarray:
-    """bf16 bit patterns of N(0,1) draws at counters offset .. offset+prod(shape)."""
+DTYPES = {"bf16": 1, "fp16": 2}   # 16-bit storage formats of q, K, V and the output
+
+
+def normal_bf16(shape, seed: int, offset: int = 0, dtype: str = "bf16") -> np.ndarray:
+    """16-bit patterns (bf16 unless dtype says fp16) of N(0,1) draws at counters offset .. offset+prod(shape)."""
     out = np.empty(shape, dtype=np.uint16)
-    _load().mpagen_fill_normal_bf16(out.ctypes.data, out.size, seed, offset)
+    _load().mpagen_fill_normal_16(out.ctypes.data, out.size, seed, offset, DTYPES[dtype])
     return out
 
 
-def normal_bf16_segments(offsets: np.ndarray, seglen: int, seed: int) -> np.ndarray:
+def normal_bf16_segments(offsets: np.ndarray, seglen: int, seed: int, dtype: str = "bf16") -> np.ndarray:
     offsets = np.ascontiguousarray(offsets, dtype=np.uint64)
     out = np.empty((offsets.size, seglen), dtype=np.uint16)
-    _load().mpagen_fill_normal_bf16_segments(out.ctypes.data, offsets.size, seglen, seed, offsets.ctypes.data)
+    _load().mpagen_fill_normal_16_segments(out.ctypes.data, offsets.size, seglen, seed, offsets.ctypes.data,
+                                           DTYPES[dtype])
+    return out
+
+
+def round_16(a, dtype: str) -> np.ndarray:
+    """The generator's float32 -> 16-bit rounding on its own (for tests)."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    out = np.empty(a.shape, dtype=np.uint16)
+    _load().mpagen_round_16(a.ctypes.data, out.ctypes.data, a.size, DTYPES[dtype])
     return out
 
 
@@ -108,6 +122,13 @@ def bf16_to_f64(a: np.ndarray) -> np.ndarray:
     return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
 
 
+def to_f64(a: np.ndarray, dtype: str = "bf16") -> np.ndarray:
+    """Exact widening of 16-bit patterns of the given format (library conversion for fp16)."""
+    if dtype == "fp16":
+        return np.ascontiguousarray(a, dtype=np.uint16).view(np.float16).astype(np.float64)
+    return bf16_to_f64(a)
+
+
 @dataclass
 class Batch:
     name: str
@@ -123,6 +144,7 @@ class Batch:
     q: np.ndarray = field(default=None)
     content_seed: int = field(default=None)  # seed of the cache content (defaults to `seed`)
     Hkv: int = field(default=None)           # K/V heads (query heads share them in groups); None = H
+    dtype: str = "bf16"                      # storage format of q, K, V, out: "bf16" or "fp16"
 
     # ---- derived metadata -------------------------------------------------------------
     @property
@@ -188,7 +210,7 @@ class Batch:
             pos = int(self.priors[i]) + np.arange(n)
             sm[r0 : r0 + n] = self.block_table[i, pos // bs].astype(np.int64) * bs + pos % bs
         self.slot_map = sm
-        self.q = normal_bf16((T, self.H, self.D), self.seed_q)
+        self.q = normal_bf16((T, self.H, self.D), self.seed_q, dtype=self.dtype)
         return self
 
     def block_contents(self, which: str, ids: np.ndarray) -> np.ndarray:
@@ -196,7 +218,7 @@ class Batch:
         seed = self.seed_k if which == "k" else self.seed_v
         per = self.HK * self.bs * self.D
         offs = np.asarray(ids, dtype=np.uint64) * np.uint64(per)
-        return normal_bf16_segments(offs, per, seed).reshape(len(ids), self.HK, self.bs, self.D)
+        return normal_bf16_segments(offs, per, seed, self.dtype).reshape(len(ids), self.HK, self.bs, self.D)
 
     def new_kv(self):
         """k_new, v_new [T,HK,D]: the values the destination slots are defined to hold."""
@@ -208,7 +230,7 @@ class Batch:
             # one segment of D values per (token, head)
             base = (blk[:, None] * self.HK + np.arange(self.HK)[None, :]) * self.bs + off[:, None]
             offs = (base.astype(np.uint64) * np.uint64(self.D)).reshape(-1)
-            outs.append(normal_bf16_segments(offs, self.D, seed).reshape(self.T, self.HK, self.D))
+            outs.append(normal_bf16_segments(offs, self.D, seed, self.dtype).reshape(self.T, self.HK, self.D))
         return outs[0], outs[1]
 
     def poison_mask(self, ids: np.ndarray, limit: str) -> np.ndarray:
@@ -251,7 +273,8 @@ class Batch:
         cs = np.concatenate([[0], np.cumsum(ql)]).astype(np.int32)
         rows = np.concatenate([np.arange(self.chunk_starts[i], self.chunk_starts[i + 1]) for i in seq_ids])
         b = Batch(self.name + "/compact", self.seed, self.H, self.D, self.bs, max(1, len(old)), cs,
-                  self.context_lens[seq_ids].copy(), newtab, content_seed=self.content_seed, Hkv=self.Hkv)
+                  self.context_lens[seq_ids].copy(), newtab, content_seed=self.content_seed, Hkv=self.Hkv,
+                  dtype=self.dtype)
         b.compact_src = old
         b.rows_src = rows
         b.q = self.q[rows]
@@ -268,7 +291,7 @@ class Batch:
                 parent.blocks_state("v", self.compact_src, limit))
 
 
-def make_batch(name, seed, H, D, bs, NB, q_lens, context_lens, block_ids=None, Hkv=None) -> Batch:
+def make_batch(name, seed, H, D, bs, NB, q_lens, context_lens, block_ids=None, Hkv=None, dtype="bf16") -> Batch:
     """Build a batch from per-sequence (q_len, context_len); block ids are drawn without
     replacement from the pool unless given."""
     q_lens = np.asarray(q_lens, dtype=np.int64)
@@ -286,7 +309,7 @@ def make_batch(name, seed, H, D, bs, NB, q_lens, context_lens, block_ids=None, H
         tab[i, : nb[i]] = block_ids[p : p + nb[i]]
         p += int(nb[i])
     cs = np.concatenate([[0], np.cumsum(q_lens)]).astype(np.int32)
-    return Batch(name, seed, H, D, bs, NB, cs, ctx.astype(np.int32), tab, Hkv=Hkv)._finish()
+    return Batch(name, seed, H, D, bs, NB, cs, ctx.astype(np.int32), tab, Hkv=Hkv, dtype=dtype)._finish()
 
 
 def config_seed(index: int) -> int:
