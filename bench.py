@@ -30,6 +30,14 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix, published
 
 def make_workload(name: str):
     import workloads as W
+    if name.endswith("@fp16"):   # the same batch with IEEE-half storage (the paper's precision)
+        base = name[: -len("@fp16")]
+        makers = {"cfg1": W.config1, "cfg2": W.config2, "cfg3": W.config3, "cfg4": W.config4}
+        if base in makers:
+            return makers[base](dtype="fp16")
+        if base.startswith("cfg5"):
+            return W.config5(int(base.split(":")[1]) if ":" in base else 47, dtype="fp16")
+        raise SystemExit(f"unknown workload {name}")
     if name.startswith(("cfg2@bs", "cfg3@bs")):   # the same batch on KV blocks of 32, 64, 128 tokens
         bs = int(name.split("@bs")[1])
         return W.config2(bs) if name.startswith("cfg2") else W.config3(bs=bs)
@@ -73,7 +81,8 @@ class DeviceWorkload:
         self.q = torch.from_numpy(b.q.view(np.int16)).to(dev)
         self.block_table = torch.from_numpy(np.ascontiguousarray(b.block_table)).to(dev)
         self.out = torch.zeros((b.T, b.H, b.D), dtype=torch.int16, device=dev)
-        self.ctx = mpa.Context(b.H, b.D, block_size=b.bs, num_kv_heads=b.HK)
+        self.ctx = mpa.Context(b.H, b.D, block_size=b.bs, num_kv_heads=b.HK,
+                               dtype=mpa.MPA_FP16 if b.dtype == "fp16" else mpa.MPA_BF16)
         # every timed step plans its batch anew, as the first layer of a model iteration does
         # (the library would otherwise reuse the work list of the identical previous call)
         self.ctx.set_option(mpa.MPA_OPT_PLAN_CACHE, 0)
@@ -166,7 +175,8 @@ def cpu_baseline(b, budget_pair_heads: float = 1.0e9):
     rr = np.repeat(rows, b.H)
     hh = np.tile(np.arange(b.H, dtype=np.int32), rows.size)
     t0 = time.perf_counter()
-    oracle.attention_rows(sub.q, kc, vc, sub.block_table, sub.chunk_starts, sub.context_lens, b.scale, rr, hh)
+    oracle.attention_rows(sub.q, kc, vc, sub.block_table, sub.chunk_starts, sub.context_lens, b.scale, rr, hh,
+                          dtype=b.dtype)
     dt = time.perf_counter() - t0
     est_full = dt * triples_full / triples_sample
     return {
@@ -239,7 +249,7 @@ def main():
     result = {
         "metric": "mixed-batch paged-attn tokens/s", "value": tokens_per_s, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": b.dtype,
         "data": "synthetic",
         "config": {"workload": f"{b.name}: H={b.H} D={b.D} bs={b.bs}, {int((b.q_lens > 1).sum())} prompt chunk(s) "
                                f"{b.q_lens[b.q_lens > 1].tolist()} at prior {b.priors[b.q_lens > 1].tolist()}, "

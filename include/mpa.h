@@ -22,7 +22,8 @@
  *     host memory read during the call only.  The library allocates no device memory.
  *   - Work is enqueued on the HIP stream passed as `stream` (a hipStream_t cast to void*,
  *     NULL = the default stream) and the call returns without waiting for the GPU.
- *   - Element type is bf16 (stored as 16-bit patterns); accumulation is fp32.
+ *   - Elements are 16-bit (bf16 or fp16, fixed per context; passed as bit patterns); scores,
+ *     softmax sums and outputs accumulate in fp32.
  *
  * Tensor layouts (row-major, innermost last)
  *   q, out               : [T, H, D]        T = number of query rows in the batch
@@ -54,7 +55,10 @@ enum {
     MPA_ERR_HIP = -5          /* a HIP runtime call failed; see mpa_last_hip_error          */
 };
 
-enum { MPA_BF16 = 1 };
+enum {
+    MPA_BF16 = 1, /* bfloat16: the upper 16 bits of an IEEE single                              */
+    MPA_FP16 = 2  /* IEEE half, the precision of the paper's experiments (Sec. 6.1)             */
+};
 
 typedef struct {
     int32_t num_heads;    /* H, query heads                                                   */
@@ -62,7 +66,7 @@ typedef struct {
                              (grouped-query attention); HK == H is multi-head attention       */
     int32_t head_dim;     /* D: 64 or 128                                                     */
     int32_t block_size;   /* bs, tokens per KV block: 16, 32, 64 or 128                       */
-    int32_t dtype;        /* MPA_BF16                                                         */
+    int32_t dtype;        /* MPA_BF16 or MPA_FP16: element type of q, k/v, the caches and out   */
 } mpa_config;
 
 /* Tuning / testing knobs for mpa_set_option. */
@@ -134,7 +138,7 @@ int mpa_kv_append(mpa_ctx *ctx, const void *k_new, const void *v_new, const int6
  * Llama-3-70B, Sec. 6.1, whose query heads share K/V heads).  q_len_i == 1 is a generation task, q_len_i > 1 a
  * prompt chunk; both kinds run in one kernel launch.
  *
- *   q            : device, [num_tokens, H, D] bf16, 16-byte aligned
+ *   q            : device, [num_tokens, H, D] of the context's dtype, 16-byte aligned
  *   k_cache, v_cache : device, read only here
  *   block_table  : device, [num_seqs, block_table_stride] int32; entries
  *                  [0, ceil(context_lens[i]/bs)) of row i must be valid block ids (not checked)
@@ -142,7 +146,8 @@ int mpa_kv_append(mpa_ctx *ctx, const void *k_new, const void *v_new, const int6
  *                  chunk_starts[num_seqs] == num_tokens
  *   context_lens : HOST, [num_seqs], context_lens[i] >= q_len_i
  *   scale        : multiplies the scores; <= 0 selects 1/sqrt(D)
- *   out          : device, [num_tokens, H, D] bf16 (round to nearest even of the fp32 result)
+ *   out          : device, [num_tokens, H, D], same dtype (round to nearest even of the fp32
+ *                  result)
  *   workspace    : device, 256-byte aligned, at least mpa_workspace_bytes_for_batch bytes; holds
  *                  the work list and split partial results for the duration of the call's GPU
  *                  work; contents need no initialisation.  Two calls that may overlap on the GPU

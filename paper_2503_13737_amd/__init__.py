@@ -21,6 +21,7 @@ MPA_ERR_WORKSPACE = -3
 MPA_ERR_BAD_BATCH = -4
 MPA_ERR_HIP = -5
 MPA_BF16 = 1
+MPA_FP16 = 2
 MPA_OPT_TG_SPLIT_BLOCKS = 1
 MPA_OPT_PP_SPLIT_TOKENS = 2
 MPA_OPT_PP_ROWSTREAM = 3

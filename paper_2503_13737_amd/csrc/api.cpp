@@ -61,7 +61,7 @@ int mpa_create(mpa_ctx **out, const mpa_config *cfg)
     if (!out || !cfg) return MPA_ERR_INVALID_ARG;
     *out = nullptr;
     if (cfg->num_heads <= 0) return MPA_ERR_INVALID_ARG;
-    if (cfg->dtype != MPA_BF16) return MPA_ERR_UNSUPPORTED;
+    if (cfg->dtype != MPA_BF16 && cfg->dtype != MPA_FP16) return MPA_ERR_UNSUPPORTED;
     if (cfg->num_kv_heads <= 0) return MPA_ERR_INVALID_ARG;
     if (cfg->num_kv_heads > cfg->num_heads || cfg->num_heads % cfg->num_kv_heads != 0) return MPA_ERR_UNSUPPORTED;
     if (cfg->head_dim != 64 && cfg->head_dim != 128) return MPA_ERR_UNSUPPORTED;
@@ -309,13 +309,13 @@ int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache, 
 
     const bool prof = (size_t)(2 * ctx->prof_used + 1) < ctx->prof_events.size();
     if (prof && (e = hipEventRecord(ctx->prof_events[2 * ctx->prof_used], s)) != hipSuccess) return fail(e);
-    int he = launch_attention(p, ctx->cfg.head_dim, stream);
+    int he = launch_attention(p, ctx->cfg.head_dim, ctx->cfg.dtype == MPA_FP16, stream);
     if (he != 0) return fail((hipError_t)he);
     if (prof) {
         if ((e = hipEventRecord(ctx->prof_events[2 * ctx->prof_used + 1], s)) != hipSuccess) return fail(e);
         ++ctx->prof_used;
     }
-    he = launch_merge(p, ctx->cfg.head_dim, stream);
+    he = launch_merge(p, ctx->cfg.head_dim, ctx->cfg.dtype == MPA_FP16, stream);
     if (he != 0) return fail((hipError_t)he);
     return MPA_OK;
 }

@@ -11,17 +11,66 @@ namespace mpa {
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
-__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+// The two 16-bit storage types.  lo/hi widen the halves of a 32-bit word, pack rounds two fp32
+// results to nearest even for the output; weights2 / dot2 / mfma are the matrix-core body's
+// conversion of two softmax weights, their sum, and the 32x32x16 product.
+//
+// kWeightCap: a lane's sum of 16 weights above this makes the body re-reference the row (see
+// tile_compute).  kRefShift: the reference exponent is set this far below the row maximum, so the
+// largest weight is 2^kRefShift right after re-referencing.
+struct Bf16 {
+    typedef __bf16 x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 x8 __attribute__((ext_vector_type(8)));
+    static constexpr float kWeightCap = 0x1p64f;
+    static constexpr float kRefShift = 0.f;
+    static __device__ __forceinline__ float lo(uint32_t w) { return __uint_as_float(w << 16); }
+    static __device__ __forceinline__ float hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+    static __device__ __forceinline__ uint32_t pack(float a, float b)
+    {
+        x2 v = {static_cast<__bf16>(a), static_cast<__bf16>(b)};
+        return __builtin_bit_cast(uint32_t, v);
+    }
+    static __device__ __forceinline__ x2 weights2(float a, float b) { return x2{static_cast<__bf16>(a), static_cast<__bf16>(b)}; }
+    static __device__ __forceinline__ x2 ones2() { return x2{static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)}; }
+    static __device__ __forceinline__ float dot2(x2 a, x2 b, float c) { return __builtin_amdgcn_fdot2_f32_bf16(a, b, c, false); }
+    static __device__ __forceinline__ f32x16 mfma(x8 a, x8 b, f32x16 c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+};
 
-// fp32 -> bf16, round to nearest even (the hardware conversion of gfx950).
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
-{
-    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-    bf16x2 v = {static_cast<__bf16>(lo), static_cast<__bf16>(hi)};
-    return __builtin_bit_cast(uint32_t, v);
-}
+// IEEE half: 5 exponent bits, largest finite value 65504.  Weights are converted with the packed
+// round-toward-zero instruction (one instruction per pair; the row sum is taken from the
+// converted values, so numerator and denominator see the same rounding); it saturates at 65504
+// instead of producing infinity, which the cap below 65504 still catches.  The reference sits 8
+// binades below the row maximum: weights start at up to 2^8, have 7 binades of head room before
+// the cap, and keep full precision down to 2^-22 of the maximum.
+struct Fp16 {
+    typedef _Float16 x2 __attribute__((ext_vector_type(2)));
+    typedef _Float16 x8 __attribute__((ext_vector_type(8)));
+    static constexpr float kWeightCap = 0x1p15f;
+    static constexpr float kRefShift = 8.f;
+    static __device__ __forceinline__ float lo(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w & 0xFFFFu)); }
+    static __device__ __forceinline__ float hi(uint32_t w) { return (float)__builtin_bit_cast(_Float16, (uint16_t)(w >> 16)); }
+    static __device__ __forceinline__ uint32_t pack(float a, float b)
+    {
+        x2 v = {static_cast<_Float16>(a), static_cast<_Float16>(b)};
+        return __builtin_bit_cast(uint32_t, v);
+    }
+    static __device__ __forceinline__ x2 weights2(float a, float b)
+    {
+        return __builtin_bit_cast(x2, __builtin_amdgcn_cvt_pkrtz(a, b));
+    }
+    static __device__ __forceinline__ x2 ones2() { return x2{(_Float16)1.0f, (_Float16)1.0f}; }
+    static __device__ __forceinline__ float dot2(x2 a, x2 b, float c) { return __builtin_amdgcn_fdot2(a, b, c, false); }
+    static __device__ __forceinline__ f32x16 mfma(x8 a, x8 b, f32x16 c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+    }
+};
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -124,7 +173,7 @@ __device__ __forceinline__ void issue_loads(KvRegs<D> &r, const uint16_t *__rest
     for (int i = 0; i < RowCfg<D>::NL; ++i) r.v[i] = __builtin_nontemporal_load(vp + i * 64);
 }
 
-template <int D, bool MASKED>
+template <class E, int D, bool MASKED>
 __device__ __forceinline__ void consume(const KvRegs<D> &r, const float (&qf)[8], float &m,
                                         float &l, float (&acc)[8], int32_t tok0, int32_t limit,
                                         int sub)
@@ -134,14 +183,14 @@ __device__ __forceinline__ void consume(const KvRegs<D> &r, const float (&qf)[8]
 #pragma unroll
     for (int i = 0; i < C::NL; ++i) {
         const u32x4 w = r.k[i];
-        float d = qf[0] * bf16_lo(w.x);
-        d = fmaf(qf[1], bf16_hi(w.x), d);
-        d = fmaf(qf[2], bf16_lo(w.y), d);
-        d = fmaf(qf[3], bf16_hi(w.y), d);
-        d = fmaf(qf[4], bf16_lo(w.z), d);
-        d = fmaf(qf[5], bf16_hi(w.z), d);
-        d = fmaf(qf[6], bf16_lo(w.w), d);
-        d = fmaf(qf[7], bf16_hi(w.w), d);
+        float d = qf[0] * E::lo(w.x);
+        d = fmaf(qf[1], E::hi(w.x), d);
+        d = fmaf(qf[2], E::lo(w.y), d);
+        d = fmaf(qf[3], E::hi(w.y), d);
+        d = fmaf(qf[4], E::lo(w.z), d);
+        d = fmaf(qf[5], E::hi(w.z), d);
+        d = fmaf(qf[6], E::lo(w.w), d);
+        d = fmaf(qf[7], E::hi(w.w), d);
         d = group_sum<C::LPR>(d);
         if (MASKED) {
             const bool valid = tok0 + i * C::TPL + sub < limit;
@@ -166,19 +215,19 @@ __device__ __forceinline__ void consume(const KvRegs<D> &r, const float (&qf)[8]
             const bool valid = tok0 + i * C::TPL + sub < limit;
             if (!valid) w = u32x4{0u, 0u, 0u, 0u};
         }
-        acc[0] = fmaf(p, bf16_lo(w.x), acc[0]);
-        acc[1] = fmaf(p, bf16_hi(w.x), acc[1]);
-        acc[2] = fmaf(p, bf16_lo(w.y), acc[2]);
-        acc[3] = fmaf(p, bf16_hi(w.y), acc[3]);
-        acc[4] = fmaf(p, bf16_lo(w.z), acc[4]);
-        acc[5] = fmaf(p, bf16_hi(w.z), acc[5]);
-        acc[6] = fmaf(p, bf16_lo(w.w), acc[6]);
-        acc[7] = fmaf(p, bf16_hi(w.w), acc[7]);
+        acc[0] = fmaf(p, E::lo(w.x), acc[0]);
+        acc[1] = fmaf(p, E::hi(w.x), acc[1]);
+        acc[2] = fmaf(p, E::lo(w.y), acc[2]);
+        acc[3] = fmaf(p, E::hi(w.y), acc[3]);
+        acc[4] = fmaf(p, E::lo(w.z), acc[4]);
+        acc[5] = fmaf(p, E::hi(w.z), acc[5]);
+        acc[6] = fmaf(p, E::lo(w.w), acc[6]);
+        acc[7] = fmaf(p, E::hi(w.w), acc[7]);
     }
     m = m_new;
 }
 
-template <int D, int NS>
+template <class E, int D, int NS>
 __device__ __forceinline__ void row_body(const AttnParams &p, const WorkItem &it, int head, int lane)
 {
     using C = RowCfg<D>;
@@ -192,10 +241,10 @@ __device__ __forceinline__ void row_body(const AttnParams &p, const WorkItem &it
     {
         const uint4 w = *reinterpret_cast<const uint4 *>(p.q + ((size_t)it.q_row0 * H + head) * D + c * 8);
         const float sc = p.scale_log2e;
-        qf[0] = bf16_lo(w.x) * sc; qf[1] = bf16_hi(w.x) * sc;
-        qf[2] = bf16_lo(w.y) * sc; qf[3] = bf16_hi(w.y) * sc;
-        qf[4] = bf16_lo(w.z) * sc; qf[5] = bf16_hi(w.z) * sc;
-        qf[6] = bf16_lo(w.w) * sc; qf[7] = bf16_hi(w.w) * sc;
+        qf[0] = E::lo(w.x) * sc; qf[1] = E::hi(w.x) * sc;
+        qf[2] = E::lo(w.y) * sc; qf[3] = E::hi(w.y) * sc;
+        qf[4] = E::lo(w.z) * sc; qf[5] = E::hi(w.z) * sc;
+        qf[6] = E::lo(w.w) * sc; qf[7] = E::hi(w.w) * sc;
     }
     float m = -INFINITY, l = 0.f;
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -213,8 +262,8 @@ __device__ __forceinline__ void row_body(const AttnParams &p, const WorkItem &it
         auto blk_of = [&](int j) { return __builtin_amdgcn_readlane(mine, j); };
         auto step = [&](const KvRegs<D> &r, int j) {
             const int32_t tok0 = it.kv_begin + (g0 + j) * kPage;
-            if (tok0 + kPage <= limit) consume<D, false>(r, qf, m, l, acc, tok0, limit, sub);
-            else consume<D, true>(r, qf, m, l, acc, tok0, limit, sub);
+            if (tok0 + kPage <= limit) consume<E, D, false>(r, qf, m, l, acc, tok0, limit, sub);
+            else consume<E, D, true>(r, qf, m, l, acc, tok0, limit, sub);
         };
         // NS register sets rotate: NS-1 blocks (8 KiB each at D=128) are in flight while one is consumed
         KvRegs<D> r[NS];
@@ -252,10 +301,10 @@ __device__ __forceinline__ void row_body(const AttnParams &p, const WorkItem &it
         if (it.part_row < 0) {
             const float inv = 1.f / l;
             uint4 o;
-            o.x = pack_bf16(acc[0] * inv, acc[1] * inv);
-            o.y = pack_bf16(acc[2] * inv, acc[3] * inv);
-            o.z = pack_bf16(acc[4] * inv, acc[5] * inv);
-            o.w = pack_bf16(acc[6] * inv, acc[7] * inv);
+            o.x = E::pack(acc[0] * inv, acc[1] * inv);
+            o.y = E::pack(acc[2] * inv, acc[3] * inv);
+            o.z = E::pack(acc[4] * inv, acc[5] * inv);
+            o.w = E::pack(acc[6] * inv, acc[7] * inv);
             *reinterpret_cast<uint4 *>(p.out + ((size_t)it.q_row0 * H + head) * D + c * 8) = o;
         } else {
             const size_t prow = (size_t)it.part_row * H + head;
@@ -284,9 +333,6 @@ __device__ __forceinline__ void row_body(const AttnParams &p, const WorkItem &it
 //   A: row l % 32, k = 8*half .. 8*half+7        B: column l % 32, k = 8*half .. 8*half+7
 //   C: column l % 32, rows 8*(v/4) + 4*half + v%4 for v = 0..15
 // ------------------------------------------------------------------------------------------
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
@@ -417,13 +463,13 @@ __device__ __forceinline__ void v_wait(VGroup<2> &g)
                  : [n] "n"(N));
 }
 
-template <int D>
-__device__ __forceinline__ void pv_group(f32x16 (&o)[TileCfg<D>::DB], const VGroup<TileCfg<D>::DB> &g, bf16x8 pf)
+template <class E, int D>
+__device__ __forceinline__ void pv_group(f32x16 (&o)[TileCfg<D>::DB], const VGroup<TileCfg<D>::DB> &g, typename E::x8 pf)
 {
 #pragma unroll
     for (int db = 0; db < TileCfg<D>::DB; ++db) {
         const u32x4 both = {g.lo[db].x, g.lo[db].y, g.hi[db].x, g.hi[db].y};
-        o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf, o[db], 0, 0, 0);
+        o[db] = E::mfma(__builtin_bit_cast(typename E::x8, both), pf, o[db]);
     }
 }
 
@@ -459,15 +505,16 @@ __device__ __forceinline__ void k_wait(u32x4 &f)
 // weights are computed against the current m, and only if a lane's partial row sum comes out
 // above 2^64 (or m is still unset) does the wavefront take the row maxima, raise m, rescale l
 // and O, and recompute the weights of that half.
-template <int D, bool LOAD_NEXT, int BUFI>
+template <class E, int D, bool LOAD_NEXT, int BUFI>
 __device__ __forceinline__ void tile_compute(const uint32_t (&kaddr)[TileCfg<D>::KS],
                                              const uint32_t (&vaddr)[TileCfg<D>::DB],
-                                             const bf16x8 (&qf)[TileCfg<D>::KS], f32x16 (&o)[TileCfg<D>::DB],
+                                             const typename E::x8 (&qf)[TileCfg<D>::KS], f32x16 (&o)[TileCfg<D>::DB],
                                              float &m, float &l, float c2, int32_t k0, int32_t pos, int half,
                                              bool masked, const TileNext<D> &next)
 {
     using C = TileCfg<D>;
-    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef typename E::x2 ex2;
+    typedef typename E::x8 ex8;
     constexpr int BUF = C::K_BYTES + C::V_BYTES;
     constexpr int KB0 = BUFI * BUF;                 // K tile of this buffer
     constexpr int PER = 2 * C::DB;                  // LDS reads per V group
@@ -490,18 +537,19 @@ __device__ __forceinline__ void tile_compute(const uint32_t (&kaddr)[TileCfg<D>:
     // Weights j (two scores) of one half: rounded to bf16 in the B-operand layout of the PV
     // product; their sum is taken from the rounded values (the very ones the product uses, so
     // numerator and denominator stay consistent).
-    const bf16x2 ones = {static_cast<__bf16>(1.0f), static_cast<__bf16>(1.0f)};
-    auto weight_pair = [&](const f32x16 &sv, bf16x8 (&pf)[2], float mc, float &sum, int j) {
-        const bf16x2 pr = {static_cast<__bf16>(fast_exp2(fmaf(sv[2 * j], c2, -mc))),
-                           static_cast<__bf16>(fast_exp2(fmaf(sv[2 * j + 1], c2, -mc)))};
+    const ex2 ones = E::ones2();
+    auto weight_pair = [&](const f32x16 &sv, ex8 (&pf)[2], float mc, float &sum, int j) {
+        const ex2 pr = E::weights2(fast_exp2(fmaf(sv[2 * j], c2, -mc)), fast_exp2(fmaf(sv[2 * j + 1], c2, -mc)));
         pf[j >> 2][(2 * j) & 7] = pr[0];
         pf[j >> 2][(2 * j + 1) & 7] = pr[1];
-        sum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, sum, false);
+        sum = E::dot2(pr, ones, sum);
     };
+    // exponent of the weights' reference for a row whose reference score is mref
+    auto ref_exp = [&](float mref) { return fmaf(mref, c2, -E::kRefShift); };
     // After the weights of a half: is the reference still good for every row of the wavefront?
-    auto settle = [&](const f32x16 &sv, bf16x8 (&pf)[2], float sum_a, float sum_b) {
+    auto settle = [&](const f32x16 &sv, ex8 (&pf)[2], float sum_a, float sum_b) {
         float lh = sum_a + sum_b;
-        const bool redo = !(lh <= 0x1p64f) || m == -INFINITY;     // also catches inf and NaN
+        const bool redo = !(lh <= E::kWeightCap) || m == -INFINITY;     // also catches inf and NaN
         if (__builtin_amdgcn_ballot_w64(redo) != 0) {
             float mt = sv[0];
 #pragma unroll
@@ -520,7 +568,7 @@ __device__ __forceinline__ void tile_compute(const uint32_t (&kaddr)[TileCfg<D>:
 #pragma unroll
                 for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
             m = m_new;
-            const float mc = m_fin * c2;
+            const float mc = ref_exp(m_fin);
             float ra = 0.f, rb = 0.f;
 #pragma unroll
             for (int j = 0; j < 8; ++j) weight_pair(sv, pf, mc, (j & 1) ? rb : ra, j);
@@ -548,7 +596,7 @@ __device__ __forceinline__ void tile_compute(const uint32_t (&kaddr)[TileCfg<D>:
         else if (ks == 5) k_wait<(C::KS - 6 < 0 ? 0 : C::KS - 6)>(kf[0][5 % C::KS]);
         else if (ks == 6) k_wait<(C::KS - 7 < 0 ? 0 : C::KS - 7)>(kf[0][6 % C::KS]);
         else k_wait<0>(kf[0][7 % C::KS]);
-        s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[0][ks]), qf[ks], s0, 0, 0, 0);
+        s0 = E::mfma(__builtin_bit_cast(ex8, kf[0][ks]), qf[ks], s0);
         if (LOAD_NEXT && ks % (C::KS / C::NL) == 0) load_part(ks / (C::KS / C::NL));
     }
 #pragma unroll
@@ -559,13 +607,13 @@ __device__ __forceinline__ void tile_compute(const uint32_t (&kaddr)[TileCfg<D>:
 
     // ---- S1 = K1 Q^T (keys 32..63) with the weights of half 0
     k_wait<PER>(kf[1][C::KS - 1]);   // only the V reads may still be under way
-    bf16x8 pf0[2], pf1[2];
+    ex8 pf0[2], pf1[2];
     {
-        const float mc = (m == -INFINITY) ? 0.f : m * c2;
+        const float mc = (m == -INFINITY) ? 0.f : ref_exp(m);
         float sum_a = 0.f, sum_b = 0.f;
 #pragma unroll
         for (int ks = 0; ks < C::KS; ++ks) {
-            s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[1][ks]), qf[ks], s1, 0, 0, 0);
+            s1 = E::mfma(__builtin_bit_cast(ex8, kf[1][ks]), qf[ks], s1);
 #pragma unroll
             for (int j = ks * 8 / C::KS; j < (ks + 1) * 8 / C::KS; ++j) weight_pair(s0, pf0, mc, (j & 1) ? sum_b : sum_a, j);
         }
@@ -576,15 +624,15 @@ __device__ __forceinline__ void tile_compute(const uint32_t (&kaddr)[TileCfg<D>:
 
     // ---- O^T += V0^T P0^T with the weights of half 1
     {
-        const float mc = (m == -INFINITY) ? 0.f : m * c2;
+        const float mc = (m == -INFINITY) ? 0.f : ref_exp(m);
         float sum_a = 0.f, sum_b = 0.f;
         v_wait<PER>(g0);
-        pv_group<D>(o, g0, pf0[0]);
+        pv_group<E, D>(o, g0, pf0[0]);
         v_issue<D, 2, BUFI>(g2, vaddr);
 #pragma unroll
         for (int j = 0; j < 4; ++j) weight_pair(s1, pf1, mc, (j & 1) ? sum_b : sum_a, j);
         v_wait<PER>(g1);
-        pv_group<D>(o, g1, pf0[1]);
+        pv_group<E, D>(o, g1, pf0[1]);
         v_issue<D, 3, BUFI>(g3, vaddr);
 #pragma unroll
         for (int j = 4; j < 8; ++j) weight_pair(s1, pf1, mc, (j & 1) ? sum_b : sum_a, j);
@@ -593,9 +641,9 @@ __device__ __forceinline__ void tile_compute(const uint32_t (&kaddr)[TileCfg<D>:
 
     // ---- O^T += V1^T P1^T
     v_wait<PER>(g2);
-    pv_group<D>(o, g2, pf1[0]);
+    pv_group<E, D>(o, g2, pf1[0]);
     v_wait<0>(g3);
-    pv_group<D>(o, g3, pf1[1]);
+    pv_group<E, D>(o, g3, pf1[1]);
 }
 
 // Pacing of a team (see TeamRef): every kPaceEvery steps wavefront 0 publishes the work-group's
@@ -622,7 +670,7 @@ __device__ __forceinline__ void progress_store(uint32_t *w, uint32_t v)
 // head of the group of a group item (its rows are the group's heads, all at the token q_row0):
 // row r of the item is row (q_row0 * H + head) + r * rstride of q / out seen as [T * H, D], and
 // likewise in the partial buffers.
-template <int D>
+template <class E, int D>
 __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &it, const TeamRef &team, int head,
                                           char *lds)
 {
@@ -641,11 +689,11 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
     const int r_tile = wave * 32 + col;
     const int r_eff = min(r_tile, rows - 1);
     const int32_t pos = grouped ? it.q_pos0 : it.q_pos0 + r_eff;
-    bf16x8 qf[C::KS];
+    typename E::x8 qf[C::KS];
     {
         const uint16_t *qrow = p.q + ((size_t)it.q_row0 * H + head + (size_t)r_eff * rstride) * D + half * 8;
 #pragma unroll
-        for (int ks = 0; ks < C::KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8 *>(qrow + ks * 16);
+        for (int ks = 0; ks < C::KS; ++ks) qf[ks] = *reinterpret_cast<const typename E::x8 *>(qrow + ks * 16);
     }
     const float c2 = p.scale_log2e;
     float m = -INFINITY, l = 0.f;
@@ -747,10 +795,10 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
         }
         if (more) point_at(blk_n);
         if (active && blk_n >= 0 && keys_n >= kKvTile) {
-            tile_compute<D, true, BUFI>(kaddr, vaddr, qf, o, m, l, c2, k0, pos, half, masked, next);
+            tile_compute<E, D, true, BUFI>(kaddr, vaddr, qf, o, m, l, c2, k0, pos, half, masked, next);
         } else {
             if (more) tile_load<D>(next, BUFI ^ 1, blk_n >= 0, keys_n, wave, lane);
-            if (active) tile_compute<D, false, BUFI>(kaddr, vaddr, qf, o, m, l, c2, k0, pos, half, masked, next);
+            if (active) tile_compute<E, D, false, BUFI>(kaddr, vaddr, qf, o, m, l, c2, k0, pos, half, masked, next);
         }
         wait_loads_to_lds();
         if (pace_now && wave == 0) {
@@ -794,8 +842,8 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
                 for (int db = 0; db < C::DB; ++db)
 #pragma unroll
                     for (int g = 0; g < 4; ++g) {
-                        u32x2 w = {pack_bf16(o[db][4 * g] * inv, o[db][4 * g + 1] * inv),
-                                   pack_bf16(o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv)};
+                        u32x2 w = {E::pack(o[db][4 * g] * inv, o[db][4 * g + 1] * inv),
+                                   E::pack(o[db][4 * g + 2] * inv, o[db][4 * g + 3] * inv)};
                         *reinterpret_cast<u32x2 *>(orow + db * 32 + g * 8 + half * 4) = w;
                     }
             } else {
@@ -807,7 +855,7 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
                     for (int g = 0; g < 4; ++g)
                         *reinterpret_cast<float4 *>(arow + db * 32 + g * 8 + half * 4) =
                             make_float4(o[db][4 * g], o[db][4 * g + 1], o[db][4 * g + 2], o[db][4 * g + 3]);
-                if (half == 0) *reinterpret_cast<float2 *>(p.part_ml + prow * 2) = make_float2(m * c2, l_tot);
+                if (half == 0) *reinterpret_cast<float2 *>(p.part_ml + prow * 2) = make_float2(fmaf(m, c2, -E::kRefShift), l_tot);
             }
         }
     }
@@ -832,7 +880,7 @@ __device__ __forceinline__ WorkItem load_item(const WorkItem *src)
 // Unified kernel: work-groups [0, n_tile_items*H) run prompt tiles, the rest run row items
 // (one wavefront per head, kWaves consecutive heads per work-group).
 // ------------------------------------------------------------------------------------------
-template <int D>
+template <class E, int D>
 __global__ void __launch_bounds__(kThreads, 2)
 attention_kernel(const AttnParams p)
 {
@@ -861,7 +909,7 @@ attention_kernel(const AttnParams p)
                 team.size = __builtin_amdgcn_readfirstlane(p.teams[item].size);
                 team.stride = __builtin_amdgcn_readfirstlane(p.teams[item].stride);
             }
-            tile_body<D>(p, it, team, head, lds);
+            tile_body<E, D>(p, it, team, head, lds);
             __syncthreads();   // the next unit's first loads overwrite the tile buffers
         }
         return;
@@ -872,13 +920,13 @@ attention_kernel(const AttnParams p)
     const int head = (idx % hg) * kWaves + wave;
     if (head >= H) return;
     const WorkItem it = load_item(p.items + item);
-    row_body<D, kRowSets>(p, it, head, lane);
+    row_body<E, D, kRowSets>(p, it, head, lane);
 }
 
 // ------------------------------------------------------------------------------------------
 // Merge: one wavefront per (merge row, head).
 // ------------------------------------------------------------------------------------------
-template <int D>
+template <class E, int D>
 __global__ void __launch_bounds__(256)
 merge_kernel(const AttnParams p)
 {
@@ -912,9 +960,9 @@ merge_kernel(const AttnParams p)
     const float inv = 1.f / l;
     uint16_t *o = p.out + ((size_t)mr.out_row * H + head) * D + lane * EPL;
     if (EPL == 2) {
-        *reinterpret_cast<uint32_t *>(o) = pack_bf16(acc[0] * inv, acc[EPL - 1] * inv);
+        *reinterpret_cast<uint32_t *>(o) = E::pack(acc[0] * inv, acc[EPL - 1] * inv);
     } else {
-        *o = (uint16_t)(pack_bf16(acc[0] * inv, 0.f) & 0xFFFFu);
+        *o = (uint16_t)(E::pack(acc[0] * inv, 0.f) & 0xFFFFu);
     }
 }
 
@@ -933,29 +981,29 @@ int launch_kv_append(const void *k_new, const void *v_new, const int64_t *slot_m
     return (int)hipGetLastError();
 }
 
-int launch_attention(const AttnParams &p, int32_t D, void *stream)
+int launch_attention(const AttnParams &p, int32_t D, bool fp16, void *stream)
 {
     const int hg = (p.heads + kWaves - 1) / kWaves;
     const int64_t grid = (int64_t)p.n_tile_wgs + (int64_t)p.n_row_items * hg;
     if (grid == 0) return 0;
     const int64_t units = (int64_t)p.n_tile_items * p.heads + p.n_group_items;
     if (grid > 0x7FFFFFFF || units > 0x7FFFFFFF) return (int)hipErrorInvalidConfiguration;
-    if (D == 128)
-        hipLaunchKernelGGL(attention_kernel<128>, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, p);
-    else
-        hipLaunchKernelGGL(attention_kernel<64>, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, p);
+    void (*kernel)(const AttnParams) =
+        fp16 ? (D == 128 ? attention_kernel<Fp16, 128> : attention_kernel<Fp16, 64>)
+             : (D == 128 ? attention_kernel<Bf16, 128> : attention_kernel<Bf16, 64>);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, p);
     return (int)hipGetLastError();
 }
 
-int launch_merge(const AttnParams &p, int32_t D, void *stream)
+int launch_merge(const AttnParams &p, int32_t D, bool fp16, void *stream)
 {
     const int64_t units = (int64_t)p.n_merge * p.heads;
     if (units == 0) return 0;
     const int64_t grid = (units + 3) / 4;
-    if (D == 128)
-        hipLaunchKernelGGL(merge_kernel<128>, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)stream, p);
-    else
-        hipLaunchKernelGGL(merge_kernel<64>, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)stream, p);
+    void (*kernel)(const AttnParams) =
+        fp16 ? (D == 128 ? merge_kernel<Fp16, 128> : merge_kernel<Fp16, 64>)
+             : (D == 128 ? merge_kernel<Bf16, 128> : merge_kernel<Bf16, 64>);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), 0, (hipStream_t)stream, p);
     return (int)hipGetLastError();
 }
 

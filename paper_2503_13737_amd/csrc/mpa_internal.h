@@ -121,7 +121,7 @@ struct AttnParams {
 // Kernel launchers (kernels.hip).  Return the raw hipError_t as int.
 int launch_kv_append(const void *k_new, const void *v_new, const int64_t *slot_map, int32_t T,
                      int32_t H, int32_t D, int32_t block_size, void *k_cache, void *v_cache, void *stream);
-int launch_attention(const AttnParams &p, int32_t D, void *stream);
-int launch_merge(const AttnParams &p, int32_t D, void *stream);
+int launch_attention(const AttnParams &p, int32_t D, bool fp16, void *stream);
+int launch_merge(const AttnParams &p, int32_t D, bool fp16, void *stream);
 
 }  // namespace mpa

@@ -8,6 +8,9 @@ import workloads as W
 
 MAX_ABS_TOL = 1e-2   # bf16 in, fp32 accumulate, bf16 out
 REL_L2_TOL = 5e-3
+# fp16 carries three more significand bits than bf16 (outputs round at 2^-12 relative, softmax
+# weights truncate at 2^-11): its bars are four times tighter.
+TOL = {"bf16": (MAX_ABS_TOL, REL_L2_TOL), "fp16": (MAX_ABS_TOL / 4, REL_L2_TOL / 4)}
 
 
 def to_dev(a: np.ndarray):
@@ -22,18 +25,19 @@ def to_host_u16(t) -> np.ndarray:
     return t.view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-def errors(got_bits: np.ndarray, ref: np.ndarray):
-    g = W.bf16_to_f64(got_bits)
+def errors(got_bits: np.ndarray, ref: np.ndarray, dtype: str = "bf16"):
+    g = W.to_f64(got_bits, dtype)
     d = g - ref
     return float(np.abs(d).max()), float(np.sqrt((d * d).sum() / max((ref * ref).sum(), 1e-300)))
 
 
-def assert_close(got_bits, ref, what="", abs_scale: float = 1.0):
+def assert_close(got_bits, ref, what="", abs_scale: float = 1.0, dtype: str = "bf16"):
     """abs_scale widens the absolute bound for cases whose outputs are far larger than those of
     the paper's workloads (bf16 outputs and bf16 weights carry a relative error of 2^-8, 2^-9)."""
-    assert not np.isnan(W.bf16_to_f64(got_bits)).any(), f"{what}: NaN in output"
-    ma, rl = errors(got_bits, ref)
-    assert ma <= MAX_ABS_TOL * abs_scale and rl <= REL_L2_TOL, f"{what}: max-abs {ma:.3e} rel-L2 {rl:.3e}"
+    assert not np.isnan(W.to_f64(got_bits, dtype)).any(), f"{what}: NaN in output"
+    ma, rl = errors(got_bits, ref, dtype)
+    abs_tol, rel_tol = TOL[dtype]
+    assert ma <= abs_tol * abs_scale and rl <= rel_tol, f"{what}: max-abs {ma:.3e} rel-L2 {rl:.3e}"
     return ma, rl
 
 
@@ -77,5 +81,5 @@ def oracle_run(b: W.Batch, scale: float | None = None):
     kn, vn = b.new_kv()
     oracle.kv_append(kn, vn, b.slot_map, kc, vc)
     out = oracle.attention(b.q, kc, vc, b.block_table, b.chunk_starts, b.context_lens,
-                           b.scale if scale is None else scale)
+                           b.scale if scale is None else scale, dtype=b.dtype)
     return out, kc, vc

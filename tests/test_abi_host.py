@@ -42,6 +42,8 @@ def test_create_validates_config():
     assert mpa.load().mpa_create(None, None) == mpa.MPA_ERR_INVALID_ARG
     c = mpa.Context(4, 64)
     c.close()
+    mpa.Context(4, 128, dtype=mpa.MPA_FP16).close()
+    assert (mpa.MPA_BF16, mpa.MPA_FP16) == (1, 2)
     assert mpa.load().mpa_destroy(None) == mpa.MPA_OK
     assert mpa.status_string(mpa.MPA_ERR_BAD_BATCH).startswith("malformed")
 

@@ -10,7 +10,7 @@ import numpy as np
 import pytest
 
 import workloads as W
-from harness import MAX_ABS_TOL, REL_L2_TOL, errors, to_host_u16
+from harness import TOL, errors, to_host_u16
 
 sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 
@@ -48,7 +48,7 @@ def check_config(b, max_pp_rows_per_head=None):
     dw.step()
     torch.cuda.synchronize()
     out = to_host_u16(dw.out)
-    assert not np.isnan(W.bf16_to_f64(out)).any(), "NaN (or unwritten rows) in the output"
+    assert not np.isnan(W.to_f64(out, b.dtype)).any(), "NaN (or unwritten rows) in the output"
 
     # kv_append: the blocks holding the new tokens must equal the oracle's append, bit for bit
     touched = np.unique(b.slot_map // b.bs)
@@ -69,14 +69,16 @@ def check_config(b, max_pp_rows_per_head=None):
     rows, heads = sample_rows(b)
     sub = b.compact(range(b.S))
     kc, vc = sub.compact_cache(b, "ctx")
-    ref = oracle.attention_rows(sub.q, kc, vc, sub.block_table, sub.chunk_starts, sub.context_lens, b.scale, rows, heads)
+    ref = oracle.attention_rows(sub.q, kc, vc, sub.block_table, sub.chunk_starts, sub.context_lens, b.scale, rows, heads,
+                                dtype=b.dtype)
     got = out[rows, heads]
-    ma, rl = errors(got, ref)
+    ma, rl = errors(got, ref, b.dtype)
+    abs_tol, rel_tol = TOL[b.dtype]
     print(f"[{b.name}] {rows.size} sampled (row, head) outputs: max-abs {ma:.3e} rel-L2 {rl:.3e}", flush=True)
-    assert ma <= MAX_ABS_TOL and rl <= REL_L2_TOL
+    assert ma <= abs_tol and rl <= rel_tol
     # per-row worst case stays within the absolute bound too
-    per_row = np.abs(W.bf16_to_f64(got) - ref).max(axis=1)
-    assert per_row.max() <= MAX_ABS_TOL
+    per_row = np.abs(W.to_f64(got, b.dtype) - ref).max(axis=1)
+    assert per_row.max() <= abs_tol
     del dw
     torch.cuda.empty_cache()
 
@@ -105,3 +107,9 @@ def test_grouped_kv_layer():
 @pytest.mark.parametrize("iteration", [0, 24, 48])
 def test_config5_long_prompt(iteration):
     check_config(W.config5(iteration))
+
+
+@pytest.mark.parametrize("make", [W.config2, W.config3, W.config4, lambda dtype: W.config5(47, dtype=dtype)],
+                         ids=["cfg2", "cfg3", "cfg4", "cfg5:47"])
+def test_fp16_storage_at_full_size(make):
+    check_config(make(dtype="fp16"))

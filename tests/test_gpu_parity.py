@@ -16,7 +16,7 @@ def mpa():
 
 
 def ctx_for(mpa, b, **opts):
-    c = mpa.Context(b.H, b.D, block_size=b.bs, num_kv_heads=b.HK)
+    c = mpa.Context(b.H, b.D, block_size=b.bs, num_kv_heads=b.HK, dtype=mpa.MPA_FP16 if b.dtype == "fp16" else mpa.MPA_BF16)
     for k, v in opts.items():
         c.set_option(getattr(mpa, k), v)
     return c
@@ -239,3 +239,77 @@ def test_I4_batch_order_independence(mpa):
                             sub.context_lens, out, ws, scale=sub.scale)
     torch.cuda.synchronize()
     assert np.array_equal(to_host_u16(out), base[sub.rows_src])
+
+
+# ------------------------------------------------------------------------------------------------
+# fp16 storage (the precision of the paper's experiments): same cases, IEEE-half patterns in
+# q / K / V / out, against the oracle decoding the same patterns.  The bars are four times
+# tighter than the bf16 ones (see harness.TOL).
+# ------------------------------------------------------------------------------------------------
+def fp16_check(mpa, b, opts_list=({},), scale=None, abs_scale=None, append=True):
+    assert b.dtype == "fp16"
+    ref, okc, ovc = oracle_run(b, scale=scale)
+    for opts in opts_list:
+        out, kc, vc = gpu_run(ctx_for(mpa, b, **opts), b, scale=scale)
+        assert np.array_equal(kc, okc) and np.array_equal(vc, ovc)
+        k = 1.0 if abs_scale is None else abs_scale(ref)
+        assert_close(out, ref, f"{b.name} {opts}", abs_scale=k, dtype="fp16")
+        for i in range(b.S):
+            r0, r1 = b.chunk_starts[i], b.chunk_starts[i + 1]
+            assert_close(out[r0:r1], ref[r0:r1], f"{b.name} {opts} seq {i}", abs_scale=k, dtype="fp16")
+    return ref
+
+
+def test_fp16_config1_all_bodies_and_splits(mpa):
+    b = W.config1(dtype="fp16")
+    fp16_check(mpa, b, [{}, {"MPA_OPT_TG_SPLIT_BLOCKS": 1}, {"MPA_OPT_TG_SPLIT_BLOCKS": 3},
+                        {"MPA_OPT_PP_SPLIT_TOKENS": 64}, {"MPA_OPT_PP_SPLIT_TOKENS": 128, "MPA_OPT_TG_SPLIT_BLOCKS": 2},
+                        {"MPA_OPT_PP_ROWSTREAM": 1}, {"MPA_OPT_PP_RESIDENT_WGS": 2, "MPA_OPT_PP_TEAM_MIN_STEPS": 1}])
+
+
+def test_fp16_and_bf16_contexts_read_the_same_bits_differently(mpa):
+    """The same bit patterns through a bf16 context give other numbers: the dtype reaches the kernels."""
+    b = W.config1(dtype="fp16")
+    ref, _, _ = oracle_run(b)
+    as_bf16 = mpa.Context(b.H, b.D, block_size=b.bs, num_kv_heads=b.HK)
+    out, _, _ = gpu_run(as_bf16, b)
+    ma, _ = errors(out, ref, "fp16")
+    assert not (ma <= 0.1)
+
+
+@pytest.mark.parametrize("seed", range(4))
+@pytest.mark.parametrize("D,H,HK", [(64, 2, 2), (128, 3, 3), (128, 5, 5), (64, 8, 2), (128, 12, 4), (128, 16, 2)])
+def test_fp16_random_ragged_batches(mpa, seed, D, H, HK):
+    b = W.random_ragged(5000 + seed, H=H, D=D, n_pp=2 + seed % 2, n_tg=4, max_q=260, max_prior=400, max_ctx=700,
+                        Hkv=HK, dtype="fp16")
+    fp16_check(mpa, b, [{}, {"MPA_OPT_PP_SPLIT_TOKENS": 128, "MPA_OPT_TG_SPLIT_BLOCKS": 3}])
+
+
+@pytest.mark.parametrize("bs", [16, 32, 128])
+@pytest.mark.parametrize("D,H,HK", [(128, 4, 4), (64, 8, 2)])
+def test_fp16_block_sizes_and_boundaries(mpa, bs, D, H, HK):
+    ql = [300, 77, 129, 1, 1, 1, 1, 1, 1]
+    ctx = [700, 77 + 3 * bs + 5, 129, 1, bs, bs + 1, 5 * bs - 1, 2000, 16]
+    b = W.make_batch(f"fp16-bs{bs}", 655 + bs, H, D, bs, sum((c + bs - 1) // bs for c in ctx) + 3, ql, ctx, Hkv=HK,
+                     dtype="fp16")
+    fp16_check(mpa, b, [{}, {"MPA_OPT_PP_SPLIT_TOKENS": 128, "MPA_OPT_TG_SPLIT_BLOCKS": 1}, {"MPA_OPT_TG_SPLIT_BLOCKS": 3}])
+
+
+@pytest.mark.parametrize("D", [64, 128])
+@pytest.mark.parametrize("scale", [1.0, 4.0, 16.0])
+def test_fp16_steep_softmax(mpa, scale, D):
+    """As test_steep_softmax.  With fp16 weights the range above the reference is 2^16, not 2^128:
+    weights that saturate the format must send the row through the re-referencing path, and the
+    reference shift must reach the partial results' merge unchanged."""
+    ql, ctx = [700, 300, 1, 1, 130], [900, 300, 500, 64, 2000]
+    b = W.make_batch(f"fp16-steep-{scale}-{D}", 91, 4, D, 16, sum((c + 15) // 16 for c in ctx) + 3, ql, ctx, dtype="fp16")
+    fp16_check(mpa, b, [{}, {"MPA_OPT_PP_SPLIT_TOKENS": 256, "MPA_OPT_TG_SPLIT_BLOCKS": 4}], scale=scale,
+               abs_scale=lambda ref: max(1.0, float(np.abs(ref).max())))
+
+
+def test_fp16_flat_softmax_over_a_long_context(mpa):
+    """A tiny scale makes all weights nearly equal: thousands of weights near the reference, row
+    sums far above the fp16 range (they are kept in fp32)."""
+    ql, ctx = [200, 1, 1], [6000, 9000, 3000]
+    b = W.make_batch("fp16-flat", 17, 4, 128, 16, sum((c + 15) // 16 for c in ctx) + 3, ql, ctx, dtype="fp16")
+    fp16_check(mpa, b, [{}, {"MPA_OPT_PP_SPLIT_TOKENS": 1024}], scale=1e-3)

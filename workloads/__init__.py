@@ -312,27 +312,31 @@ def make_batch(name, seed, H, D, bs, NB, q_lens, context_lens, block_ids=None, H
     return Batch(name, seed, H, D, bs, NB, cs, ctx.astype(np.int32), tab, Hkv=Hkv, dtype=dtype)._finish()
 
 
+def _sfx(dtype: str) -> str:
+    return "" if dtype == "bf16" else "-" + dtype
+
+
 def config_seed(index: int) -> int:
     return BASE_SEED * 10 + index
 
 
-def config1() -> Batch:
+def config1(dtype: str = "bf16") -> Batch:
     """Tiny mixed batch: 4 heads, head_dim 64; chunks 37@0 and 64@48; six generation rows."""
     ql = [37, 64, 1, 1, 1, 1, 1, 1]
     ctx = [37, 48 + 64, 10, 33, 64, 100, 150, 200]
-    return make_batch("cfg1-tiny-mixed", config_seed(1), 4, 64, 16, 64, ql, ctx)
+    return make_batch("cfg1-tiny-mixed" + _sfx(dtype), config_seed(1), 4, 64, 16, 64, ql, ctx, dtype=dtype)
 
 
-def config2(bs: int = 16) -> Batch:
+def config2(bs: int = 16, dtype: str = "bf16") -> Batch:
     """13B-shaped layer, generation only: 64 sequences, contexts uniform on [256, 2048].
     bs: tokens per KV block (the pool keeps its size in tokens)."""
     s = config_seed(2)
     ctx = uniform_ints(64, 256, 2048, s * 4 + 3)
-    return make_batch("cfg2-13b-tg" + (f"-bs{bs}" if bs != 16 else ""), s, 40, 128, bs, 32768 * 16 // bs,
-                      np.ones(64, dtype=np.int64), ctx)
+    return make_batch("cfg2-13b-tg" + (f"-bs{bs}" if bs != 16 else "") + _sfx(dtype), s, 40, 128, bs, 32768 * 16 // bs,
+                      np.ones(64, dtype=np.int64), ctx, dtype=dtype)
 
 
-def config3(prior: int | None = None, bs: int = 16) -> Batch:
+def config3(prior: int | None = None, bs: int = 16, dtype: str = "bf16") -> Batch:
     """13B-shaped layer, mixed: one 512-token chunk at prior context uniform on [0, 4096] plus
     48 generation rows with contexts uniform on [512, 4096].  bs: tokens per KV block."""
     s = config_seed(3)
@@ -341,10 +345,11 @@ def config3(prior: int | None = None, bs: int = 16) -> Batch:
     ctx_tg = uniform_ints(48, 512, 4096, s * 4 + 2)
     ql = np.concatenate([[512], np.ones(48, dtype=np.int64)])
     ctx = np.concatenate([[prior + 512], ctx_tg])
-    return make_batch("cfg3-13b-mixed" + (f"-bs{bs}" if bs != 16 else ""), s, 40, 128, bs, 32768 * 16 // bs, ql, ctx)
+    return make_batch("cfg3-13b-mixed" + (f"-bs{bs}" if bs != 16 else "") + _sfx(dtype), s, 40, 128, bs, 32768 * 16 // bs,
+                      ql, ctx, dtype=dtype)
 
 
-def config4() -> Batch:
+def config4(dtype: str = "bf16") -> Batch:
     """12-head slice of a 96-head layer: four 512-token chunks at prior contexts uniform on
     [0, 32768]; 128 generation rows with lognormal contexts (median 1024, sigma 1, cap 8192)."""
     s = config_seed(4)
@@ -353,7 +358,7 @@ def config4() -> Batch:
     ctx_tg = np.clip(np.rint(np.exp(math.log(1024.0) + 1.0 * z)), 1, 8192).astype(np.int64)
     ql = np.concatenate([np.full(4, 512), np.ones(128, dtype=np.int64)])
     ctx = np.concatenate([priors + 512, ctx_tg])
-    return make_batch("cfg4-175b-slice", s, 12, 128, 16, 32768, ql, ctx)
+    return make_batch("cfg4-175b-slice" + _sfx(dtype), s, 12, 128, 16, 32768, ql, ctx, dtype=dtype)
 
 
 def config_gqa() -> Batch:
@@ -375,7 +380,7 @@ CFG5_CHUNK = 2048
 CFG5_ITERS = (CFG5_PROMPT + CFG5_CHUNK - 1) // CFG5_CHUNK  # 49
 
 
-def config5(iteration: int) -> Batch:
+def config5(iteration: int, dtype: str = "bf16") -> Batch:
     """Long prompt: iteration k processes prompt tokens [2048k, min(2048(k+1), 100000)) against
     all earlier ones, batched with 64 generation rows whose contexts start uniform on
     [1024, 16384] and grow by one per iteration.  Block tables are drawn once for all
@@ -403,14 +408,14 @@ def config5(iteration: int) -> Batch:
     cs = np.concatenate([[0], np.cumsum(ql)]).astype(np.int32)
     # the cache content seed stays the config's, so the prompt's K/V is the same in every
     # iteration; only q is redrawn per iteration
-    b = Batch(f"cfg5-long-prompt-it{iteration}", s * 100 + iteration, H, D, bs, NB, cs,
-              ctx.astype(np.int32), tab, content_seed=s)
+    b = Batch(f"cfg5-long-prompt-it{iteration}" + _sfx(dtype), s * 100 + iteration, H, D, bs, NB, cs,
+              ctx.astype(np.int32), tab, content_seed=s, dtype=dtype)
     return b._finish()
 
 
 def random_ragged(seed: int, H: int = 2, D: int = 64, bs: int = 16, n_pp: int = 2, n_tg: int = 3,
                   max_q: int = 70, max_prior: int = 90, max_ctx: int = 120, NB: int | None = None,
-                  Hkv: int | None = None) -> Batch:
+                  Hkv: int | None = None, dtype: str = "bf16") -> Batch:
     """Small random mixed batch for property-style tests (sizes are arbitrary integers)."""
     ql_pp = uniform_ints(n_pp, 2, max_q, seed * 8 + 1) if n_pp else np.zeros(0, dtype=np.int64)
     pr_pp = uniform_ints(n_pp, 0, max_prior, seed * 8 + 2) if n_pp else np.zeros(0, dtype=np.int64)
@@ -420,7 +425,7 @@ def random_ragged(seed: int, H: int = 2, D: int = 64, bs: int = 16, n_pp: int = 
     order = permutation(len(ql), seed * 8 + 4)
     ql, ctx = ql[order], ctx[order]
     need = int(((ctx + bs - 1) // bs).sum())
-    return make_batch(f"ragged-{seed}", seed, H, D, bs, NB or (need + 5), ql, ctx, Hkv=Hkv)
+    return make_batch(f"ragged-{seed}" + _sfx(dtype), seed, H, D, bs, NB or (need + 5), ql, ctx, Hkv=Hkv, dtype=dtype)
 
 
 def f32_to_bf16(a) -> np.ndarray:
