@@ -201,7 +201,8 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
         }
     }
     const int64_t group = opt.heads / opt.kv_heads;
-    const bool rows_on_tiles = group >= kGroupMin && !opt.pp_rowstream;   // generation rows become group items
+    // generation rows become group items (one tile holds the whole group)
+    const bool rows_on_tiles = group >= kGroupMin && group <= kTileRows && !opt.pp_rowstream;
     const int64_t row_split = auto_row_split_tokens(opt, row_tokens);
     // key range of a group item, in keys: enough items for the chip, whole 64-key steps
     const int64_t group_split =

@@ -111,9 +111,9 @@ def test_grouped_kv_heads(mpa, seed, D, H, HK):
         assert_close(out, ref, f"{b.name} H={H} HK={HK} {opts}")
 
 
-@pytest.mark.parametrize("H,HK,D", [(8, 2, 128), (32, 1, 64), (40, 8, 128), (16, 4, 64)])
+@pytest.mark.parametrize("H,HK,D", [(8, 2, 128), (32, 1, 64), (40, 8, 128), (16, 4, 64), (128, 1, 64), (192, 1, 64)])
 def test_generation_rows_of_grouped_heads_on_the_matrix_core_body(mpa, H, HK, D):
-    """Group sizes 4, 5, 32: a generation row runs as one tile per K/V head whose rows are the
+    """Group sizes 4, 5, 32, 128 (a full tile) and 192 (more than a tile: back on the streaming body): a generation row runs as one tile per K/V head whose rows are the
     group's query heads.  Contexts of one key, block and step boundaries, long ones with forced
     short ranges (several partials per row), next to a prompt chunk."""
     ql = [1, 1, 1, 1, 1, 1, 1, 150]

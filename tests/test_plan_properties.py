@@ -75,10 +75,10 @@ def test_resident_and_pacing_options_do_not_change_the_work_list():
         c.set_option(mpa.MPA_OPT_PP_RESIDENT_WGS, -1)
 
 
-@pytest.mark.parametrize("H,HK", [(8, 2), (16, 2), (8, 1), (12, 4), (8, 4)])
+@pytest.mark.parametrize("H,HK", [(8, 2), (16, 2), (8, 1), (12, 4), (8, 4), (128, 1), (256, 1), (384, 2)])
 def test_grouped_heads_plan(H, HK):
     """From group size 4 on generation rows become matrix-core items, one per K/V head and key
-    range (kind 2); below it they stay row items.  Coverage, partial rows and bounds as usual."""
+    range (kind 2); below it, and for groups larger than one tile's 128 rows, they stay row items.  Coverage, partial rows and bounds as usual."""
     b = W.random_ragged(900 + H + HK, H=H, D=128, n_pp=1, n_tg=5, max_q=300, max_prior=1500, max_ctx=4000, Hkv=HK)
     c = mpa.Context(H, 128, num_kv_heads=HK)
     for split in (0, 3):
@@ -86,7 +86,7 @@ def test_grouped_heads_plan(H, HK):
         items, counts = c.plan_describe(b.chunk_starts, b.context_lens)
         kinds = items[:, 7] & 0xFF
         assert counts[0] + counts[1] == len(items)
-        if H // HK >= 4:
+        if 4 <= H // HK <= 128:
             assert counts[1] == 0 and (kinds == 2).sum() > 0 and (items[kinds == 2][:, 4] % 64 == 0).all()
             # group items sit between the prompt tiles and the (absent) row items
             first = int(np.argmax(kinds == 2))
