@@ -1,0 +1,205 @@
+"""Pins of the scheduler oracle (oracle/sched_oracle.py) to what the paper and arithmetic fix:
+its worked chunking example, the stated KVC-demand rule, Eq. 6, the remaining-time formula on
+hand-computed numbers, the nearest-demand choice of Alg. 2 against a brute-force search, and the
+invariants any correct schedule has, over simulated traces.  CPU only."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import sched_oracle as SO
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "paper_block_and_chunk_arithmetic.txt")
+
+
+def golden():
+    out = {}
+    for line in open(GOLDEN):
+        line = line.split("#")[0].strip()
+        if "=" in line:
+            k, v = line.split("=")
+            vals = [float(x) if "." in x else int(x) for x in v.split()]
+            out[k.strip()] = vals[0] if len(vals) == 1 else vals
+    return out
+
+
+def make(b=16, nb=4096, s_pf=768, t_pf=0.1, t_max=0.1, gamma=0.75, max_tokens=8192, order=None):
+    return SO.Scheduler(b, nb, s_pf, t_pf, t_max, gamma, max_tokens, order)
+
+
+def test_paper_dynamic_chunking_example():
+    g = golden()
+    picks = SO.sequential_chunks(g["dyn_chunk_example_lengths"], g["dyn_chunk_example_budgets"], g["dyn_chunk_example_kvc"])
+    assert picks[0] == [(0, 96), (1, 4)]
+    assert [t for it in picks for (i, t) in it if i == 1] == g["dyn_chunk_example_chunks_of_prompt2"]
+
+
+def test_scheduler_cuts_a_prompt_where_budget_or_kvc_ends():
+    """The same rule inside the scheduler: the 8192-token prompt alone with a budget of 300; before
+    the third iteration the rest of the pool is taken away except for 128 tokens."""
+    s = make(b=4, nb=3000, s_pf=300, t_pf=0.1, t_max=0.1)
+    s.add_request(2, 8192, 1, 0.1, 0.1, 0.0)     # SLO == T_pf: S_b == S_pf
+    got = []
+    for it in range(3):
+        if it == 2:
+            del s.free[: len(s.free) - 128 // 4]
+        batch = s.next_batch(0.1 * it)
+        got.append([(e.req.id, e.tokens) for e in batch])
+        s.complete(0.1 * (it + 1))
+    assert got == [[(2, 300)], [(2, 300)], [(2, 128)]] and len(s.free) == 0
+    assert s.next_batch(0.3) == []               # nothing fits any more
+
+
+def test_kvc_demand_rule():
+    g = golden()
+    s = make(b=16)
+    r = SO.Request(1, 101, 5, 1.0, 1.0, 0.0)
+    assert s.new_blocks(r, 37) == 3
+    r.blocks, r.processed = [0, 1, 2], 37
+    assert s.new_blocks(r, 64) == g["new_blocks_b16_prior37_chunk64"]
+    s128 = make(b=128)
+    tot = sum(s128.new_blocks(SO.Request(i, n, 1, 1.0, 1.0, 0.0), n) * 128 for i, n in enumerate([1, 128, 129, 300]))
+    assert tot == g["alloc_b128_lens_1_128_129_300"]
+    # a generation task: no demand while its last block has room, one block when it is full
+    t = SO.Request(2, 31, 9, 1.0, 1.0, 0.0, processed=31, generated=1, state=SO.RETURNED, blocks=[5, 6])
+    assert s.new_blocks(t, 1) == 0       # context 31 -> 32 fits two blocks of 16
+    t.generated = 2
+    assert s.new_blocks(t, 1) == 1       # context 32 -> 33 opens a third
+
+
+def test_token_budget_eq6():
+    g = golden()
+    for s_pf in (g["pivot_forward_size_opt13b"], g["pivot_forward_size_opt175b"]):
+        s = make(s_pf=s_pf, t_pf=0.125, t_max=0.125, max_tokens=100000)
+        s.add_request(1, 50000, 4, 0.125, 0.125, 0.0)
+        s.next_batch(0.0)
+        assert s.token_budget == s_pf                       # SLO_min == T_pf
+        s = make(s_pf=s_pf, t_pf=0.125, t_max=0.125, max_tokens=100000)
+        s.add_request(1, 50000, 4, g["reading_speed_slo"], 0.125, 0.0)
+        s.next_batch(0.0)
+        assert s.token_budget == s_pf * 3 // 2              # 0.1875 / 0.125
+        s = make(s_pf=s_pf, t_pf=0.125, t_max=0.125, max_tokens=1000)
+        s.add_request(1, 50000, 4, 10.0, 0.125, 0.0)
+        s.next_batch(0.0)
+        assert s.token_budget == 1000                        # capped
+
+
+def test_remaining_time_formula():
+    s = make(s_pf=768, t_max=0.2)
+    r = SO.Request(1, 1000, 5, 1.5, 0.1875, 10.0)
+    # waited 0.4 s, 1000 tokens left, L_c = 768 before any chunk: 2 chunks of 0.2 s
+    assert s.remaining_time(r, 10.4) == pytest.approx(1.5 - 0.4 - 0.4, abs=1e-12)
+    s.chunk_tokens, s.chunks = 1000, 4        # L_c = 250 -> 4 chunks
+    assert s.remaining_time(r, 10.4) == pytest.approx(1.5 - 0.4 - 0.8, abs=1e-12)
+    r.processed = 900                          # 100 left -> 1 chunk
+    assert s.remaining_time(r, 10.4) == pytest.approx(1.5 - 0.4 - 0.2, abs=1e-12)
+    t = SO.Request(2, 10, 5, 1.5, 0.1875, 3.0, processed=10, generated=2, state=SO.RETURNED)
+    assert s.remaining_time(t, 99.0) == pytest.approx(0.1875 - 0.2, abs=1e-12)   # no waiting time
+    t.state = SO.PREEMPTED
+    assert s.remaining_time(t, 3.05) == pytest.approx(0.1875 - 0.05 - 0.2, abs=1e-12)
+
+
+def test_queue_order_and_urgency():
+    s = make(s_pf=64, t_pf=0.125, t_max=0.125, gamma=0.0, max_tokens=1000)
+    # three short prompts with SLOs 0.5, 0.1875 (urgent: 0.1875 - 0 - 0.125 <= 0.125), 0.3125
+    s.add_request(1, 10, 1, 0.5, 0.5, 0.0)
+    s.add_request(2, 10, 1, 0.1875, 0.5, 0.0)
+    s.add_request(3, 10, 1, 0.3125, 0.5, 0.0)
+    batch = s.next_batch(0.0)
+    # urgent 2 first; gamma 0 admits only the head of the rest (3)
+    assert [e.req.id for e in batch] == [2, 3]
+    assert s.token_budget == 96                  # 64 * 0.1875 / 0.125, the head's SLO
+
+
+def brute_force_pick(a_c, a_m, b, demands):
+    best, arg = None, None
+    for i, (d_c, d_m) in enumerate(demands):
+        if d_c <= a_c and d_m <= a_m:
+            d = math.hypot(a_c - d_c, a_m - d_m)
+            if best is None or d < best - 1e-9:
+                best, arg = d, i
+    return arg
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_select_requests_takes_the_nearest_demand_first(seed):
+    """First pick of Alg. 2 against a brute-force search over (D_c, D_m) with real square roots."""
+    rng = np.random.default_rng(seed)
+    b, nb = 16, 200
+    s = make(b=b, nb=nb, s_pf=512, t_pf=0.1, t_max=0.1, gamma=100.0, max_tokens=512)
+    lens = rng.integers(1, 700, size=8)
+    for i, n in enumerate(lens):
+        s.add_request(i, int(n), 2, 5.0 + 0.001 * i, 5.0, 0.0)   # nobody urgent, all within gamma
+    batch = s.next_batch(0.0)
+    a_c, a_m = 512, nb * b
+    demands = []
+    for n in lens:
+        d_c = min(int(n), a_c, a_m)
+        demands.append((d_c, -(-d_c // b) * b))
+    first = brute_force_pick(a_c, a_m, b, demands)
+    assert batch[0].req.id == first
+    assert sum(e.tokens for e in batch) <= 512
+
+
+def simulate(s, trace, n_iter, iter_time, on_batch=None):
+    """Feeds a trace to a scheduler; the iteration time follows the forward size."""
+    now, nxt, done = 0.0, 0, []
+    n = len(trace["arrival"])
+    for it in range(n_iter):
+        while nxt < n and trace["arrival"][nxt] <= now:
+            s.add_request(nxt, int(trace["prompt_len"][nxt]), int(trace["max_new"][nxt]),
+                          float(trace["slo_first"][nxt]), float(trace["slo_token"][nxt]), float(trace["arrival"][nxt]))
+            nxt += 1
+        batch = s.next_batch(now)
+        if on_batch:
+            on_batch(s, batch, now)
+        now += iter_time(sum(e.tokens for e in batch))
+        done += s.complete(now)
+    return done
+
+
+@pytest.mark.parametrize("seed,nb", [(1, 4096), (2, 1500), (3, 600)])
+def test_schedule_invariants_over_a_trace(seed, nb):
+    """Whatever the decisions: the budget is never exceeded, no block is ever shared or lost, every
+    request's tokens run exactly once and in order, returned generation tasks stay unless
+    preempted, and at most one new long prompt starts while another is in progress (urgent ones
+    aside).  The small pools force preemptions and recomputation."""
+    b = 16
+    trace = W.poisson_trace(150, seed, rate=8.0, max_prompt=3000, max_new=64)
+    s = make(b=b, nb=nb, s_pf=768, t_pf=0.05, t_max=0.05, gamma=0.75, max_tokens=2048)
+    seen = {}
+    state = {"batches": 0, "tokens": 0, "preempted": 0}
+
+    def check(s, batch, now):
+        assert sum(e.tokens for e in batch) <= s.token_budget
+        ids = [e.req.id for e in batch]
+        assert len(set(ids)) == len(ids)
+        held = [blk for r in s.reqs.values() for blk in r.blocks]
+        assert len(set(held)) == len(held) and not (set(held) & set(s.free))
+        assert len(held) + len(s.free) == nb
+        _, cs, ctx, slots, tables = s.batch_arrays()
+        assert len(set(slots)) == len(slots)
+        for e, c, tab in zip(batch, ctx, tables):
+            r = e.req
+            assert len(tab) == -(-c // b) == len(r.blocks)
+            prior = c - e.tokens
+            hist = seen.setdefault(r.id, [0, 0])     # [tokens in cache, recomputations]
+            if prior == 0 and hist[0] != 0:
+                hist[0] = 0                           # recomputation restarts the sequence
+                hist[1] += 1
+            assert prior == hist[0]
+            hist[0] = c
+        state["batches"] += 1
+        state["tokens"] += sum(e.tokens for e in batch)
+        state["preempted"] += len(s.preempted_now)
+
+    done = simulate(s, trace, 1500, lambda sf: 0.05 * max(sf, 64) / 768, check)
+    assert len(done) == len(set(done)) and len(done) > 30
+    assert state["tokens"] > 0
+    if nb <= 600:
+        assert state["preempted"] > 0
+    for rid in done:
+        # a finished request was fed its prompt and all generated tokens but the last
+        assert seen[rid][0] >= int(trace["prompt_len"][rid])

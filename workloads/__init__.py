@@ -456,3 +456,42 @@ def paginate(kv_per_seq, bs: int, NB: int, seed: int):
             kc[b, :, o, :] = k[t]
             vc[b, :, o, :] = v[t]
     return kc, vc, tab
+
+
+# ------------------------------------------------------------------------------------------------
+# Request traces for the scheduler (inputs only: arrival times, lengths, SLOs).
+# ------------------------------------------------------------------------------------------------
+def _uniform01(n: int, seed: int) -> np.ndarray:
+    return ((bits(n, seed) >> np.uint64(11)).astype(np.float64) + 0.5) / 9007199254740992.0
+
+
+def _log_uniform_ints(u: np.ndarray, lo: int, hi: int) -> np.ndarray:
+    return np.clip(np.floor(np.exp(math.log(lo) + u * (math.log(hi + 1) - math.log(lo)))), lo, hi).astype(np.int64)
+
+
+def poisson_trace(n: int, seed: int, rate: float = 8.0, max_prompt: int = 100_000, max_new: int = 2048,
+                  base_token_slo: float = 0.1875, base_first_slo: float = 1.5):
+    """n requests shaped like the paper's mixed trace (Sec. 3 setup and request features): Poisson
+    arrivals at `rate` per second; prompt lengths 34 % in [10, 512], 52 % in [512, 4096], 14 %
+    above (to max_prompt), outputs 51 % / 36 % / 13 % over the same ranges and cut at max_new
+    (log-uniform inside a range); heterogeneous SLOs: the per-token SLO is 1, 2 or 4 times the
+    reading speed of 0.1875 s/token, the first-token SLO the same multiple of base_first_slo.
+    Returns a dict of arrays: arrival (s), prompt_len, max_new, slo_first, slo_token."""
+    gaps = -np.log(_uniform01(n, seed * 16 + 1)) / rate
+    arrival = np.cumsum(gaps)
+
+    def lengths(cls_u, in_u, shares, cap):
+        out = np.empty(n, dtype=np.int64)
+        c0, c1 = shares
+        small, mid = cls_u < c0, (cls_u >= c0) & (cls_u < c0 + c1)
+        big = ~(small | mid)
+        out[small] = _log_uniform_ints(in_u[small], 10, 512)
+        out[mid] = _log_uniform_ints(in_u[mid], 512, 4096)
+        out[big] = _log_uniform_ints(in_u[big], 4096, max(cap, 4097))
+        return np.minimum(out, cap)
+
+    prompt = lengths(_uniform01(n, seed * 16 + 2), _uniform01(n, seed * 16 + 3), (0.34, 0.52), max_prompt)
+    new = lengths(_uniform01(n, seed * 16 + 4), _uniform01(n, seed * 16 + 5), (0.51, 0.36), max_new)
+    mult = np.array([1.0, 2.0, 4.0])[(bits(n, seed * 16 + 6) % np.uint64(3)).astype(np.int64)]
+    return {"arrival": arrival, "prompt_len": prompt, "max_new": new,
+            "slo_first": base_first_slo * mult, "slo_token": base_token_slo * mult}
