@@ -33,12 +33,25 @@ EXPORTS = [
     "mpa_create", "mpa_destroy", "mpa_set_option", "mpa_last_hip_error", "mpa_status_string",
     "mpa_workspace_bytes_for_batch", "mpa_workspace_bytes", "mpa_kv_append",
     "mpa_mixed_paged_attention", "mpa_plan_describe", "mpa_profile_enable", "mpa_profile_read",
+    "mpa_sched_create", "mpa_sched_destroy", "mpa_sched_add_request", "mpa_sched_next_batch",
+    "mpa_sched_batch_arrays", "mpa_sched_complete", "mpa_sched_live_requests",
 ]
 
 
 class MpaConfig(ctypes.Structure):
     _fields_ = [("num_heads", ctypes.c_int32), ("num_kv_heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32), ("block_size", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+
+
+class SchedConfig(ctypes.Structure):
+    _fields_ = [("block_size", ctypes.c_int32), ("num_blocks", ctypes.c_int32),
+                ("pivot_forward_size", ctypes.c_int32), ("max_batch_tokens", ctypes.c_int32),
+                ("pivot_time", ctypes.c_double), ("max_batch_time", ctypes.c_double), ("gamma", ctypes.c_double)]
+
+
+class SchedBatch(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("num_seqs", "num_tokens", "token_budget", "num_prompt_chunks",
+                                              "num_generation", "num_preempted", "max_blocks_per_seq", "free_blocks")]
 
 
 class MpaError(RuntimeError):
@@ -83,6 +96,21 @@ def load() -> ctypes.CDLL:
         lib.mpa_profile_read.restype = ctypes.c_int
         lib.mpa_plan_describe.argtypes = [vp, vp, vp, i32, vp, i64, vp]
         lib.mpa_plan_describe.restype = i64
+        f64 = ctypes.c_double
+        lib.mpa_sched_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(SchedConfig), vp]
+        lib.mpa_sched_create.restype = ctypes.c_int
+        lib.mpa_sched_destroy.argtypes = [vp]
+        lib.mpa_sched_destroy.restype = ctypes.c_int
+        lib.mpa_sched_add_request.argtypes = [vp, i64, i32, i32, f64, f64, f64]
+        lib.mpa_sched_add_request.restype = ctypes.c_int
+        lib.mpa_sched_next_batch.argtypes = [vp, f64, ctypes.POINTER(SchedBatch)]
+        lib.mpa_sched_next_batch.restype = ctypes.c_int
+        lib.mpa_sched_batch_arrays.argtypes = [vp, vp, vp, vp, vp, vp, i32]
+        lib.mpa_sched_batch_arrays.restype = ctypes.c_int
+        lib.mpa_sched_complete.argtypes = [vp, f64, vp, i32, vp]
+        lib.mpa_sched_complete.restype = ctypes.c_int
+        lib.mpa_sched_live_requests.argtypes = [vp]
+        lib.mpa_sched_live_requests.restype = i32
         _lib = lib
     return _lib
 
@@ -214,3 +242,71 @@ def mixed_paged_attention(ctx: Context, q, k_cache, v_cache, block_table, chunk_
                           workspace, scale: float = 0.0, stream=None):
     ctx.mixed_paged_attention(q, k_cache, v_cache, block_table, chunk_starts, context_lens, out, workspace,
                               scale, stream)
+
+
+class Scheduler:
+    """Owns an mpa_sched (include/mpa_sched.h): forms the batch of every iteration and returns the
+    arrays mpa_kv_append / mpa_mixed_paged_attention take.  Host only."""
+
+    def __init__(self, block_size: int, num_blocks: int, pivot_forward_size: int, pivot_time: float,
+                 max_batch_time: float, gamma: float, max_batch_tokens: int, block_order=None):
+        self._lib = load()
+        self._h = ctypes.c_void_p()
+        cfg = SchedConfig(block_size, num_blocks, pivot_forward_size, max_batch_tokens, pivot_time, max_batch_time, gamma)
+        order = None if block_order is None else _host_i32(block_order)
+        if order is not None and order.size != num_blocks:
+            raise MpaError(MPA_ERR_INVALID_ARG, "mpa_sched_create")
+        st = self._lib.mpa_sched_create(ctypes.byref(self._h), ctypes.byref(cfg), _ptr(order))
+        if st != MPA_OK:
+            raise MpaError(st, "mpa_sched_create")
+        self.info = SchedBatch()
+
+    def close(self):
+        if self._h:
+            self._lib.mpa_sched_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def add_request(self, rid: int, prompt_len: int, max_new_tokens: int, slo_first: float, slo_token: float, now: float):
+        st = self._lib.mpa_sched_add_request(self._h, rid, prompt_len, max_new_tokens, slo_first, slo_token, now)
+        if st != MPA_OK:
+            raise MpaError(st, "mpa_sched_add_request")
+
+    def next_batch(self, now: float) -> SchedBatch:
+        st = self._lib.mpa_sched_next_batch(self._h, now, ctypes.byref(self.info))
+        if st != MPA_OK:
+            raise MpaError(st, "mpa_sched_next_batch")
+        return self.info
+
+    def batch_arrays(self, stride: int | None = None):
+        """(request_ids [S] int64, chunk_starts [S+1] int32, context_lens [S] int32, slot_map [T] int64,
+        block_table [S, stride] int32) of the batch formed last."""
+        i = self.info
+        stride = max(i.max_blocks_per_seq, 1) if stride is None else stride
+        ids = np.empty(i.num_seqs, dtype=np.int64)
+        cs = np.empty(i.num_seqs + 1, dtype=np.int32)
+        ctx = np.empty(i.num_seqs, dtype=np.int32)
+        slots = np.empty(i.num_tokens, dtype=np.int64)
+        table = np.empty((i.num_seqs, stride), dtype=np.int32)
+        st = self._lib.mpa_sched_batch_arrays(self._h, _ptr(ids), _ptr(cs), _ptr(ctx), _ptr(slots), _ptr(table), stride)
+        if st != MPA_OK:
+            raise MpaError(st, "mpa_sched_batch_arrays")
+        return ids, cs, ctx, slots, table
+
+    def complete(self, now: float) -> np.ndarray:
+        cap = max(self.info.num_seqs, 1)
+        out = np.empty(cap, dtype=np.int64)
+        n = ctypes.c_int32(0)
+        st = self._lib.mpa_sched_complete(self._h, now, _ptr(out), cap, ctypes.byref(n))
+        if st != MPA_OK:
+            raise MpaError(st, "mpa_sched_complete")
+        return out[: n.value].copy()
+
+    @property
+    def live_requests(self) -> int:
+        return int(self._lib.mpa_sched_live_requests(self._h))
