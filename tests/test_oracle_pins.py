@@ -25,7 +25,8 @@ def read_golden():
         line = line.split("#")[0].strip()
         if "=" in line:
             k, v = line.split("=")
-            vals[k.strip()] = int(v)
+            if len(v.split()) == 1 and "." not in v:     # the scheduler's entries (lists, seconds) are read by its own pins
+                vals[k.strip()] = int(v)
     return vals
 
 
