@@ -495,3 +495,12 @@ def poisson_trace(n: int, seed: int, rate: float = 8.0, max_prompt: int = 100_00
     mult = np.array([1.0, 2.0, 4.0])[(bits(n, seed * 16 + 6) % np.uint64(3)).astype(np.int64)]
     return {"arrival": arrival, "prompt_len": prompt, "max_new": new,
             "slo_first": base_first_slo * mult, "slo_token": base_token_slo * mult}
+
+
+def token_rows(request_ids, positions, width: int, seed: int, dtype: str = "bf16") -> np.ndarray:
+    """One row of `width` N(0,1) draws per (request, position) pair, a function of the pair alone:
+    the content of a token of a scheduled request, whichever iteration or block it lands in."""
+    rid = np.asarray(request_ids, dtype=np.uint64)
+    pos = np.asarray(positions, dtype=np.uint64)
+    offs = (rid * np.uint64(1 << 20) + pos) * np.uint64(width)
+    return normal_bf16_segments(offs, width, seed, dtype)
