@@ -15,6 +15,7 @@ from __future__ import annotations
 
 import argparse
 import json
+import math
 import os
 import sys
 import time
@@ -187,6 +188,143 @@ def cpu_baseline(b, budget_pair_heads: float = 1.0e9):
     }
 
 
+def run_scheduled(args, mpa):
+    """Workload "sched13b": the batches come from the scheduler (include/mpa_sched.h) driven by a
+    Poisson trace with the paper's length mix, on an OPT-13B-shaped layer with the paper's block
+    size (32) and pivot forward size (768).  A step is one iteration: arrivals, scheduling decision,
+    upload of its arrays, kv_append + mixed_paged_attention, completion.  The scheduler's clock is a
+    model of the whole network's iteration time (20 ms + 30 ms per 768 tokens: T_pf = 50 ms at the
+    pivot); the arrival rate puts the modelled system at 70 % load, where it reaches a steady state
+    of about a hundred generation tasks next to the prompt chunks.  The cache pool holds seeded random
+    values everywhere (this workload measures speed; parity on scheduled batches is a test)."""
+    import torch
+    import workloads as W
+    H, HK, D, bs, NB = 40, 40, 128, 32, 16384
+    s_pf, t_pf, gamma, max_tokens = 768, 0.05, 0.75, 4096
+    n_req = 6000
+    trace = W.poisson_trace(n_req, 31, rate=1.0, max_prompt=16384, max_new=2048)
+    mean_tokens = float((trace["prompt_len"] + trace["max_new"]).mean())
+    rate = 0.7 * (s_pf / t_pf) / mean_tokens
+    trace["arrival"] = trace["arrival"] / rate
+    iter_time = lambda sf: 0.02 + 0.03 * sf / s_pf
+    t_max = iter_time(s_pf * 0.1875 / t_pf)   # the budget of the tightest SLO class
+    order = W.permutation(NB, 31)
+    dev = "cuda"
+    g = torch.Generator(device=dev)
+    g.manual_seed(31)
+    caches = []
+    for _ in range(2):
+        c = torch.empty((NB, HK, bs, D), dtype=torch.bfloat16, device=dev)
+        for s0 in range(0, NB, 2048):
+            c[s0:s0 + 2048].normal_(generator=g)
+        caches.append(c.view(torch.int16))
+    k_cache, v_cache = caches
+    pool = torch.empty((3, max_tokens, H, D), dtype=torch.bfloat16, device=dev).normal_(generator=g).view(torch.int16)
+    q_all, k_all, v_all = pool[0], pool[1], pool[2]
+    out = torch.empty((max_tokens, H, D), dtype=torch.int16, device=dev)
+    ctx = mpa.Context(H, D, block_size=bs, num_kv_heads=HK)
+    ws = {"buf": torch.empty(1 << 30, dtype=torch.uint8, device=dev)}
+    sched = mpa.Scheduler(bs, NB, s_pf, t_pf, t_max, gamma, max_tokens, block_order=order)
+    state = {"now": 0.0, "next": 0}
+
+    def arrivals(sc):
+        while state["next"] < n_req and trace["arrival"][state["next"]] <= state["now"]:
+            i = state["next"]
+            sc.add_request(i, int(trace["prompt_len"][i]), int(trace["max_new"][i]), float(trace["slo_first"][i]),
+                           float(trace["slo_token"][i]), float(trace["arrival"][i]))
+            state["next"] += 1
+
+    # reach a steady state without the GPU (the pool's content is valid everywhere)
+    pre = 6000
+    for _ in range(pre):
+        arrivals(sched)
+        info = sched.next_batch(state["now"])
+        state["now"] += iter_time(info.num_tokens)
+        sched.complete(state["now"])
+    snapshot = dict(state)
+
+    def iteration(timed):
+        t0 = time.perf_counter()
+        arrivals(sched)
+        info = sched.next_batch(state["now"])
+        ids, cs, ctxl, slots, table = sched.batch_arrays()
+        t1 = time.perf_counter()
+        T = info.num_tokens
+        if T:
+            d_slots = torch.from_numpy(slots).to(dev, non_blocking=True)
+            d_table = torch.from_numpy(table).to(dev, non_blocking=True)
+            need = ctx.workspace_bytes_for_batch(cs, ctxl)
+            if need > ws["buf"].numel():
+                torch.cuda.synchronize()
+                ws["buf"] = torch.empty(need * 2, dtype=torch.uint8, device=dev)
+            ctx.kv_append(k_all[:T, :HK], v_all[:T, :HK], d_slots, k_cache, v_cache)
+            ctx.mixed_paged_attention(q_all[:T], k_cache, v_cache, d_table, cs, ctxl, out[:T], ws["buf"], scale=1.0 / math.sqrt(D))
+        t2 = time.perf_counter()
+        state["now"] += iter_time(T)
+        sched.complete(state["now"])
+        t3 = time.perf_counter()
+        if timed is not None:
+            timed["sched_s"] += (t1 - t0) + (t3 - t2)
+            timed["tokens"] += T
+            timed["seqs"] += info.num_seqs
+            timed["chunks"] += info.num_prompt_chunks
+            timed["chunk_tokens"] += T - info.num_generation
+            timed["bytes"] += int(ctxl.sum()) * 4 * D * HK + T * H * D * 4
+            timed["kv_tokens"] += int(ctxl.sum())
+            timed["launches"] += 1 if T else 0
+            timed["live"] += sched.live_requests
+
+    for _ in range(args.warmup):
+        iteration(None)
+    torch.cuda.synchronize()
+    ctx.profile_enable(args.steps)
+    timed = dict.fromkeys(["sched_s", "tokens", "seqs", "chunks", "chunk_tokens", "bytes", "kv_tokens", "launches", "live"], 0)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        iteration(timed)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = ctx.profile_read(args.steps)
+    ctx.profile_enable(0)
+    kernel_s = float(ms.sum()) * 1e-3
+    achieved = timed["bytes"] / kernel_s / 1e9
+    k = args.steps
+    result = {
+        "metric": "scheduler-driven mixed-batch paged-attn tokens/s", "value": timed["tokens"] / wall, "unit": "tokens/s",
+        "n_gpus": 1, "steps": k, "warmup": args.warmup, "ms_per_step": wall * 1e3 / k, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"sched13b: H={H} D={D} bs={bs}, pool {NB} blocks, S_pf={s_pf}, gamma={gamma}, Poisson trace at "
+                               f"{rate:.2f} req/s (70 % of the modelled capacity), {pre} iterations of run-in; per iteration: "
+                               f"{timed['seqs'] / k:.1f} sequences, {timed['tokens'] / k:.1f} tokens "
+                               f"({timed['chunks'] / k:.2f} prompt chunks of {timed['chunk_tokens'] / max(timed['chunks'], 1):.0f} tokens), "
+                               f"{timed['kv_tokens'] / k:.0f} KV tokens read, {timed['live'] / k:.0f} live requests",
+                   "step": "arrivals + scheduling decision + array upload + kv_append + mixed_paged_attention + completion"},
+        "scheduler": {"us_per_iteration": timed["sched_s"] * 1e6 / k, "fraction_of_step": timed["sched_s"] / wall},
+        "roofline": {"kernel": "attention_kernel (scheduled batches)", "bound": "hbm", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes": timed["bytes"] / max(timed["launches"], 1), "kernel_ms": kernel_s * 1e3 / max(timed["launches"], 1)},
+    }
+    if not args.no_cpu_baseline:
+        # the scheduler oracle over the same run-in and timed iterations (decisions only)
+        from oracle import sched_oracle as SO
+        o = SO.Scheduler(bs, NB, s_pf, t_pf, t_max, gamma, max_tokens, order)
+        state.update(now=0.0, next=0)
+        n_it, t_or = pre + args.warmup + k, 0.0
+        for it in range(n_it):
+            arrivals(o)
+            t0 = time.perf_counter()
+            batch = o.next_batch(state["now"])
+            o.batch_arrays()
+            state["now"] += iter_time(sum(e.tokens for e in batch))
+            o.complete(state["now"])
+            if it >= pre + args.warmup:
+                t_or += time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": k / t_or, "unit": "scheduling iterations/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"the scheduler oracle (Python) on the same {k} timed iterations of the same trace; "
+                                            f"the library takes {timed['sched_s'] * 1e6 / k:.0f} us per iteration"}
+    print(json.dumps(result), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -211,6 +349,9 @@ def main():
     import paper_2503_13737_amd as mpa
     mpa.load()  # fails loudly when the HIP library is missing
 
+    if args.workload == "sched13b":
+        run_scheduled(args, mpa)
+        return
     b = make_workload(args.workload)
     dw = DeviceWorkload(b, mpa)
     torch.cuda.synchronize()
