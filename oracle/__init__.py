@@ -63,6 +63,19 @@ def kv_append(k_new, v_new, slot_map, k_cache, v_cache):
                                  T, H, D, bs, k_cache.ctypes.data, v_cache.ctypes.data)
 
 
+def copy_blocks(src_k, src_v, dst_k, dst_v, pairs):
+    """Whole-block copies between cache pools ([NB,HK,bs,D] uint16 each), in place on dst_k/dst_v:
+    block pairs[i][1] of the destination becomes block pairs[i][0] of the source, K and V, all
+    heads.  This is what moving a preempted request's blocks to another pool and back amounts to
+    (the engine's handling of KVC overflow, paper Sec. 5).  Written as the definition: one
+    assignment per pair, in order."""
+    pairs = np.asarray(pairs, dtype=np.int64).reshape(-1, 2)
+    assert src_k.shape[1:] == dst_k.shape[1:] and src_v.shape[1:] == dst_v.shape[1:]
+    for s, d in pairs:
+        dst_k[d] = src_k[s]
+        dst_v[d] = src_v[s]
+
+
 DTYPES = {"bf16": 1, "fp16": 2}
 
 

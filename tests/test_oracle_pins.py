@@ -422,3 +422,36 @@ def test_brute_force_dense_fp16(L, prior, H, D, bs):
     # the same bits read as bf16 are other numbers: the format switch is not a no-op
     other = oracle.attention(q, kc, vc, tab, np.array([0, n]), np.array([L]), 1 / math.sqrt(D), dtype="bf16")
     assert np.abs(other - ref).max() > 1e-3
+
+
+# ---------------------------------------------------------------- block copies (swap out / in)
+def test_copy_blocks_round_trip_and_untouched_blocks():
+    """Out to a second pool and back in to other blocks: the moved blocks arrive bit for bit, every
+    other block of both pools keeps its content, and attention through the re-mapped table gives
+    the identical result (blocks are position-independent)."""
+    b = W.config1()
+    kc, vc = b.full_cache("ctx")
+    seq = 7
+    nblk = int(b.n_blocks()[seq])
+    held = b.block_table[seq, :nblk].astype(np.int64)
+    host_k = np.full((nblk + 2,) + kc.shape[1:], 0x1234, dtype=np.uint16)
+    host_v = host_k.copy()
+    out_pairs = np.stack([held, np.arange(nblk)[::-1]], axis=1)
+    oracle.copy_blocks(kc, vc, host_k, host_v, out_pairs)
+    for s, d in out_pairs:
+        for byte_for_byte in (np.array_equal(host_k[d], kc[s]), np.array_equal(host_v[d], vc[s])):
+            assert byte_for_byte
+    assert (host_k[nblk:] == 0x1234).all() and (host_v[nblk:] == 0x1234).all()
+    # back in, to blocks nobody references
+    free = np.setdiff1d(np.arange(b.NB), b.referenced_blocks())[:nblk].astype(np.int64)
+    kc2, vc2 = kc.copy(), vc.copy()
+    kc2[held], vc2[held] = W.POISON, W.POISON
+    oracle.copy_blocks(host_k, host_v, kc2, vc2, np.stack([np.arange(nblk)[::-1], free], axis=1))
+    assert np.array_equal(kc2[free], kc[held]) and np.array_equal(vc2[free], vc[held])
+    others = np.setdiff1d(np.arange(b.NB), np.concatenate([held, free]))
+    assert np.array_equal(kc2[others], kc[others])
+    tab2 = b.block_table.copy()
+    tab2[seq, :nblk] = free
+    ref = oracle.attention(b.q, kc, vc, b.block_table, b.chunk_starts, b.context_lens, b.scale)
+    got = oracle.attention(b.q, kc2, vc2, tab2, b.chunk_starts, b.context_lens, b.scale)
+    assert np.array_equal(got, ref)
