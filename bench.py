@@ -325,6 +325,46 @@ def run_scheduled(args, mpa):
     print(json.dumps(result), flush=True)
 
 
+def run_copy_blocks(args, mpa):
+    """Workload "swap13b": mpa_copy_blocks moving the 2,048 scattered blocks of preempted requests
+    (64 K tokens of an OPT-13B-shaped layer, block size 32) from the cache pool to a second pool.
+    A step is one call; bytes = blocks x block bytes x (K and V) x (read + write)."""
+    import torch
+    import workloads as W
+    HK, D, bs, NB, n = 40, 128, 32, 8192, 2048
+    ctx = mpa.Context(HK, D, block_size=bs)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(7)
+    pool = [torch.empty((NB, HK, bs, D), dtype=torch.bfloat16, device="cuda").normal_(generator=g).view(torch.int16) for _ in range(2)]
+    other = [torch.zeros((n, HK, bs, D), dtype=torch.int16, device="cuda") for _ in range(2)]
+    pairs = np.stack([W.permutation(NB, 7)[:n], W.permutation(n, 8)], axis=1).astype(np.int64)
+    d_pairs = torch.from_numpy(pairs).cuda()
+    call = lambda: ctx.copy_blocks(pool[0], pool[1], other[0], other[1], d_pairs)
+    for _ in range(args.warmup):
+        call()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]   # the calls go to torch's current stream
+    t0 = time.perf_counter()
+    ev[0].record()
+    for _ in range(args.steps):
+        call()
+    ev[1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = ev[0].elapsed_time(ev[1]) / args.steps
+    by = n * HK * bs * D * 2 * 2 * 2
+    ok = bool(torch.equal(other[0][d_pairs[:, 1]], pool[0][d_pairs[:, 0]]) and torch.equal(other[1][d_pairs[:, 1]], pool[1][d_pairs[:, 0]]))
+    a = by / (ms * 1e-3) / 1e9
+    print(json.dumps({
+        "metric": "block-copy tokens/s", "value": n * bs * args.steps / wall, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": f"swap13b: {n} scattered blocks of {HK} heads x {bs} tokens x {D} (K and V) from a pool of {NB} "
+                               f"to a second pool", "copied_correctly": ok},
+        "roofline": {"kernel": "copy_blocks_kernel", "bound": "hbm", "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": a / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes": by, "kernel_ms": ms}}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -351,6 +391,9 @@ def main():
 
     if args.workload == "sched13b":
         run_scheduled(args, mpa)
+        return
+    if args.workload == "swap13b":
+        run_copy_blocks(args, mpa)
         return
     b = make_workload(args.workload)
     dw = DeviceWorkload(b, mpa)

@@ -127,6 +127,24 @@ int mpa_kv_append(mpa_ctx *ctx, const void *k_new, const void *v_new, const int6
                   int32_t num_tokens, void *k_cache, void *v_cache, void *stream);
 
 /*
+ * Whole-block copies between cache pools: for i in [0, num_pairs), block pairs[2i+1] of the
+ * destination pool becomes block pairs[2i] of the source pool, K and V, all K/V heads; bit-exact.
+ * For moving the blocks of a preempted request to another pool and back (the paper leaves KVC
+ * overflow to the engine's swapping, Sec. 5) and for migrating blocks inside one pool.
+ *
+ *   src_k, src_v : device (or host memory mapped to the device), [NBs, HK, bs, D], read only
+ *   dst_k, dst_v : same geometry, [NBd, HK, bs, D], written in place; may be the source pool itself
+ *                  as long as no destination block is also a source block of the call
+ *   pairs        : device, [num_pairs, 2] int64 {source block, destination block}; a pair with a
+ *                  negative id is skipped; ids must be inside their pools and destination ids
+ *                  pairwise distinct (not checked)
+ *   num_pairs == 0 is a no-op.
+ * Errors: INVALID_ARG, HIP.
+ */
+int mpa_copy_blocks(mpa_ctx *ctx, const void *src_k, const void *src_v, void *dst_k, void *dst_v,
+                    const int64_t *pairs, int32_t num_pairs, void *stream);
+
+/*
  * Attention of every query row of a mixed batch over its sequence's cached K/V.
  *
  * Sequence i owns rows chunk_starts[i] .. chunk_starts[i+1]-1 of q/out (q_len_i of them; the

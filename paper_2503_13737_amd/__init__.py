@@ -31,7 +31,7 @@ MPA_OPT_PLAN_CACHE = 6
 
 EXPORTS = [
     "mpa_create", "mpa_destroy", "mpa_set_option", "mpa_last_hip_error", "mpa_status_string",
-    "mpa_workspace_bytes_for_batch", "mpa_workspace_bytes", "mpa_kv_append",
+    "mpa_workspace_bytes_for_batch", "mpa_workspace_bytes", "mpa_kv_append", "mpa_copy_blocks",
     "mpa_mixed_paged_attention", "mpa_plan_describe", "mpa_profile_enable", "mpa_profile_read",
     "mpa_sched_create", "mpa_sched_destroy", "mpa_sched_add_request", "mpa_sched_next_batch",
     "mpa_sched_batch_arrays", "mpa_sched_complete", "mpa_sched_live_requests",
@@ -87,6 +87,8 @@ def load() -> ctypes.CDLL:
         lib.mpa_workspace_bytes.restype = sz
         lib.mpa_kv_append.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp]
         lib.mpa_kv_append.restype = ctypes.c_int
+        lib.mpa_copy_blocks.argtypes = [vp, vp, vp, vp, vp, vp, i32, vp]
+        lib.mpa_copy_blocks.restype = ctypes.c_int
         lib.mpa_mixed_paged_attention.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, i32, i32,
                                                   ctypes.c_float, vp, vp, sz, vp]
         lib.mpa_mixed_paged_attention.restype = ctypes.c_int
@@ -204,6 +206,13 @@ class Context:
                                   _ptr(k_cache), _ptr(v_cache), _stream_ptr(stream))
         if rc != MPA_OK:
             raise MpaError(rc, "mpa_kv_append")
+
+    def copy_blocks(self, src_k, src_v, dst_k, dst_v, pairs, stream=None, num_pairs=None):
+        n = int(pairs.shape[0]) if num_pairs is None else int(num_pairs)
+        rc = load().mpa_copy_blocks(self._h, _ptr(src_k), _ptr(src_v), _ptr(dst_k), _ptr(dst_v), _ptr(pairs), n,
+                                    _stream_ptr(stream))
+        if rc != MPA_OK:
+            raise MpaError(rc, "mpa_copy_blocks")
 
     def mixed_paged_attention(self, q, k_cache, v_cache, block_table, chunk_starts, context_lens, out,
                               workspace, scale: float = 0.0, stream=None, block_table_stride=None,

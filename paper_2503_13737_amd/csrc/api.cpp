@@ -209,6 +209,27 @@ int mpa_kv_append(mpa_ctx *ctx, const void *k_new, const void *v_new, const int6
     return MPA_OK;
 }
 
+int mpa_copy_blocks(mpa_ctx *ctx, const void *src_k, const void *src_v, void *dst_k, void *dst_v,
+                    const int64_t *pairs, int32_t num_pairs, void *stream)
+{
+    if (!ctx || num_pairs < 0) return MPA_ERR_INVALID_ARG;
+    if (num_pairs == 0) return MPA_OK;
+    if (!src_k || !src_v || !dst_k || !dst_v || !pairs) return MPA_ERR_INVALID_ARG;
+    if (!aligned(src_k, 16) || !aligned(src_v, 16) || !aligned(dst_k, 16) || !aligned(dst_v, 16) || !aligned(pairs, 8))
+        return MPA_ERR_INVALID_ARG;
+    const int64_t block_bytes = (int64_t)ctx->cfg.num_kv_heads * ctx->cfg.block_size * ctx->cfg.head_dim * 2;
+    // at most 65,535 pairs per launch (the grid's second dimension)
+    for (int32_t done = 0; done < num_pairs; done += 65535) {
+        const int32_t n = std::min<int32_t>(65535, num_pairs - done);
+        int e = launch_copy_blocks(src_k, src_v, dst_k, dst_v, pairs + 2 * (int64_t)done, n, block_bytes, stream);
+        if (e != 0) {
+            ctx->last_hip = e;
+            return MPA_ERR_HIP;
+        }
+    }
+    return MPA_OK;
+}
+
 int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache, const void *v_cache,
                               const int32_t *block_table, int32_t block_table_stride,
                               const int32_t *chunk_starts, const int32_t *context_lens,

@@ -135,6 +135,38 @@ kv_append_kernel(const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_ne
 }
 
 // ------------------------------------------------------------------------------------------
+// Block copy: work-group (x, i) moves 16 KiB of K and of V of pair i (1024 lanes x 16 bytes each,
+// four per thread, all loads issued before the stores).
+// ------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256)
+copy_blocks_kernel(const u32x4 *__restrict__ src_k, const u32x4 *__restrict__ src_v, u32x4 *__restrict__ dst_k,
+                   u32x4 *__restrict__ dst_v, const int64_t *__restrict__ pairs, int64_t vec_per_block)
+{
+    const int64_t src = pairs[2 * (int64_t)blockIdx.y], dst = pairs[2 * (int64_t)blockIdx.y + 1];
+    if (src < 0 || dst < 0) return;
+    const int64_t v0 = (int64_t)blockIdx.x * 1024 + threadIdx.x;
+    const u32x4 *sk = src_k + src * vec_per_block, *sv = src_v + src * vec_per_block;
+    u32x4 *dk = dst_k + dst * vec_per_block, *dv = dst_v + dst * vec_per_block;
+    u32x4 k[4], v[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t j = v0 + i * 256;
+        if (j < vec_per_block) {
+            k[i] = __builtin_nontemporal_load(sk + j);
+            v[i] = __builtin_nontemporal_load(sv + j);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int64_t j = v0 + i * 256;
+        if (j < vec_per_block) {
+            __builtin_nontemporal_store(k[i], dk + j);
+            __builtin_nontemporal_store(v[i], dv + j);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // Row-streaming body: one wavefront, one query row, one head, a contiguous range of KV blocks.
 //
 // A (block, head) tile of K is 16 tokens x D bf16, contiguous.  A 1 KiB load (16 B per lane)
@@ -978,6 +1010,18 @@ int launch_kv_append(const void *k_new, const void *v_new, const int64_t *slot_m
     hipLaunchKernelGGL(kv_append_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
                        (const uint4 *)k_new, (const uint4 *)v_new, slot_map, T, H, vec_per_row, block_size,
                        (uint4 *)k_cache, (uint4 *)v_cache);
+    return (int)hipGetLastError();
+}
+
+int launch_copy_blocks(const void *src_k, const void *src_v, void *dst_k, void *dst_v, const int64_t *pairs,
+                       int32_t n, int64_t block_bytes, void *stream)
+{
+    if (n == 0) return 0;
+    const int64_t vec_per_block = block_bytes / 16;
+    const int64_t gx = (vec_per_block + 1023) / 1024;
+    if (gx > 0x7FFFFFFF || n > 65535) return (int)hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(copy_blocks_kernel, dim3((unsigned)gx, (unsigned)n), dim3(256), 0, (hipStream_t)stream,
+                       (const u32x4 *)src_k, (const u32x4 *)src_v, (u32x4 *)dst_k, (u32x4 *)dst_v, pairs, vec_per_block);
     return (int)hipGetLastError();
 }
 

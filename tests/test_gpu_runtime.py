@@ -4,7 +4,7 @@ import numpy as np
 import pytest
 
 import workloads as W
-from harness import DeviceBatch, assert_close, oracle_run, to_host_u16
+from harness import DeviceBatch, assert_close, oracle_run, to_dev, to_host_u16
 
 pytestmark = pytest.mark.gpu
 
@@ -115,3 +115,61 @@ def test_workspace_too_small_is_rejected_before_launch(mpa):
                                   db.out, ws, scale=b.scale, workspace_bytes=need - 1)
     assert e.value.status == mpa.MPA_ERR_WORKSPACE
     assert ctx.last_hip_error() == 0
+
+
+@pytest.mark.parametrize("H,HK,D,bs", [(4, 4, 64, 16), (8, 2, 128, 32), (5, 5, 128, 128)])
+def test_copy_blocks_swaps_a_sequence_out_and_back_in(mpa, H, HK, D, bs):
+    """Blocks of two sequences go to a second pool and come back into other blocks: bit-exact
+    against the oracle's copies on both pools (untouched blocks included, a negative pair is
+    skipped), and attention through the re-mapped table is bit-identical to before."""
+    import oracle
+    import torch
+    ql, ctx = [70, 1, 1, 33], [200, 300, 17, 33 + 3 * bs]
+    b = W.make_batch("swap", 404, H, D, bs, sum((c + bs - 1) // bs for c in ctx) + 40, ql, ctx, Hkv=HK)
+    c = mpa.Context(H, D, block_size=bs, num_kv_heads=HK)
+    kc, vc = b.full_cache("ctx")
+    d_kc, d_vc = to_dev(kc), to_dev(vc)
+    ws = torch.empty(c.workspace_bytes_for_batch(b.chunk_starts, b.context_lens), dtype=torch.uint8, device="cuda")
+
+    def attend(table):
+        out = torch.full((b.T, H, D), 0x7FFF, dtype=torch.int16, device="cuda")
+        c.mixed_paged_attention(to_dev(b.q), d_kc, d_vc, to_dev(np.ascontiguousarray(table)), b.chunk_starts, b.context_lens,
+                                out, ws, scale=b.scale)
+        torch.cuda.synchronize()
+        return to_host_u16(out)
+
+    before = attend(b.block_table)
+    nbl = b.n_blocks()
+    held = np.concatenate([b.block_table[i, : nbl[i]] for i in (0, 3)]).astype(np.int64)
+    n = held.size
+    host_k = np.full((n + 3,) + kc.shape[1:], 0x4321, dtype=np.uint16)
+    host_v = host_k.copy()
+    d_hk, d_hv = to_dev(host_k), to_dev(host_v)
+    out_pairs = np.stack([held, W.permutation(n, 9)], axis=1)
+    out_pairs = np.concatenate([out_pairs, [[-1, n + 1], [held[0], -1]]]).astype(np.int64)   # skipped
+    c.copy_blocks(d_kc, d_vc, d_hk, d_hv, to_dev(out_pairs))
+    oracle.copy_blocks(kc, vc, host_k, host_v, out_pairs[:n])
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host_u16(d_hk), host_k) and np.array_equal(to_host_u16(d_hv), host_v)
+    # the old blocks are given up (poisoned here), the sequence returns into unreferenced blocks
+    free = np.setdiff1d(np.arange(b.NB), b.referenced_blocks())[:n].astype(np.int64)
+    kc[held], vc[held] = W.POISON, W.POISON
+    d_kc[torch.from_numpy(held).cuda()] = 0x7FFF
+    d_vc[torch.from_numpy(held).cuda()] = 0x7FFF
+    in_pairs = np.stack([out_pairs[:n, 1], free], axis=1)
+    c.copy_blocks(d_hk, d_hv, d_kc, d_vc, to_dev(in_pairs))
+    oracle.copy_blocks(host_k, host_v, kc, vc, in_pairs)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host_u16(d_kc), kc) and np.array_equal(to_host_u16(d_vc), vc)
+    table = b.block_table.copy()
+    remap = dict(zip(held.tolist(), free.tolist()))
+    for i in (0, 3):
+        table[i, : nbl[i]] = [remap[int(x)] for x in table[i, : nbl[i]]]
+    assert np.array_equal(attend(table), before)
+    # inside one pool (migration), and the empty call
+    moved = np.stack([free[:2], held[:2]], axis=1)
+    c.copy_blocks(d_kc, d_vc, d_kc, d_vc, to_dev(moved))
+    oracle.copy_blocks(kc.copy(), vc.copy(), kc, vc, moved)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host_u16(d_kc), kc)
+    assert mpa.load().mpa_copy_blocks(c._h, None, None, None, None, None, 0, None) == 0
