@@ -83,7 +83,10 @@ enum {
     MPA_OPT_PLAN_CACHE = 6       /* 1 (default) = a call whose chunk_starts / context_lens equal
                                     the previous call's reuses its work list (the layers of one
                                     model iteration all present the same batch); 0 = plan anew
-                                    on every call                                             */
+                                    on every call; 2 = as 1, and if workspace and stream are the
+                                    previous call's too, the work list already in that workspace
+                                    is used as it is and nothing is copied: the caller promises
+                                    not to write to the workspace between such calls          */
 };
 
 /* Create a context for one cache geometry.  Validates cfg; makes no HIP call.

@@ -34,6 +34,10 @@ struct mpa_ctx {
     std::vector<int32_t> plan_key;   // chunk_starts then context_lens of that batch
     bool plan_valid = false;         // cleared by mpa_set_option
     bool plan_cache = true;
+    bool keep_upload = false;            // MPA_OPT_PLAN_CACHE == 2
+    const void *uploaded_ws = nullptr;   // where, and on which stream, the cached plan's work list was last uploaded
+    const void *uploaded_stream = nullptr;
+    bool uploaded_valid = false;
     std::vector<hipEvent_t> prof_events;  // start/stop pairs
     int32_t prof_used = 0;                // pairs recorded in the current series
     std::mutex mu;
@@ -143,7 +147,11 @@ int mpa_set_option(mpa_ctx *ctx, int32_t option, int64_t value)
         if (value < 0) return MPA_ERR_INVALID_ARG;
         ctx->opt.pp_resident_wgs = value;
         return MPA_OK;
-    case MPA_OPT_PLAN_CACHE: ctx->plan_cache = value != 0; return MPA_OK;
+    case MPA_OPT_PLAN_CACHE:
+        if (value < 0 || value > 2) return MPA_ERR_INVALID_ARG;
+        ctx->plan_cache = value != 0;
+        ctx->keep_upload = value == 2;
+        return MPA_OK;
     case MPA_OPT_PP_TEAM_MIN_STEPS:
         if (value < 0) return MPA_ERR_INVALID_ARG;
         ctx->opt.pp_team_min_steps = value;
@@ -254,6 +262,7 @@ int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache, 
                       std::memcmp(ctx->plan_key.data() + num_seqs + 1, context_lens, (size_t)num_seqs * sizeof(int32_t)) == 0;
     if (!same) {
         ctx->plan_valid = false;
+        ctx->uploaded_valid = false;
         int rc = build_plan(ctx->opt, chunk_starts, context_lens, num_seqs, &plan);
         if (rc != MPA_OK) return rc;
         ctx->plan_key.assign(chunk_starts, chunk_starts + num_seqs + 1);
@@ -269,14 +278,22 @@ int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache, 
 
     auto fail = [&](hipError_t e) {
         ctx->last_hip = (int)e;
+        ctx->uploaded_valid = false;
         return MPA_ERR_HIP;
     };
 
+    // The work list of this very plan may still sit in this workspace from the previous call on
+    // this stream (the kernels only read it, and every progress word is back at its start value
+    // when a launch has finished): then nothing is copied.
+    const bool list_in_place = same && ctx->keep_upload && ctx->uploaded_valid && ctx->uploaded_ws == workspace &&
+                               ctx->uploaded_stream == stream;
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e;
+    if (!list_in_place) {
     // stage the work list in pinned memory and copy it into the workspace on the stream
     const size_t list_bytes = plan.off_acc;  // items, merge rows, teams, progress words; padded
     Staging &st = ctx->staging[ctx->next_slot];
     ctx->next_slot = (ctx->next_slot + 1) % kStagingSlots;
-    hipError_t e;
     if (st.in_flight) {
         if ((e = hipEventSynchronize(st.done)) != hipSuccess) return fail(e);
         st.in_flight = false;
@@ -296,11 +313,14 @@ int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache, 
     std::memcpy(h + plan.off_merge, plan.merge.data(), plan.merge.size() * sizeof(MergeRow));
     std::memcpy(h + plan.off_teams, plan.teams.data(), plan.teams.size() * sizeof(TeamRef));
     std::memset(h + plan.off_progress, 0xFF, (size_t)plan.progress_words * sizeof(uint32_t));  // kNotRunning
-    hipStream_t s = (hipStream_t)stream;
     if ((e = hipMemcpyAsync(workspace, h, list_bytes, hipMemcpyHostToDevice, s)) != hipSuccess)
         return fail(e);
     if ((e = hipEventRecord(st.done, s)) != hipSuccess) return fail(e);
     st.in_flight = true;
+    ctx->uploaded_ws = workspace;
+    ctx->uploaded_stream = stream;
+    ctx->uploaded_valid = true;
+    }
 
     char *ws = static_cast<char *>(workspace);
     AttnParams p;

@@ -82,6 +82,34 @@ def test_reused_work_list_same_batch_then_same_sizes_other_lengths(mpa):
         assert_close(to_host_u16(db.out), refs[id(b)], f"{b.name} call {step}")
 
 
+def test_work_list_left_in_the_workspace_is_reused(mpa):
+    """Plan cache level 2: same batch, same workspace, same stream -> no upload; the inputs change
+    from call to call (as from layer to layer) and every result is checked.  Another workspace,
+    another batch and a return to the first batch each upload again.  Includes a prompt-heavy
+    batch with few resident work-groups, whose progress words must be back at their start value."""
+    import torch
+    ql, ctxl = [600, 300, 1, 1, 1], [1500, 300, 700, 64, 2000]
+    batches = [W.make_batch(f"keep-{seed}", seed, 4, 128, 16, sum((c + 15) // 16 for c in ctxl) + 3, ql, ctxl) for seed in (51, 52, 53)]
+    other = W.make_batch("keep-other", 54, 4, 128, 16, 200, [100, 1], [400, 900])
+    ctx = mpa.Context(4, 128)
+    ctx.set_option(mpa.MPA_OPT_PLAN_CACHE, 2)
+    ctx.set_option(mpa.MPA_OPT_PP_RESIDENT_WGS, 3)
+    ctx.set_option(mpa.MPA_OPT_PP_TEAM_MIN_STEPS, 1)
+    need = max(ctx.workspace_bytes_for_batch(b.chunk_starts, b.context_lens) for b in batches + [other])
+    ws1 = torch.empty(need, dtype=torch.uint8, device="cuda")
+    ws2 = torch.empty(need, dtype=torch.uint8, device="cuda")
+    ws1.fill_(0xFF)
+    ws2.fill_(0xFF)
+    for step, (b, ws) in enumerate([(batches[0], ws1), (batches[1], ws1), (batches[2], ws1), (batches[0], ws2),
+                                    (batches[1], ws2), (other, ws2), (batches[2], ws2), (batches[0], ws2)]):
+        db = DeviceBatch(b, "prior")
+        run_on(ctx, db, b, ws)
+        torch.cuda.synchronize()
+        assert_close(to_host_u16(db.out), oracle_run(b)[0], f"{b.name} call {step}")
+    with pytest.raises(mpa.MpaError):
+        ctx.set_option(mpa.MPA_OPT_PLAN_CACHE, 3)
+
+
 def test_run_to_run_bit_identical_on_split_heavy_batch(mpa):
     import torch
     b = W.random_ragged(9100, H=5, D=128, n_pp=2, n_tg=4, max_q=400, max_prior=3000, max_ctx=4000)
