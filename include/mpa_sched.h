@@ -5,7 +5,9 @@
  * After every iteration it forms the batch of the next one (paper Sec. 4):
  *   - the token budget S_b = S_pf * SLO_min / T_pf (Sec. 4.2, token budget determination);
  *   - requests ordered by remaining time T_r = SLO - T_w - N_ck * T_max, urgent when
- *     T_r <= T_max (Sec. 4.3);
+ *     T_r <= T_max (Sec. 4.3); requests of offline applications carry a JCT SLO instead, spread
+ *     over their iterations as an allowed waiting time whose unused or overdrawn part moves on
+ *     to the next iteration (Sec. 4.3, SLOs of offline applications);
  *   - prompts cut dynamically where the budget or the KV cache ends, one long prompt at a time
  *     (Sec. 4.2, dynamic chunking; limiting running long-prompt requests);
  *   - KV-cache demand per request in whole blocks, later chunks first filling the free slots of
@@ -44,6 +46,8 @@ typedef struct {
     double pivot_time;          /* T_pf: batch execution time at S_pf, seconds                  */
     double max_batch_time;      /* T_max: longest batch execution time, seconds (Sec. 4.3)      */
     double gamma;               /* window of remaining times considered together (Sec. 4.4)     */
+    double preempt_max_time;    /* P_max: longest preemption, seconds; offline requests only    */
+    double preempt_probability; /* P: chance of a preemption after a generated token (Sec. 4.3) */
 } mpa_sched_config;
 
 typedef struct {
@@ -68,6 +72,14 @@ int mpa_sched_destroy(mpa_sched *s);
  * max_new_tokens - 1 tokens do not fit the pool). */
 int mpa_sched_add_request(mpa_sched *s, int64_t id, int32_t prompt_len, int32_t max_new_tokens,
                           double slo_first, double slo_token, double now);
+
+/* A request of an offline application: slo_jct seconds for the whole job, predicted_new_tokens =
+ * S_g, the caller's estimate of how many tokens it will generate (it still stops after
+ * max_new_tokens).  Its execution time is estimated as N_ck * T_max + S_g * (T_max + P_max * P) with
+ * N_ck = ceil(prompt_len / L_c); the rest of the SLO, divided by N_ck + S_g, is the waiting time it is
+ * allowed per iteration.  Errors: as mpa_sched_add_request, and predicted_new_tokens < 1. */
+int mpa_sched_add_offline_request(mpa_sched *s, int64_t id, int32_t prompt_len, int32_t max_new_tokens,
+                                  int32_t predicted_new_tokens, double slo_jct, double now);
 
 /* Forms the batch of the next iteration at time `now` and allocates its blocks.  An empty batch
  * (num_seqs == 0) is a valid outcome. */

@@ -9,6 +9,10 @@ What it follows
   * remaining time          T_r = SLO - T_w - T_e,  T_e = N_ck * T_max,
                             N_ck = ceil(S_r / L_c) for a prompt, 1 for a generation task (Sec. 4.3)
   * queue order             ascending T_r; urgent = T_r <= T_max                (Sec. 4.3)
+  * offline requests        a JCT SLO is spread over the request's iterations:
+                            T_e = N_ck * T_max + S_g * (T_max + P_max * P),
+                            allowance per iteration = (SLO_JCT - T_e) / (N_ck + S_g); waiting longer
+                            or shorter than the allowance is carried into the next one (Sec. 4.3)
   * dynamic chunking        tokens are taken from a prompt until the budget or the KVC is used up;
                             the prompt is cut wherever that happens               (Sec. 4.2)
   * one long prompt at a time: a new long prompt does not start while another is being
@@ -53,6 +57,9 @@ class Request:
     started: bool = False
     blocks: list = field(default_factory=list)
     t_r: float = 0.0
+    offline: bool = False  # has a JCT SLO instead of per-token SLOs
+    allowance: float = 0.0 # waiting time allowed per iteration, fixed when the request arrives
+    carry: float = 0.0     # unused (+) or overdrawn (-) waiting time of the iterations so far
 
     @property
     def is_prompt(self):
@@ -72,7 +79,8 @@ class Entry:
 
 class Scheduler:
     def __init__(self, block_size, num_blocks, pivot_forward_size, pivot_time, max_batch_time, gamma,
-                 max_batch_tokens, block_order=None):
+                 max_batch_tokens, block_order=None, preempt_max_time=0.0, preempt_probability=0.0):
+        self.p_max, self.p_prob = float(preempt_max_time), float(preempt_probability)
         self.b, self.nb = int(block_size), int(num_blocks)
         self.s_pf, self.t_pf, self.t_max, self.gamma = int(pivot_forward_size), float(pivot_time), float(max_batch_time), float(gamma)
         self.max_tokens = int(max_batch_tokens)
@@ -97,16 +105,37 @@ class Scheduler:
             raise ValueError("bad request")
         self.reqs[rid] = Request(rid, int(prompt_len), int(max_new), float(slo_first), float(slo_token), float(now))
 
+    def add_offline_request(self, rid, prompt_len, max_new, predicted_new, slo_jct, now):
+        """Sec. 4.3, SLOs of offline applications: predicted_new is S_g, the estimated number of
+        tokens the request will generate."""
+        self.add_request(rid, prompt_len, max_new, 0.0, 0.0, now)
+        r = self.reqs[rid]
+        n_ck = math.ceil(r.prompt_len / self.mean_chunk())
+        per_token = self.t_max + self.p_max * self.p_prob
+        t_e = n_ck * self.t_max + predicted_new * per_token
+        r.offline, r.allowance = True, (slo_jct - t_e) / (n_ck + predicted_new)
+
     def mean_chunk(self) -> float:
         return float(self.s_pf) if self.chunks == 0 else self.chunk_tokens / self.chunks
 
     def remaining_time(self, r: Request, now: float) -> float:
+        if r.offline:
+            # what is left of this iteration's allowance (a returned task has not waited yet)
+            waited = 0.0 if r.state == RETURNED else now - r.t_enter
+            return (r.allowance + r.carry) - waited
         if r.state == WAITING:
             n_ck = math.ceil((r.prompt_len - r.processed) / self.mean_chunk())
             return (r.slo_first - (now - r.t_enter)) - n_ck * self.t_max
         if r.state == RETURNED:
             return (r.slo_token - 0.0) - 1 * self.t_max
         return (r.slo_token - (now - r.t_enter)) - 1 * self.t_max
+
+    def slo_of(self, r: Request) -> float:
+        """The iteration-level SLO that enters Eq. 6: an offline request's is its allowance plus
+        the execution of one batch."""
+        if r.offline:
+            return r.allowance + self.t_max
+        return r.slo_first if r.is_prompt else r.slo_token
 
     def is_long(self, r: Request) -> bool:
         return r.prompt_len > self.s_pf
@@ -122,7 +151,7 @@ class Scheduler:
             r.t_r = self.remaining_time(r, now)
         order = sorted(live, key=lambda r: (r.t_r, r.id))
         head = order[0]
-        slo_min = head.slo_first if head.is_prompt else head.slo_token
+        slo_min = self.slo_of(head)
         s_b = int(math.floor(self.s_pf * slo_min / self.t_pf))
         s_b = max(1, min(s_b, self.max_tokens))
         self.token_budget = s_b
@@ -165,6 +194,11 @@ class Scheduler:
             self.select_requests(a_c, a_m, order)
         # blocks are handed out in batch order; chunk statistics feed L_c
         for e in batch:
+            r = e.req
+            if r.offline:
+                # the iteration starts now: what it under- or over-used of its allowance moves on
+                waited = 0.0 if r.state == RETURNED else now - r.t_enter
+                r.carry = (r.allowance + r.carry) - waited
             for _ in range(e.new_blocks):
                 e.req.blocks.append(self.free.pop())
             if e.req.is_prompt:
@@ -257,6 +291,8 @@ class Scheduler:
                 r.processed += e.tokens
                 if r.processed == r.prompt_len:
                     r.generated, r.state = 1, RETURNED
+                elif r.offline:
+                    r.t_enter = now      # the next chunk's iteration waits from here
             else:
                 r.generated += 1
                 r.state = RETURNED

@@ -33,7 +33,7 @@ EXPORTS = [
     "mpa_create", "mpa_destroy", "mpa_set_option", "mpa_last_hip_error", "mpa_status_string",
     "mpa_workspace_bytes_for_batch", "mpa_workspace_bytes", "mpa_kv_append", "mpa_copy_blocks",
     "mpa_mixed_paged_attention", "mpa_plan_describe", "mpa_profile_enable", "mpa_profile_read",
-    "mpa_sched_create", "mpa_sched_destroy", "mpa_sched_add_request", "mpa_sched_next_batch",
+    "mpa_sched_create", "mpa_sched_destroy", "mpa_sched_add_request", "mpa_sched_add_offline_request", "mpa_sched_next_batch",
     "mpa_sched_batch_arrays", "mpa_sched_complete", "mpa_sched_live_requests",
 ]
 
@@ -46,7 +46,8 @@ class MpaConfig(ctypes.Structure):
 class SchedConfig(ctypes.Structure):
     _fields_ = [("block_size", ctypes.c_int32), ("num_blocks", ctypes.c_int32),
                 ("pivot_forward_size", ctypes.c_int32), ("max_batch_tokens", ctypes.c_int32),
-                ("pivot_time", ctypes.c_double), ("max_batch_time", ctypes.c_double), ("gamma", ctypes.c_double)]
+                ("pivot_time", ctypes.c_double), ("max_batch_time", ctypes.c_double), ("gamma", ctypes.c_double),
+                ("preempt_max_time", ctypes.c_double), ("preempt_probability", ctypes.c_double)]
 
 
 class SchedBatch(ctypes.Structure):
@@ -105,6 +106,8 @@ def load() -> ctypes.CDLL:
         lib.mpa_sched_destroy.restype = ctypes.c_int
         lib.mpa_sched_add_request.argtypes = [vp, i64, i32, i32, f64, f64, f64]
         lib.mpa_sched_add_request.restype = ctypes.c_int
+        lib.mpa_sched_add_offline_request.argtypes = [vp, i64, i32, i32, i32, f64, f64]
+        lib.mpa_sched_add_offline_request.restype = ctypes.c_int
         lib.mpa_sched_next_batch.argtypes = [vp, f64, ctypes.POINTER(SchedBatch)]
         lib.mpa_sched_next_batch.restype = ctypes.c_int
         lib.mpa_sched_batch_arrays.argtypes = [vp, vp, vp, vp, vp, vp, i32]
@@ -258,10 +261,12 @@ class Scheduler:
     arrays mpa_kv_append / mpa_mixed_paged_attention take.  Host only."""
 
     def __init__(self, block_size: int, num_blocks: int, pivot_forward_size: int, pivot_time: float,
-                 max_batch_time: float, gamma: float, max_batch_tokens: int, block_order=None):
+                 max_batch_time: float, gamma: float, max_batch_tokens: int, block_order=None,
+                 preempt_max_time: float = 0.0, preempt_probability: float = 0.0):
         self._lib = load()
         self._h = ctypes.c_void_p()
-        cfg = SchedConfig(block_size, num_blocks, pivot_forward_size, max_batch_tokens, pivot_time, max_batch_time, gamma)
+        cfg = SchedConfig(block_size, num_blocks, pivot_forward_size, max_batch_tokens, pivot_time, max_batch_time, gamma,
+                          preempt_max_time, preempt_probability)
         order = None if block_order is None else _host_i32(block_order)
         if order is not None and order.size != num_blocks:
             raise MpaError(MPA_ERR_INVALID_ARG, "mpa_sched_create")
@@ -285,6 +290,13 @@ class Scheduler:
         st = self._lib.mpa_sched_add_request(self._h, rid, prompt_len, max_new_tokens, slo_first, slo_token, now)
         if st != MPA_OK:
             raise MpaError(st, "mpa_sched_add_request")
+
+    def add_offline_request(self, rid: int, prompt_len: int, max_new_tokens: int, predicted_new_tokens: int,
+                            slo_jct: float, now: float):
+        st = self._lib.mpa_sched_add_offline_request(self._h, rid, prompt_len, max_new_tokens, predicted_new_tokens,
+                                                     slo_jct, now)
+        if st != MPA_OK:
+            raise MpaError(st, "mpa_sched_add_offline_request")
 
     def next_batch(self, now: float) -> SchedBatch:
         st = self._lib.mpa_sched_next_batch(self._h, now, ctypes.byref(self.info))

@@ -32,12 +32,14 @@ struct Req {
     bool in_batch = false;
     bool evicted_now = false; // preempted by the decision being formed
     bool taken = false;       // scratch of the selection loop
+    bool offline = false;     // JCT SLO: `allowance` seconds of waiting per iteration, `carry` moved on
+    double allowance = 0.0, carry = 0.0;
     std::vector<int32_t> blocks;
 
     bool is_prompt() const { return state == kPrompt; }
     // tokens whose K/V are cached; a generation task has not fed its newest token yet
     int64_t cached() const { return is_prompt() ? processed : prompt_len + generated - 1; }
-    double slo() const { return is_prompt() ? slo_first : slo_token; }
+    double waited(double now) const { return state == kReturned ? 0.0 : now - t_enter; }
 };
 
 struct Entry {
@@ -78,9 +80,19 @@ struct mpa_sched {
     {
         return chunks == 0 ? (double)cfg.pivot_forward_size : (double)chunk_tokens / (double)chunks;
     }
-    // Sec. 4.3: T_r = SLO - T_w - N_ck * T_max
+    // the iteration-level SLO that enters Eq. 6
+    double slo(const Req &r) const
+    {
+        if (r.offline) return r.allowance + cfg.max_batch_time;
+        return r.is_prompt() ? r.slo_first : r.slo_token;
+    }
+    // Sec. 4.3: T_r = SLO - T_w - N_ck * T_max; for a JCT SLO what is left of the iteration's allowance
     double remaining_time(const Req &r, double now) const
     {
+        if (r.offline) {
+            const double allowed = r.allowance + r.carry;
+            return allowed - r.waited(now);
+        }
         double n_ck = 1.0, waited = 0.0;
         if (r.is_prompt()) {
             n_ck = std::ceil((double)(r.prompt_len - r.processed) / mean_chunk());
@@ -88,7 +100,7 @@ struct mpa_sched {
         } else if (r.state == kSetAside) {
             waited = now - r.t_enter;
         }
-        const double slack = r.slo() - waited;
+        const double slack = (r.is_prompt() ? r.slo_first : r.slo_token) - waited;
         const double exec = n_ck * cfg.max_batch_time;
         return slack - exec;
     }
@@ -174,7 +186,8 @@ int mpa_sched_create(mpa_sched **out, const mpa_sched_config *cfg, const int32_t
     if (!out || !cfg) return MPA_ERR_INVALID_ARG;
     *out = nullptr;
     if (cfg->block_size < 1 || cfg->num_blocks < 1 || cfg->pivot_forward_size < 1 || cfg->max_batch_tokens < 1 ||
-        !(cfg->pivot_time > 0.0) || !(cfg->max_batch_time > 0.0) || !(cfg->gamma >= 0.0))
+        !(cfg->pivot_time > 0.0) || !(cfg->max_batch_time > 0.0) || !(cfg->gamma >= 0.0) ||
+        !(cfg->preempt_max_time >= 0.0) || !(cfg->preempt_probability >= 0.0))
         return MPA_ERR_INVALID_ARG;
     std::unique_ptr<mpa_sched> s(new (std::nothrow) mpa_sched());
     if (!s) return MPA_ERR_INVALID_ARG;
@@ -216,6 +229,24 @@ int mpa_sched_add_request(mpa_sched *s, int64_t id, int32_t prompt_len, int32_t 
     return MPA_OK;
 }
 
+int mpa_sched_add_offline_request(mpa_sched *s, int64_t id, int32_t prompt_len, int32_t max_new_tokens,
+                                  int32_t predicted_new_tokens, double slo_jct, double now)
+{
+    if (!s || predicted_new_tokens < 1) return MPA_ERR_INVALID_ARG;
+    const int rc = mpa_sched_add_request(s, id, prompt_len, max_new_tokens, 0.0, 0.0, now);
+    if (rc != MPA_OK) return rc;
+    Req &r = *s->live[id];
+    const double n_ck = std::ceil((double)r.prompt_len / s->mean_chunk());
+    const double preempt = s->cfg.preempt_max_time * s->cfg.preempt_probability;
+    const double per_token = s->cfg.max_batch_time + preempt;
+    const double prompt_time = n_ck * s->cfg.max_batch_time;
+    const double gen_time = (double)predicted_new_tokens * per_token;
+    const double t_e = prompt_time + gen_time;
+    r.offline = true;
+    r.allowance = (slo_jct - t_e) / (n_ck + (double)predicted_new_tokens);
+    return MPA_OK;
+}
+
 // Algorithm 1.
 int mpa_sched_next_batch(mpa_sched *s, double now, mpa_sched_batch *info)
 {
@@ -242,7 +273,7 @@ int mpa_sched_next_batch(mpa_sched *s, double now, mpa_sched_batch *info)
     });
     // Eq. 6 with the SLO of the queue head
     {
-        const double scaled = (double)s->cfg.pivot_forward_size * order[0]->slo();
+        const double scaled = (double)s->cfg.pivot_forward_size * s->slo(*order[0]);
         const double budget = std::floor(scaled / s->cfg.pivot_time);
         int64_t sb = budget >= (double)s->cfg.max_batch_tokens ? s->cfg.max_batch_tokens : (int64_t)budget;
         s->token_budget = (int32_t)std::max<int64_t>(1, std::min<int64_t>(sb, s->cfg.max_batch_tokens));
@@ -293,6 +324,10 @@ int mpa_sched_next_batch(mpa_sched *s, double now, mpa_sched_batch *info)
 
     // allocation, in batch order
     for (Entry &e : s->batch) {
+        if (e.r->offline) {   // the iteration starts: unused or overdrawn waiting time moves on
+            const double allowed = e.r->allowance + e.r->carry;
+            e.r->carry = allowed - e.r->waited(now);
+        }
         for (int64_t k = 0; k < e.new_blocks; ++k) {
             e.r->blocks.push_back(s->free_blocks.back());
             s->free_blocks.pop_back();
@@ -346,7 +381,6 @@ int mpa_sched_batch_arrays(const mpa_sched *s, int64_t *request_ids, int32_t *ch
 
 int mpa_sched_complete(mpa_sched *s, double now, int64_t *finished_ids, int32_t cap, int32_t *num_finished)
 {
-    (void)now;
     if (!s) return MPA_ERR_INVALID_ARG;
     int32_t n = 0;
     for (const Entry &e : s->batch) {
@@ -356,6 +390,8 @@ int mpa_sched_complete(mpa_sched *s, double now, int64_t *finished_ids, int32_t 
             if (r.processed == r.prompt_len) {   // the last chunk yields the prompt's token
                 r.generated = 1;
                 r.state = kReturned;
+            } else if (r.offline) {
+                r.t_enter = now;                 // the next chunk's iteration waits from here
             }
         } else {
             r.generated += 1;

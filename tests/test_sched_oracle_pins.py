@@ -203,3 +203,34 @@ def test_schedule_invariants_over_a_trace(seed, nb):
     for rid in done:
         # a finished request was fed its prompt and all generated tokens but the last
         assert seen[rid][0] >= int(trace["prompt_len"][rid])
+
+
+def test_offline_allowance_and_its_propagation():
+    """Sec. 4.3, SLOs of offline applications, on hand-computed numbers: L_c = 768, a 2000-token
+    prompt (3 chunks), 100 predicted tokens, T_max 0.1 s, P_max 2 s, P 0.05:
+    T_e = 3 * 0.1 + 100 * (0.1 + 0.1) = 20.3 s; with a JCT SLO of 61.5 s each of the 103 iterations
+    may wait (61.5 - 20.3) / 103 = 0.4 s.  Waiting 0.25 s leaves 0.15 s for the next iteration
+    (allowance + d); waiting 0.7 s of the 0.55 s then allowed takes 0.15 s from the one after
+    (allowance - d)."""
+    s = SO.Scheduler(16, 4096, 768, 0.1, 0.1, 0.75, 768, None, preempt_max_time=2.0, preempt_probability=0.05)
+    s.add_offline_request(1, 2000, 50, 100, 61.5, 10.0)
+    r = s.reqs[1]
+    assert r.allowance == pytest.approx(0.4, abs=1e-12)
+    assert s.remaining_time(r, 10.1) == pytest.approx(0.3, abs=1e-12)
+    batch = s.next_batch(10.25)                      # scheduled after waiting 0.25 s
+    assert [e.req.id for e in batch] == [1]
+    assert r.carry == pytest.approx(0.15, abs=1e-12)
+    s.complete(10.35)                                # its next chunk waits from here
+    assert s.remaining_time(r, 10.35) == pytest.approx(0.55, abs=1e-12)
+    s.next_batch(10.35 + 0.7)
+    assert r.carry == pytest.approx(-0.15, abs=1e-12)
+    s.complete(11.15)
+    assert s.remaining_time(r, 11.15) == pytest.approx(0.25, abs=1e-12)
+    # Eq. 6 sees the allowance plus one batch execution as this request's iteration SLO
+    assert s.slo_of(r) == pytest.approx(0.5, abs=1e-12)
+    # once it generates, a task that returns and runs at once has waited 0 s: the whole allowance moves on
+    s.next_batch(11.15)
+    s.complete(11.25)
+    assert r.state == SO.RETURNED and r.carry == pytest.approx(0.25, abs=1e-12)
+    s.next_batch(11.25)
+    assert r.carry == pytest.approx(0.65, abs=1e-12)

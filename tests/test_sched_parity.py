@@ -10,17 +10,24 @@ import workloads as W
 from oracle import sched_oracle as SO
 
 
-def run_both(trace, n_iter, b, nb, s_pf, t_pf, t_max, gamma, max_tokens, order, iter_time):
-    o = SO.Scheduler(b, nb, s_pf, t_pf, t_max, gamma, max_tokens, order)
-    c = mpa.Scheduler(b, nb, s_pf, t_pf, t_max, gamma, max_tokens, order)
+def run_both(trace, n_iter, b, nb, s_pf, t_pf, t_max, gamma, max_tokens, order, iter_time, offline_every=0):
+    """offline_every = k > 0: every k-th request is an offline one with a JCT SLO of 40 times its
+    first-token SLO and a predicted length of half its real one."""
+    o = SO.Scheduler(b, nb, s_pf, t_pf, t_max, gamma, max_tokens, order, 1.5, 0.1)
+    c = mpa.Scheduler(b, nb, s_pf, t_pf, t_max, gamma, max_tokens, order, 1.5, 0.1)
     now, nxt, n = 0.0, 0, len(trace["arrival"])
     stats = {"batches": 0, "tokens": 0, "preempted": 0, "finished": 0, "chunks": 0}
     for it in range(n_iter):
         while nxt < n and trace["arrival"][nxt] <= now:
             args = (nxt, int(trace["prompt_len"][nxt]), int(trace["max_new"][nxt]), float(trace["slo_first"][nxt]),
                     float(trace["slo_token"][nxt]), float(trace["arrival"][nxt]))
-            o.add_request(*args)
-            c.add_request(*args)
+            if offline_every and nxt % offline_every == 0:
+                off = (nxt, args[1], args[2], max(1, args[2] // 2), 40.0 * args[3], args[5])
+                o.add_offline_request(*off)
+                c.add_offline_request(*off)
+            else:
+                o.add_request(*args)
+                c.add_request(*args)
             nxt += 1
         ob = o.next_batch(now)
         info = c.next_batch(now)
@@ -56,6 +63,14 @@ def test_same_batches_as_the_oracle_over_a_trace(seed, b, nb, rate):
         assert st["preempted"] > 0     # the small pools exercise preemption and recomputation
 
 
+@pytest.mark.parametrize("seed,nb,every", [(11, 4096, 2), (12, 700, 3), (13, 1500, 1)])
+def test_same_batches_with_offline_requests_in_the_mix(seed, nb, every):
+    trace = W.poisson_trace(140, seed, rate=8.0, max_prompt=3000, max_new=64)
+    st = run_both(trace, 1200, 16, nb, 768, 0.05, 0.05, 0.75, 2048, W.permutation(nb, seed),
+                  lambda sf: 0.05 * max(sf, 64) / 768, offline_every=every)
+    assert st["batches"] > 300 and st["chunks"] > 50
+
+
 def test_same_batches_with_tight_slos_and_a_small_budget():
     """Budget below the pivot (SLO_min < T_pf), many urgent requests, gamma 0."""
     trace = W.poisson_trace(120, 9, rate=20.0, max_prompt=1500, max_new=32, base_token_slo=0.03, base_first_slo=0.2)
@@ -76,6 +91,8 @@ def test_scheduler_argument_checks():
         s.add_request(2, 128, 2, 1.0, 1.0, 0.0)         # 129 tokens do not fit 8 blocks of 16
     with pytest.raises(mpa.MpaError):
         s.add_request(3, 0, 2, 1.0, 1.0, 0.0)
+    with pytest.raises(mpa.MpaError):
+        s.add_offline_request(4, 10, 2, 0, 100.0, 0.0)   # no predicted length
     info = s.next_batch(0.0)
     assert (info.num_seqs, info.num_tokens, info.num_prompt_chunks) == (1, 100, 1)
     ids, cs, ctx, slots, tab = s.batch_arrays(stride=9)
