@@ -6,10 +6,14 @@ new K/V followed by mixed_paged_attention (work-list planning and upload include
 tensors already resident in HBM.  Default workload: the OPT-13B-shaped mixed batch (one
 512-token prompt chunk + 48 generation rows, 40 heads x 128, block size 16).
 
-Prints ONE JSON line (see README/DESIGN for the fields).  `roofline` describes the attention
+Prints ONE JSON line: metric / value / unit (tokens/s of the whole step), ms_per_step, the
+workload in `config`, and the objects below.  `roofline` describes the attention
 kernel of the mixed step (HBM bound: the generation rows dominate); `roofline_tg` and
 `roofline_pp` are the same kernel timed on the generation-only and prompt-only parts of the
-batch, against the HBM and bf16 matrix-core peaks respectively.
+batch, against the HBM and bf16 matrix-core peaks respectively; `cpu_baseline` is the fp64
+oracle timed on the host cores on a sample of the same batch.  Other workloads (--workload): cfg1,
+cfg2, cfg4, cfg5[:iteration], gqa, <cfg>@bs32|64|128, <cfg>@fp16, sched13b (batches formed by the
+scheduler from a Poisson trace), swap13b (block copies).
 """
 from __future__ import annotations
 
