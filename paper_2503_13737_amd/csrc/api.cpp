@@ -2,7 +2,9 @@
 #include <hip/hip_runtime.h>
 
 #include <cmath>
+#include <chrono>
 #include <cstring>
+#include <thread>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -15,11 +17,33 @@ using namespace mpa;
 namespace {
 constexpr int kStagingSlots = 8;
 
+constexpr size_t kStagingHeader = 256;   // the completion word sits in front of the data
+
+// One slot of the ring through which work lists travel: pinned host memory that the upload kernel
+// reads, and a word in front of it to which that kernel writes the slot's ticket when it is done
+// reading.  The slot is refilled only after its ticket has shown up.
 struct Staging {
-    void *host = nullptr;  // pinned
-    size_t bytes = 0;
-    hipEvent_t done = nullptr;
+    void *host = nullptr;  // pinned: [completion word, padding | data]
+    size_t bytes = 0;      // of data
+    uint64_t ticket = 0;   // of the upload in flight from this slot
     bool in_flight = false;
+
+    volatile uint64_t *flag() const { return static_cast<volatile uint64_t *>(host); }
+    char *data() const { return static_cast<char *>(host) + kStagingHeader; }
+    // The upload kernels of a slot finish long before the ring comes round; if one does not show
+    // up for seconds (a failed launch), the device is drained rather than the host left spinning.
+    void wait() {
+        if (!in_flight || !host) return;
+        const auto t0 = std::chrono::steady_clock::now();
+        while (*flag() < ticket) {
+            std::this_thread::yield();
+            if (std::chrono::steady_clock::now() - t0 > std::chrono::seconds(5)) {
+                (void)hipDeviceSynchronize();
+                break;
+            }
+        }
+        in_flight = false;
+    }
 };
 }  // namespace
 
@@ -29,6 +53,7 @@ struct mpa_ctx {
     int last_hip = 0;
     Staging staging[kStagingSlots];
     int next_slot = 0;
+    uint64_t next_ticket = 1;
     Plan plan;  // the plan of the last batch; reused as it is when the next batch is the same
                 // (all layers of one model iteration present the same batch)
     std::vector<int32_t> plan_key;   // chunk_starts then context_lens of that batch
@@ -86,10 +111,7 @@ int mpa_destroy(mpa_ctx *ctx)
 {
     if (!ctx) return MPA_OK;
     for (auto &s : ctx->staging) {
-        if (s.done) {
-            if (s.in_flight) (void)hipEventSynchronize(s.done);
-            (void)hipEventDestroy(s.done);
-        }
+        s.wait();
         if (s.host) (void)hipHostFree(s.host);
     }
     for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
@@ -294,28 +316,25 @@ int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache, 
     const size_t list_bytes = plan.off_acc;  // items, merge rows, teams, progress words; padded
     Staging &st = ctx->staging[ctx->next_slot];
     ctx->next_slot = (ctx->next_slot + 1) % kStagingSlots;
-    if (st.in_flight) {
-        if ((e = hipEventSynchronize(st.done)) != hipSuccess) return fail(e);
-        st.in_flight = false;
-    }
+    st.wait();
     if (st.bytes < list_bytes) {
         if (st.host) (void)hipHostFree(st.host);
         st.host = nullptr;
         st.bytes = 0;
         size_t want = list_bytes * 2;
-        if ((e = hipHostMalloc(&st.host, want, hipHostMallocDefault)) != hipSuccess) return fail(e);
+        if ((e = hipHostMalloc(&st.host, kStagingHeader + want, hipHostMallocCoherent)) != hipSuccess) return fail(e);
         st.bytes = want;
+        *st.flag() = 0;
     }
-    if (!st.done && (e = hipEventCreateWithFlags(&st.done, hipEventDisableTiming)) != hipSuccess)
-        return fail(e);
-    char *h = static_cast<char *>(st.host);
+    char *h = st.data();
     std::memcpy(h + plan.off_items, plan.items.data(), plan.items.size() * sizeof(WorkItem));
     std::memcpy(h + plan.off_merge, plan.merge.data(), plan.merge.size() * sizeof(MergeRow));
     std::memcpy(h + plan.off_teams, plan.teams.data(), plan.teams.size() * sizeof(TeamRef));
     std::memset(h + plan.off_progress, 0xFF, (size_t)plan.progress_words * sizeof(uint32_t));  // kNotRunning
-    if ((e = hipMemcpyAsync(workspace, h, list_bytes, hipMemcpyHostToDevice, s)) != hipSuccess)
-        return fail(e);
-    if ((e = hipEventRecord(st.done, s)) != hipSuccess) return fail(e);
+    if (list_bytes % 16 != 0) return MPA_ERR_WORKSPACE;   // the plan pads its sections
+    st.ticket = ctx->next_ticket++;
+    if (int ue = launch_upload(h, workspace, list_bytes, const_cast<uint64_t *>(st.flag()), st.ticket, stream))
+        return fail((hipError_t)ue);
     st.in_flight = true;
     ctx->uploaded_ws = workspace;
     ctx->uploaded_stream = stream;

@@ -135,6 +135,31 @@ kv_append_kernel(const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_ne
 }
 
 // ------------------------------------------------------------------------------------------
+// Work-list upload: the few KiB the host planned go from pinned host memory (which the GPU reads
+// directly) into the workspace.  A kernel in the launch queue instead of an asynchronous memory
+// copy: the copy engine's hand-over to the next kernel costs more than the copy itself.  One
+// work-group, 64 KiB in flight per round; when every thread has read its share it tells the host,
+// through a word in the same pinned allocation, that the staging buffer may be refilled (an
+// event recorded behind the kernel would put a barrier into the queue for the same news).
+// ------------------------------------------------------------------------------------------
+constexpr int kUploadThreads = 1024;
+__global__ void __launch_bounds__(kUploadThreads)
+upload_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, int64_t n, uint64_t *done_flag, uint64_t ticket)
+{
+    for (int64_t i0 = threadIdx.x; i0 < n; i0 += kUploadThreads * 4) {
+        u32x4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (i0 + k * kUploadThreads < n) v[k] = src[i0 + k * kUploadThreads];
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (i0 + k * kUploadThreads < n) dst[i0 + k * kUploadThreads] = v[k];
+    }
+    __syncthreads();   // every thread's stores are issued, so all its loads from src have returned
+    if (threadIdx.x == 0) __hip_atomic_store(done_flag, ticket, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+// ------------------------------------------------------------------------------------------
 // Block copy: work-group (x, i) moves 16 KiB of K and of V of pair i (1024 lanes x 16 bytes each,
 // four per thread, all loads issued before the stores).
 // ------------------------------------------------------------------------------------------
@@ -1021,6 +1046,14 @@ int launch_kv_append(const void *k_new, const void *v_new, const int64_t *slot_m
     hipLaunchKernelGGL(kv_append_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
                        (const uint4 *)k_new, (const uint4 *)v_new, slot_map, T, H, vec_per_row, block_size,
                        (uint4 *)k_cache, (uint4 *)v_cache);
+    return (int)hipGetLastError();
+}
+
+int launch_upload(const void *pinned_src, void *dst, size_t bytes, uint64_t *pinned_flag, uint64_t ticket, void *stream)
+{
+    const int64_t n = (int64_t)(bytes / 16);
+    hipLaunchKernelGGL(upload_kernel, dim3(1), dim3(kUploadThreads), 0, (hipStream_t)stream,
+                       (const u32x4 *)pinned_src, (u32x4 *)dst, n, pinned_flag, ticket);
     return (int)hipGetLastError();
 }
 
