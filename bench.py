@@ -96,9 +96,9 @@ class DeviceWorkload:
 
     def step(self):
         b = self.b
-        self.ctx.kv_append(self.k_new, self.v_new, self.slot_map, self.k_cache, self.v_cache)
-        self.ctx.mixed_paged_attention(self.q, self.k_cache, self.v_cache, self.block_table,
-                                       b.chunk_starts, b.context_lens, self.out, self.ws, scale=b.scale)
+        # kv_append + mixed_paged_attention through the library's one-call form
+        self.ctx.append_and_attend(self.k_new, self.v_new, self.slot_map, self.q, self.k_cache, self.v_cache,
+                                   self.block_table, b.chunk_starts, b.context_lens, self.out, self.ws, scale=b.scale)
 
     def attention_only(self, sub, q_rows, out, ws):
         """Attention over a sub-batch (sequence subset) sharing this workload's cache."""
@@ -442,7 +442,7 @@ def main():
         "config": {"workload": f"{b.name}: H={b.H} D={b.D} bs={b.bs}, {int((b.q_lens > 1).sum())} prompt chunk(s) "
                                f"{b.q_lens[b.q_lens > 1].tolist()} at prior {b.priors[b.q_lens > 1].tolist()}, "
                                f"{int((b.q_lens == 1).sum())} generation rows, {b.tg_kv_tokens()} generation KV tokens",
-                   "rows": b.T, "seqs": b.S, "step": "kv_append + mixed_paged_attention (plan + upload included)"},
+                   "rows": b.T, "seqs": b.S, "step": "kv_append + mixed_paged_attention in the one-call form mpa_append_and_attend (plan + upload included)"},
         "roofline": {"kernel": "attention_kernel (mixed)", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes": bytes_alg, "kernel_ms": attn_avg_ms},

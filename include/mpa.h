@@ -186,6 +186,19 @@ int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache,
                               void *stream);
 
 /*
+ * mpa_kv_append of all num_tokens rows followed by mpa_mixed_paged_attention, as one call: the
+ * append shares a launch with the upload of the call's work list (neither depends on the other,
+ * both precede the attention kernel), which takes one kernel out of the chain of an iteration.
+ * Arguments and errors as in the two calls; k_cache / v_cache are written (the new tokens' slots)
+ * and then read.  Same results, bit for bit, as the two separate calls.
+ */
+int mpa_append_and_attend(mpa_ctx *ctx, const void *k_new, const void *v_new, const int64_t *slot_map,
+                          const void *q, void *k_cache, void *v_cache, const int32_t *block_table,
+                          int32_t block_table_stride, const int32_t *chunk_starts, const int32_t *context_lens,
+                          int32_t num_seqs, int32_t num_tokens, float scale, void *out, void *workspace,
+                          size_t workspace_bytes, void *stream);
+
+/*
  * Kernel timing for benchmarks.  mpa_profile_enable(ctx, n) with n > 0 makes every following
  * mpa_mixed_paged_attention call record a pair of HIP events on its stream directly around the
  * launch of the main attention kernel (after the work-list copy, before the merge), for up to n

@@ -260,14 +260,26 @@ int mpa_copy_blocks(mpa_ctx *ctx, const void *src_k, const void *src_v, void *ds
     return MPA_OK;
 }
 
-int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache, const void *v_cache,
-                              const int32_t *block_table, int32_t block_table_stride,
-                              const int32_t *chunk_starts, const int32_t *context_lens,
-                              int32_t num_seqs, int32_t num_tokens, float scale, void *out,
-                              void *workspace, size_t workspace_bytes, void *stream)
+}  // extern "C"
+
+namespace {
+// The new K/V of the iteration, when the append travels with the attention call.
+struct AppendArgs {
+    const void *k_new, *v_new;
+    const int64_t *slot_map;
+    void *k_cache, *v_cache;
+};
+
+int attend(mpa_ctx *ctx, const AppendArgs *app, const void *q, const void *k_cache, const void *v_cache,
+           const int32_t *block_table, int32_t block_table_stride, const int32_t *chunk_starts,
+           const int32_t *context_lens, int32_t num_seqs, int32_t num_tokens, float scale, void *out,
+           void *workspace, size_t workspace_bytes, void *stream)
 {
     if (!ctx || num_seqs < 0 || num_tokens < 0) return MPA_ERR_INVALID_ARG;
     if (num_seqs == 0) return num_tokens == 0 ? MPA_OK : MPA_ERR_BAD_BATCH;
+    if (app && (!app->k_new || !app->v_new || !app->slot_map || !aligned(app->k_new, 16) || !aligned(app->v_new, 16) ||
+                !aligned(app->slot_map, 8)))
+        return MPA_ERR_INVALID_ARG;
     if (!q || !k_cache || !v_cache || !block_table || !chunk_starts || !context_lens || !out)
         return MPA_ERR_INVALID_ARG;
     if (block_table_stride <= 0) return MPA_ERR_INVALID_ARG;
@@ -311,6 +323,11 @@ int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache, 
                                ctx->uploaded_stream == stream;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
+    if (list_in_place && app) {
+        int ae = launch_kv_append(app->k_new, app->v_new, app->slot_map, num_tokens, ctx->cfg.num_kv_heads,
+                                  ctx->cfg.head_dim, ctx->cfg.block_size, app->k_cache, app->v_cache, stream);
+        if (ae != 0) return fail((hipError_t)ae);
+    }
     if (!list_in_place) {
     // stage the work list in pinned memory and copy it into the workspace on the stream
     const size_t list_bytes = plan.off_acc;  // items, merge rows, teams, progress words; padded
@@ -333,8 +350,11 @@ int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache, 
     std::memset(h + plan.off_progress, 0xFF, (size_t)plan.progress_words * sizeof(uint32_t));  // kNotRunning
     if (list_bytes % 16 != 0) return MPA_ERR_WORKSPACE;   // the plan pads its sections
     st.ticket = ctx->next_ticket++;
-    if (int ue = launch_upload(h, workspace, list_bytes, const_cast<uint64_t *>(st.flag()), st.ticket, stream))
-        return fail((hipError_t)ue);
+    const int ue = app ? launch_append_upload(app->k_new, app->v_new, app->slot_map, num_tokens, ctx->cfg.num_kv_heads,
+                                              ctx->cfg.head_dim, ctx->cfg.block_size, app->k_cache, app->v_cache, h,
+                                              workspace, list_bytes, const_cast<uint64_t *>(st.flag()), st.ticket, stream)
+                       : launch_upload(h, workspace, list_bytes, const_cast<uint64_t *>(st.flag()), st.ticket, stream);
+    if (ue != 0) return fail((hipError_t)ue);
     st.in_flight = true;
     ctx->uploaded_ws = workspace;
     ctx->uploaded_stream = stream;
@@ -378,6 +398,30 @@ int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache, 
     he = launch_merge(p, ctx->cfg.head_dim, ctx->cfg.dtype == MPA_FP16, stream);
     if (he != 0) return fail((hipError_t)he);
     return MPA_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache, const void *v_cache,
+                              const int32_t *block_table, int32_t block_table_stride,
+                              const int32_t *chunk_starts, const int32_t *context_lens,
+                              int32_t num_seqs, int32_t num_tokens, float scale, void *out,
+                              void *workspace, size_t workspace_bytes, void *stream)
+{
+    return attend(ctx, nullptr, q, k_cache, v_cache, block_table, block_table_stride, chunk_starts, context_lens,
+                  num_seqs, num_tokens, scale, out, workspace, workspace_bytes, stream);
+}
+
+int mpa_append_and_attend(mpa_ctx *ctx, const void *k_new, const void *v_new, const int64_t *slot_map,
+                          const void *q, void *k_cache, void *v_cache, const int32_t *block_table,
+                          int32_t block_table_stride, const int32_t *chunk_starts, const int32_t *context_lens,
+                          int32_t num_seqs, int32_t num_tokens, float scale, void *out, void *workspace,
+                          size_t workspace_bytes, void *stream)
+{
+    const AppendArgs app = {k_new, v_new, slot_map, k_cache, v_cache};
+    return attend(ctx, &app, q, k_cache, v_cache, block_table, block_table_stride, chunk_starts, context_lens,
+                  num_seqs, num_tokens, scale, out, workspace, workspace_bytes, stream);
 }
 
 }  // extern "C"

@@ -113,13 +113,11 @@ __device__ __forceinline__ size_t page_offset(int32_t word, int32_t kv_heads, in
 // ------------------------------------------------------------------------------------------
 // KV append: one thread moves 16 bytes of K and 16 bytes of V.
 // ------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256)
-kv_append_kernel(const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_new,
-                 const int64_t *__restrict__ slot_map, int32_t T, int32_t H, int32_t vec_per_row,
-                 int32_t block_size, uint4 *__restrict__ k_cache, uint4 *__restrict__ v_cache)
+__device__ __forceinline__ void append_body(int64_t gid, const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_new,
+                                            const int64_t *__restrict__ slot_map, int32_t T, int32_t H, int32_t vec_per_row,
+                                            int32_t block_size, uint4 *__restrict__ k_cache, uint4 *__restrict__ v_cache)
 {
     const int64_t per_token = (int64_t)H * vec_per_row;
-    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (gid >= (int64_t)T * per_token) return;
     const int32_t t = (int32_t)(gid / per_token);
     const int32_t rem = (int32_t)(gid - (int64_t)t * per_token);
@@ -134,6 +132,14 @@ kv_append_kernel(const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_ne
     v_cache[dst] = v_new[gid];
 }
 
+__global__ void __launch_bounds__(256)
+kv_append_kernel(const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_new,
+                 const int64_t *__restrict__ slot_map, int32_t T, int32_t H, int32_t vec_per_row,
+                 int32_t block_size, uint4 *__restrict__ k_cache, uint4 *__restrict__ v_cache)
+{
+    append_body((int64_t)blockIdx.x * 256 + threadIdx.x, k_new, v_new, slot_map, T, H, vec_per_row, block_size, k_cache, v_cache);
+}
+
 // ------------------------------------------------------------------------------------------
 // Work-list upload: the few KiB the host planned go from pinned host memory (which the GPU reads
 // directly) into the workspace.  A kernel in the launch queue instead of an asynchronous memory
@@ -143,20 +149,43 @@ kv_append_kernel(const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_ne
 // event recorded behind the kernel would put a barrier into the queue for the same news).
 // ------------------------------------------------------------------------------------------
 constexpr int kUploadThreads = 1024;
-__global__ void __launch_bounds__(kUploadThreads)
-upload_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, int64_t n, uint64_t *done_flag, uint64_t ticket)
+template <int THREADS>
+__device__ __forceinline__ void upload_body(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, int64_t n,
+                                            uint64_t *done_flag, uint64_t ticket)
 {
-    for (int64_t i0 = threadIdx.x; i0 < n; i0 += kUploadThreads * 4) {
+    for (int64_t i0 = threadIdx.x; i0 < n; i0 += THREADS * 4) {
         u32x4 v[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k)
-            if (i0 + k * kUploadThreads < n) v[k] = src[i0 + k * kUploadThreads];
+            if (i0 + k * THREADS < n) v[k] = src[i0 + k * THREADS];
 #pragma unroll
         for (int k = 0; k < 4; ++k)
-            if (i0 + k * kUploadThreads < n) dst[i0 + k * kUploadThreads] = v[k];
+            if (i0 + k * THREADS < n) dst[i0 + k * THREADS] = v[k];
     }
     __syncthreads();   // every thread's stores are issued, so all its loads from src have returned
     if (threadIdx.x == 0) __hip_atomic_store(done_flag, ticket, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
+__global__ void __launch_bounds__(kUploadThreads)
+upload_kernel(const u32x4 *__restrict__ src, u32x4 *__restrict__ dst, int64_t n, uint64_t *done_flag, uint64_t ticket)
+{
+    upload_body<kUploadThreads>(src, dst, n, done_flag, ticket);
+}
+
+// The append of an iteration's K/V and the upload of its work list in one launch (neither needs
+// the other; both must precede the attention kernel): work-group 0 uploads, the rest append.
+__global__ void __launch_bounds__(256)
+append_upload_kernel(const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_new,
+                     const int64_t *__restrict__ slot_map, int32_t T, int32_t H, int32_t vec_per_row,
+                     int32_t block_size, uint4 *__restrict__ k_cache, uint4 *__restrict__ v_cache,
+                     const u32x4 *__restrict__ list_src, u32x4 *__restrict__ list_dst, int64_t list_vecs,
+                     uint64_t *done_flag, uint64_t ticket)
+{
+    if (blockIdx.x == 0) {
+        upload_body<256>(list_src, list_dst, list_vecs, done_flag, ticket);
+        return;
+    }
+    append_body(((int64_t)blockIdx.x - 1) * 256 + threadIdx.x, k_new, v_new, slot_map, T, H, vec_per_row, block_size, k_cache, v_cache);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1054,6 +1083,21 @@ int launch_upload(const void *pinned_src, void *dst, size_t bytes, uint64_t *pin
     const int64_t n = (int64_t)(bytes / 16);
     hipLaunchKernelGGL(upload_kernel, dim3(1), dim3(kUploadThreads), 0, (hipStream_t)stream,
                        (const u32x4 *)pinned_src, (u32x4 *)dst, n, pinned_flag, ticket);
+    return (int)hipGetLastError();
+}
+
+int launch_append_upload(const void *k_new, const void *v_new, const int64_t *slot_map, int32_t T, int32_t H, int32_t D,
+                         int32_t block_size, void *k_cache, void *v_cache, const void *pinned_src, void *dst,
+                         size_t bytes, uint64_t *pinned_flag, uint64_t ticket, void *stream)
+{
+    const int32_t vec_per_row = D / 8;
+    const int64_t total = (int64_t)T * H * vec_per_row;
+    const int64_t blocks = 1 + (total + 255) / 256;
+    if (blocks > 0x7FFFFFFF) return (int)hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(append_upload_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
+                       (const uint4 *)k_new, (const uint4 *)v_new, slot_map, T, H, vec_per_row, block_size,
+                       (uint4 *)k_cache, (uint4 *)v_cache, (const u32x4 *)pinned_src, (u32x4 *)dst, (int64_t)(bytes / 16),
+                       pinned_flag, ticket);
     return (int)hipGetLastError();
 }
 

@@ -123,6 +123,9 @@ int launch_kv_append(const void *k_new, const void *v_new, const int64_t *slot_m
                      int32_t H, int32_t D, int32_t block_size, void *k_cache, void *v_cache, void *stream);
 // bytes: a multiple of 16; *pinned_flag (host memory the GPU can write) receives `ticket` once pinned_src has been read
 int launch_upload(const void *pinned_src, void *dst, size_t bytes, uint64_t *pinned_flag, uint64_t ticket, void *stream);
+int launch_append_upload(const void *k_new, const void *v_new, const int64_t *slot_map, int32_t T, int32_t H, int32_t D,
+                         int32_t block_size, void *k_cache, void *v_cache, const void *pinned_src, void *dst,
+                         size_t bytes, uint64_t *pinned_flag, uint64_t ticket, void *stream);
 int launch_copy_blocks(const void *src_k, const void *src_v, void *dst_k, void *dst_v, const int64_t *pairs,
                        int32_t n, int64_t block_bytes, void *stream);
 int launch_attention(const AttnParams &p, int32_t D, bool fp16, void *stream);

@@ -201,3 +201,40 @@ def test_copy_blocks_swaps_a_sequence_out_and_back_in(mpa, H, HK, D, bs):
     torch.cuda.synchronize()
     assert np.array_equal(to_host_u16(d_kc), kc)
     assert mpa.load().mpa_copy_blocks(c._h, None, None, None, None, None, 0, None) == 0
+
+
+@pytest.mark.parametrize("make", [
+    lambda: W.config1(),
+    lambda: W.config1(dtype="fp16"),
+    lambda: W.random_ragged(7100, H=8, D=128, bs=32, n_pp=3, n_tg=5, max_q=300, max_prior=900, max_ctx=1500, Hkv=2),
+    lambda: W.make_batch("fused-mixed", 61, 4, 128, 16, 400, [600, 300, 1, 1, 1], [1500, 300, 700, 64, 2000]),
+], ids=["cfg1", "cfg1-fp16", "ragged-gqa-bs32", "prompt-heavy"])
+def test_append_and_attend_equals_the_two_calls(mpa, make):
+    """The one-call form (append sharing a launch with the work-list upload) against kv_append
+    followed by mixed_paged_attention: caches and outputs bit for bit, first with a fresh work
+    list, then with the list left in the workspace (plan cache level 2), and against the oracle."""
+    import torch
+    b = make()
+    dt = mpa.MPA_FP16 if b.dtype == "fp16" else mpa.MPA_BF16
+    ref = oracle_run(b)[0]
+    outs = []
+    for fused in (False, True):
+        ctx = mpa.Context(b.H, b.D, block_size=b.bs, num_kv_heads=b.HK, dtype=dt)
+        ctx.set_option(mpa.MPA_OPT_PLAN_CACHE, 2)
+        ws = torch.empty(ctx.workspace_bytes_for_batch(b.chunk_starts, b.context_lens), dtype=torch.uint8, device="cuda")
+        ws.fill_(0xFF)
+        for call in range(2):
+            db = DeviceBatch(b, "prior")
+            if fused:
+                ctx.append_and_attend(db.k_new, db.v_new, db.slot_map, db.q, db.k_cache, db.v_cache, db.block_table,
+                                      b.chunk_starts, b.context_lens, db.out, ws, scale=b.scale)
+            else:
+                run_on(ctx, db, b, ws)
+            torch.cuda.synchronize()
+            outs.append((to_host_u16(db.out), to_host_u16(db.k_cache), to_host_u16(db.v_cache)))
+    for o in outs[1:]:
+        for got, want in zip(o, outs[0]):
+            assert np.array_equal(got, want)
+    assert_close(outs[0][0], ref, b.name, dtype=b.dtype)
+    kc, vc = oracle_run(b)[1:]
+    assert np.array_equal(outs[2][1], kc) and np.array_equal(outs[2][2], vc)
