@@ -80,6 +80,9 @@ enum {
     MPA_OPT_PP_TEAM_MIN_STEPS = 5, /* shortest key range, in 64-key steps, whose query tiles keep
                                     pace with each other to share K/V through L2; 0 = automatic,
                                     a huge value switches pacing off                          */
+    MPA_OPT_PROFILE_EVERY = 7,   /* with mpa_profile_enable: time every k-th attention call only
+                                    (default 1); a pair of timing events costs the queue about
+                                    ten microseconds per call                                 */
     MPA_OPT_PLAN_CACHE = 6       /* 1 (default) = a call whose chunk_starts / context_lens equal
                                     the previous call's reuses its work list (the layers of one
                                     model iteration all present the same batch); 0 = plan anew

@@ -65,6 +65,8 @@ struct mpa_ctx {
     bool uploaded_valid = false;
     std::vector<hipEvent_t> prof_events;  // start/stop pairs
     int32_t prof_used = 0;                // pairs recorded in the current series
+    int32_t prof_every = 1;               // MPA_OPT_PROFILE_EVERY
+    int64_t prof_calls = 0;               // attention calls since profiling was enabled
     std::mutex mu;
 };
 
@@ -126,6 +128,7 @@ int mpa_profile_enable(mpa_ctx *ctx, int32_t max_calls)
     for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
     ctx->prof_events.clear();
     ctx->prof_used = 0;
+    ctx->prof_calls = 0;
     for (int32_t i = 0; i < 2 * max_calls; ++i) {
         hipEvent_t e;
         hipError_t rc = hipEventCreate(&e);
@@ -173,6 +176,10 @@ int mpa_set_option(mpa_ctx *ctx, int32_t option, int64_t value)
         if (value < 0 || value > 2) return MPA_ERR_INVALID_ARG;
         ctx->plan_cache = value != 0;
         ctx->keep_upload = value == 2;
+        return MPA_OK;
+    case MPA_OPT_PROFILE_EVERY:
+        if (value < 1 || value > 1 << 20) return MPA_ERR_INVALID_ARG;
+        ctx->prof_every = (int32_t)value;
         return MPA_OK;
     case MPA_OPT_PP_TEAM_MIN_STEPS:
         if (value < 0) return MPA_ERR_INVALID_ARG;
@@ -387,7 +394,8 @@ int attend(mpa_ctx *ctx, const AppendArgs *app, const void *q, const void *k_cac
     p.teams = reinterpret_cast<const TeamRef *>(ws + plan.off_teams);
     p.progress = reinterpret_cast<uint32_t *>(ws + plan.off_progress);
 
-    const bool prof = (size_t)(2 * ctx->prof_used + 1) < ctx->prof_events.size();
+    const bool prof = (size_t)(2 * ctx->prof_used + 1) < ctx->prof_events.size() &&
+                      ctx->prof_calls++ % ctx->prof_every == 0;
     if (prof && (e = hipEventRecord(ctx->prof_events[2 * ctx->prof_used], s)) != hipSuccess) return fail(e);
     int he = launch_attention(p, ctx->cfg.head_dim, ctx->cfg.dtype == MPA_FP16, stream);
     if (he != 0) return fail((hipError_t)he);
