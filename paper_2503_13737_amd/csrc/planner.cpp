@@ -57,6 +57,7 @@ int64_t auto_row_split_tokens(const PlanOptions &opt, int64_t total_tokens)
 // occupies one of the kTileSlots resident work-groups; generation rows keep the memory pipe busy
 // for `row_us` anyway), and the longest range within a few percent of the best score wins.
 constexpr int64_t kTileSlots = 512;      // 2 resident work-groups per compute unit
+constexpr double kStepBesideRowsUs = 3.5; // the same while generation rows saturate HBM (loads take longer), fitted
 constexpr double kStepUs = 1.9;          // one 64-key step of a 128-row tile with the chip full, measured
 constexpr double kPieceOverheadSteps = 5.0;  // item and Q loads, first tile, partial result, its share of the merge
 constexpr double kRowBytesPerUs = 6.0e6; // generation rows stream at about 6 TB/s
@@ -317,7 +318,17 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
         const double tile_us = (double)steps * opt.heads * kStepUs / (double)kTileSlots;
         int64_t wgs = units;
         if (opt.pp_resident_wgs > 0) wgs = std::min(units, opt.pp_resident_wgs);
-        else if (!rows.empty() && row_us > 0.15 * tile_us) wgs = std::min(units, kTileSlots * 3 / 4);
+        else if (!rows.empty() && row_us > 0.15 * tile_us) {
+            wgs = std::min(units, kTileSlots * 3 / 4);
+            // Rows that last more than twice as long as the tiles hide them anyway: then only as
+            // many work-groups walk the tile units as finish them within 0.7 of the rows' time
+            // (a step takes kStepBesideRowsUs while the rows saturate HBM), and the slots they
+            // leave go to rows from the start (measured: config 3 2 % shorter, prior 0 3 %).
+            if (row_us > 2.0 * tile_us) {
+                const double need = (double)steps * opt.heads * kStepBesideRowsUs / (0.7 * row_us);
+                wgs = std::min(wgs, std::max<int64_t>((int64_t)need + 1, (units + 3) / 4));
+            }
+        }
         plan->n_tile_wgs = (int32_t)wgs;
     }
     // Teams: runs of adjacent tiles with the same (sequence, first key) -- see TeamRef.
