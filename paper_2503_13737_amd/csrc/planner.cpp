@@ -30,6 +30,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 constexpr int64_t kRowItemTarget = 256 * 8 * 2;
 constexpr int64_t kMaxRowSplitTokens = 1536;
 constexpr int64_t kMinRowSplitTokens = 128;
+constexpr int64_t kRowSlots = 512;          // work-groups resident at a time (2 per compute unit)
 constexpr int64_t kMinTileSplitSteps = 8;   // 512 keys
 constexpr int64_t kTeamMinSteps = 16;       // shorter ranges do not drift apart far enough to matter
 // Grouped K/V heads: from this group size on a generation row runs on the matrix-core body, one
@@ -41,13 +42,36 @@ constexpr int64_t kMinGroupSplitSteps = 4;
 
 // Key range of a row item in tokens: whole KV blocks, at least kMinRowSplitTokens, few enough
 // items for every wavefront slot to see several.
-int64_t auto_row_split_tokens(const PlanOptions &opt, int64_t total_tokens)
+//
+// Around that length the one is taken whose work-groups fill whole rounds of the resident slots
+// best: the rows are bandwidth-bound, so a last round with few work-groups in it streams at a
+// fraction of the chip's rate for a whole range's time (measured on configs 2 and 3: kernel times
+// follow this fill factor, 2 % between good and bad lengths).
+int64_t auto_row_split_tokens(const PlanOptions &opt, int64_t total_tokens, const std::vector<int64_t> &row_keys)
 {
     const int64_t bs = opt.block_size;
     if (opt.tg_split_blocks > 0) return opt.tg_split_blocks * bs;
     const int64_t want = std::min(std::max<int64_t>(ceil_div(total_tokens * opt.heads, kRowItemTarget), kMinRowSplitTokens),
                                   kMaxRowSplitTokens);
-    return ceil_div(want, bs) * bs;
+    const int64_t want_blocks = ceil_div(want, bs);
+    if (row_keys.empty() || row_keys.size() > 512) return want_blocks * bs;   // keeps the search to a few microseconds
+    const int64_t lo = std::max<int64_t>(ceil_div(kMinRowSplitTokens, bs), want_blocks * 2 / 3);
+    const int64_t hi = std::max(lo, std::min<int64_t>(kMaxRowSplitTokens / bs, want_blocks * 3 / 2));
+    const int64_t wgs_per_item = ceil_div(opt.heads, kWaves);
+    int64_t best = want_blocks;
+    double best_fill = -1.0;
+    for (int64_t nb = lo; nb <= hi; ++nb) {
+        int64_t items = 0;
+        for (int64_t keys : row_keys) items += ceil_div(keys, nb * bs);
+        const int64_t wgs = items * wgs_per_item;
+        const double fill = (double)wgs / (double)(ceil_div(wgs, kRowSlots) * kRowSlots);
+        const bool nearer = std::llabs(nb - want_blocks) < std::llabs(best - want_blocks);
+        if (fill > best_fill + 1e-9 || (fill > best_fill - 1e-9 && nearer)) {
+            best_fill = fill;
+            best = nb;
+        }
+    }
+    return best * bs;
 }
 
 // Key-range length for prompt tiles.  `tile_steps` holds, per tile, the number of 64-key steps
@@ -187,13 +211,17 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
     if (cs[0] != 0) return MPA_ERR_BAD_BATCH;
     const int64_t bs = opt.block_size;
     int64_t row_tokens = 0;   // keys visited by generation rows, in whole blocks
+    std::vector<int64_t> row_keys;   // the same per row
     std::vector<int64_t> tile_steps;
     for (int32_t i = 0; i < S; ++i) {
         int64_t q_len = (int64_t)cs[i + 1] - cs[i];
         if (q_len < 1 || ctx[i] < q_len) return MPA_ERR_BAD_BATCH;
         int64_t prior = ctx[i] - q_len;
         if (q_len == 1 || opt.pp_rowstream) {
-            for (int64_t j = 0; j < q_len; ++j) row_tokens += ceil_div(prior + j + 1, bs) * bs;
+            for (int64_t j = 0; j < q_len; ++j) {
+                row_tokens += ceil_div(prior + j + 1, bs) * bs;
+                row_keys.push_back(prior + j + 1);
+            }
         } else {
             for (int64_t r0 = 0; r0 < q_len; r0 += kTileRows) {
                 int64_t rows = std::min<int64_t>(kTileRows, q_len - r0);
@@ -204,7 +232,10 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
     const int64_t group = opt.heads / opt.kv_heads;
     // generation rows become group items (one tile holds the whole group)
     const bool rows_on_tiles = group >= kGroupMin && group <= kTileRows && !opt.pp_rowstream;
-    const int64_t row_split = auto_row_split_tokens(opt, row_tokens);
+    // (next to prompt tiles, which hold slots of their own for part of the launch, the rounds do
+    // not come out as counted: there the plain target length stays)
+    static const std::vector<int64_t> kNoRows;
+    const int64_t row_split = auto_row_split_tokens(opt, row_tokens, tile_steps.empty() ? row_keys : kNoRows);
     // key range of a group item, in keys: enough items for the chip, whole 64-key steps
     const int64_t group_split =
         std::max<int64_t>(ceil_div(ceil_div(row_tokens * opt.kv_heads, kGroupItemTarget), kKvTile),
