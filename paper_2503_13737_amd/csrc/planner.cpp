@@ -58,6 +58,11 @@ int64_t auto_row_split_tokens(const PlanOptions &opt, int64_t total_tokens, cons
     const int64_t lo = std::max<int64_t>(ceil_div(kMinRowSplitTokens, bs), want_blocks * 2 / 3);
     const int64_t hi = std::max(lo, std::min<int64_t>(kMaxRowSplitTokens / bs, want_blocks * 3 / 2));
     const int64_t wgs_per_item = ceil_div(opt.heads, kWaves);
+    {   // with many rounds the last one weighs little, and the longest ranges are the cheapest
+        int64_t items = 0;
+        for (int64_t keys : row_keys) items += ceil_div(keys, want_blocks * bs);
+        if (items * wgs_per_item > 4 * kRowSlots) return want_blocks * bs;
+    }
     int64_t best = want_blocks;
     double best_fill = -1.0;
     for (int64_t nb = lo; nb <= hi; ++nb) {
