@@ -265,8 +265,8 @@ def run_scheduled(args, mpa):
             if need > ws["buf"].numel():
                 torch.cuda.synchronize()
                 ws["buf"] = torch.empty(need * 2, dtype=torch.uint8, device=dev)
-            ctx.kv_append(k_all[:T, :HK], v_all[:T, :HK], d_slots, k_cache, v_cache)
-            ctx.mixed_paged_attention(q_all[:T], k_cache, v_cache, d_table, cs, ctxl, out[:T], ws["buf"], scale=1.0 / math.sqrt(D))
+            ctx.append_and_attend(k_all[:T, :HK], v_all[:T, :HK], d_slots, q_all[:T], k_cache, v_cache, d_table, cs, ctxl,
+                                  out[:T], ws["buf"], scale=1.0 / math.sqrt(D))
         t2 = time.perf_counter()
         state["now"] += iter_time(T)
         sched.complete(state["now"])
