@@ -336,36 +336,37 @@ int attend(mpa_ctx *ctx, const AppendArgs *app, const void *q, const void *k_cac
         if (ae != 0) return fail((hipError_t)ae);
     }
     if (!list_in_place) {
-    // stage the work list in pinned memory and copy it into the workspace on the stream
-    const size_t list_bytes = plan.off_acc;  // items, merge rows, teams, progress words; padded
-    Staging &st = ctx->staging[ctx->next_slot];
-    ctx->next_slot = (ctx->next_slot + 1) % kStagingSlots;
-    st.wait();
-    if (st.bytes < list_bytes) {
-        if (st.host) (void)hipHostFree(st.host);
-        st.host = nullptr;
-        st.bytes = 0;
-        size_t want = list_bytes * 2;
-        if ((e = hipHostMalloc(&st.host, kStagingHeader + want, hipHostMallocCoherent)) != hipSuccess) return fail(e);
-        st.bytes = want;
-        *st.flag() = 0;
-    }
-    char *h = st.data();
-    std::memcpy(h + plan.off_items, plan.items.data(), plan.items.size() * sizeof(WorkItem));
-    std::memcpy(h + plan.off_merge, plan.merge.data(), plan.merge.size() * sizeof(MergeRow));
-    std::memcpy(h + plan.off_teams, plan.teams.data(), plan.teams.size() * sizeof(TeamRef));
-    std::memset(h + plan.off_progress, 0xFF, (size_t)plan.progress_words * sizeof(uint32_t));  // kNotRunning
-    if (list_bytes % 16 != 0) return MPA_ERR_WORKSPACE;   // the plan pads its sections
-    st.ticket = ctx->next_ticket++;
-    const int ue = app ? launch_append_upload(app->k_new, app->v_new, app->slot_map, num_tokens, ctx->cfg.num_kv_heads,
-                                              ctx->cfg.head_dim, ctx->cfg.block_size, app->k_cache, app->v_cache, h,
-                                              workspace, list_bytes, const_cast<uint64_t *>(st.flag()), st.ticket, stream)
-                       : launch_upload(h, workspace, list_bytes, const_cast<uint64_t *>(st.flag()), st.ticket, stream);
-    if (ue != 0) return fail((hipError_t)ue);
-    st.in_flight = true;
-    ctx->uploaded_ws = workspace;
-    ctx->uploaded_stream = stream;
-    ctx->uploaded_valid = true;
+        // stage the work list in pinned memory; a small kernel carries it into the workspace on the stream
+        const size_t list_bytes = plan.off_acc;  // items, merge rows, teams, progress words; padded
+        Staging &st = ctx->staging[ctx->next_slot];
+        ctx->next_slot = (ctx->next_slot + 1) % kStagingSlots;
+        st.wait();
+        if (st.bytes < list_bytes) {
+            if (st.host) (void)hipHostFree(st.host);
+            st.host = nullptr;
+            st.bytes = 0;
+            size_t want = list_bytes * 2;
+            if ((e = hipHostMalloc(&st.host, kStagingHeader + want, hipHostMallocCoherent)) != hipSuccess)
+                return fail(e);
+            st.bytes = want;
+            *st.flag() = 0;
+        }
+        char *h = st.data();
+        std::memcpy(h + plan.off_items, plan.items.data(), plan.items.size() * sizeof(WorkItem));
+        std::memcpy(h + plan.off_merge, plan.merge.data(), plan.merge.size() * sizeof(MergeRow));
+        std::memcpy(h + plan.off_teams, plan.teams.data(), plan.teams.size() * sizeof(TeamRef));
+        std::memset(h + plan.off_progress, 0xFF, (size_t)plan.progress_words * sizeof(uint32_t));  // kNotRunning
+        if (list_bytes % 16 != 0) return MPA_ERR_WORKSPACE;   // the plan pads its sections
+        st.ticket = ctx->next_ticket++;
+        const int ue = app ? launch_append_upload(app->k_new, app->v_new, app->slot_map, num_tokens, ctx->cfg.num_kv_heads,
+                                                  ctx->cfg.head_dim, ctx->cfg.block_size, app->k_cache, app->v_cache, h,
+                                                  workspace, list_bytes, const_cast<uint64_t *>(st.flag()), st.ticket, stream)
+                           : launch_upload(h, workspace, list_bytes, const_cast<uint64_t *>(st.flag()), st.ticket, stream);
+        if (ue != 0) return fail((hipError_t)ue);
+        st.in_flight = true;
+        ctx->uploaded_ws = workspace;
+        ctx->uploaded_stream = stream;
+        ctx->uploaded_valid = true;
     }
 
     char *ws = static_cast<char *>(workspace);
