@@ -143,3 +143,30 @@ def test_plan_large_configs_fit_upper_bound():
         need = c.workspace_bytes_for_batch(b.chunk_starts, b.context_lens)
         ub = c.workspace_bytes(b.S, b.T, int(b.context_lens.max()))
         assert 0 < need <= ub, (b.name, need, ub)
+
+
+def test_one_call_form_and_block_copy_reject_bad_arguments_without_gpu():
+    lib = mpa.load()
+    c = mpa.Context(4, 64)
+    cs = np.array([0, 3, 4], dtype=np.int32)
+    cl = np.array([5, 9], dtype=np.int32)
+    fake = ctypes.c_void_p(0x1000)   # aligned, never dereferenced: every case fails validation first
+
+    def call(kn=fake, vn=fake, sm=fake, q=fake, ws=fake, wsb=1 << 20, T=4):
+        return lib.mpa_append_and_attend(c._h, kn, vn, sm, q, fake, fake, fake, 4, mpa._ptr(cs), mpa._ptr(cl), 2, T,
+                                         0.0, fake, ws, wsb, None)
+
+    assert call(kn=None) == mpa.MPA_ERR_INVALID_ARG
+    assert call(vn=ctypes.c_void_p(0x1008)) == mpa.MPA_ERR_INVALID_ARG
+    assert call(sm=ctypes.c_void_p(0x1004)) == mpa.MPA_ERR_INVALID_ARG
+    assert call(q=None) == mpa.MPA_ERR_INVALID_ARG
+    assert call(T=7) == mpa.MPA_ERR_BAD_BATCH
+    assert call(ws=None) == mpa.MPA_ERR_WORKSPACE          # nothing is appended when the call is refused
+    assert lib.mpa_append_and_attend(c._h, None, None, None, None, None, None, None, 0, None, None, 0, 0, 0.0,
+                                     None, None, 0, None) == mpa.MPA_OK
+    assert lib.mpa_copy_blocks(c._h, None, fake, fake, fake, fake, 3, None) == mpa.MPA_ERR_INVALID_ARG
+    assert lib.mpa_copy_blocks(c._h, fake, fake, fake, fake, ctypes.c_void_p(0x1004), 3, None) == mpa.MPA_ERR_INVALID_ARG
+    assert lib.mpa_copy_blocks(c._h, fake, fake, fake, fake, fake, -1, None) == mpa.MPA_ERR_INVALID_ARG
+    assert lib.mpa_copy_blocks(None, fake, fake, fake, fake, fake, 1, None) == mpa.MPA_ERR_INVALID_ARG
+    with pytest.raises(mpa.MpaError):
+        c.set_option(mpa.MPA_OPT_PROFILE_EVERY, 0)
