@@ -313,3 +313,39 @@ def test_fp16_flat_softmax_over_a_long_context(mpa):
     ql, ctx = [200, 1, 1], [6000, 9000, 3000]
     b = W.make_batch("fp16-flat", 17, 4, 128, 16, sum((c + 15) // 16 for c in ctx) + 3, ql, ctx, dtype="fp16")
     fp16_check(mpa, b, [{}, {"MPA_OPT_PP_SPLIT_TOKENS": 1024}], scale=1e-3)
+
+
+def test_random_combinations_of_geometry_dtype_and_options(mpa):
+    """Thirty seeded draws over head layout, head_dim, block size, storage type, batch mix and
+    planner options at once (the dedicated tests vary these one or two at a time), each through the
+    one-call form and checked against the oracle, caches included."""
+    import torch
+    draws = W.bits(30 * 12, 4711).reshape(30, 12)
+    for n, u in enumerate(draws):
+        u = [int(x) for x in u]
+        D = (64, 128)[u[0] % 2]
+        HK = (1, 2, 3, 4)[u[1] % 4]
+        group = (1, 1, 2, 4, 8)[u[2] % 5]
+        H = HK * group
+        bs = (16, 32, 64, 128)[u[3] % 4]
+        dtype = ("bf16", "fp16")[u[4] % 2]
+        n_pp, n_tg = u[5] % 3, 1 + u[6] % 5
+        b = W.random_ragged(8000 + n, H=H, D=D, bs=bs, n_pp=n_pp, n_tg=n_tg, max_q=40 + u[7] % 400,
+                            max_prior=u[8] % 1500, max_ctx=1 + u[9] % 2500, Hkv=HK, dtype=dtype)
+        opts = {}
+        if u[10] % 3 == 1:
+            opts = {"MPA_OPT_TG_SPLIT_BLOCKS": 1 + u[11] % 7, "MPA_OPT_PP_SPLIT_TOKENS": 64 * (1 + u[11] % 5)}
+        elif u[10] % 3 == 2:
+            opts = {"MPA_OPT_PP_RESIDENT_WGS": 1 + u[11] % 9, "MPA_OPT_PP_TEAM_MIN_STEPS": 1 + u[11] % 3}
+        what = f"draw {n}: H={H} HK={HK} D={D} bs={bs} {dtype} pp={n_pp} tg={n_tg} T={b.T} {opts}"
+        print(what, flush=True)
+        ctx = ctx_for(mpa, b, **opts)
+        db = DeviceBatch(b, "prior")
+        ws = torch.empty(ctx.workspace_bytes_for_batch(b.chunk_starts, b.context_lens), dtype=torch.uint8, device="cuda")
+        ws.fill_(0xFF)
+        ctx.append_and_attend(db.k_new, db.v_new, db.slot_map, db.q, db.k_cache, db.v_cache, db.block_table,
+                              b.chunk_starts, b.context_lens, db.out, ws, scale=b.scale)
+        torch.cuda.synchronize()
+        ref, okc, ovc = oracle_run(b)
+        assert np.array_equal(to_host_u16(db.k_cache), okc) and np.array_equal(to_host_u16(db.v_cache), ovc), what
+        assert_close(to_host_u16(db.out), ref, what, dtype=dtype)
