@@ -22,6 +22,9 @@
  *     host memory read during the call only.  The library allocates no device memory.
  *   - Work is enqueued on the HIP stream passed as `stream` (a hipStream_t cast to void*,
  *     NULL = the default stream) and the call returns without waiting for the GPU.
+ *   - The attention calls plan on the host from the two host arrays and hand the plan to the GPU
+ *     through a ring of pinned host buffers owned by the context: they are asynchronous, but not
+ *     meant for capture into a HIP graph (a replay would re-read a buffer that later calls reuse).
  *   - Elements are 16-bit (bf16 or fp16, fixed per context; passed as bit patterns); scores,
  *     softmax sums and outputs accumulate in fp32.
  *
