@@ -29,7 +29,9 @@ Readings where the paper is silent are listed in the design notes of the reposit
 shape this file: SLO_min is the SLO of the queue head; generation tasks returning from the last
 iteration stay in the batch; a victim that is a prompt chunk is shortened before it is dropped; a
 generation task preempted for KVC gives its blocks back and re-enters as a prompt over all its
-tokens (recompute), one preempted for the token budget keeps them; L_c is the mean length of the
+tokens (recompute) -- or, when a swap pool is configured and has room, moves them there and
+copies them back into fresh blocks when it is scheduled again --, one preempted for the token
+budget keeps them; L_c is the mean length of the
 chunks formed so far (S_pf before the first); a prompt is long if it exceeds S_pf; a long prompt
 that may not begin yet is skipped when the candidates are drawn, and one in progress is always a
 candidate; distances are compared as exact integers (squared), ties go to the earlier queue
@@ -40,7 +42,9 @@ from __future__ import annotations
 import math
 from dataclasses import dataclass, field
 
-WAITING, RETURNED, PREEMPTED = 0, 1, 2   # prompt (new / partly processed / recompute), TG back from the last iteration, TG set aside
+# prompt (new / partly processed / recompute), TG back from the last iteration, TG set aside with its
+# blocks, TG set aside with its blocks moved to the swap pool
+WAITING, RETURNED, PREEMPTED, SWAPPED = 0, 1, 2, 3
 
 
 @dataclass
@@ -60,6 +64,7 @@ class Request:
     offline: bool = False  # has a JCT SLO instead of per-token SLOs
     allowance: float = 0.0 # waiting time allowed per iteration, fixed when the request arrives
     carry: float = 0.0     # unused (+) or overdrawn (-) waiting time of the iterations so far
+    swap: list = field(default_factory=list)   # its blocks in the swap pool while it is swapped out
 
     @property
     def is_prompt(self):
@@ -79,7 +84,10 @@ class Entry:
 
 class Scheduler:
     def __init__(self, block_size, num_blocks, pivot_forward_size, pivot_time, max_batch_time, gamma,
-                 max_batch_tokens, block_order=None, preempt_max_time=0.0, preempt_probability=0.0):
+                 max_batch_tokens, block_order=None, preempt_max_time=0.0, preempt_probability=0.0, swap_blocks=0):
+        self.swap_free = list(range(int(swap_blocks)))[::-1]   # a stack like the main pool's
+        self.swap_out, self.swap_in = [], []                   # (from, to) block pairs of the last decision
+        self._has_swap = int(swap_blocks) > 0
         self.p_max, self.p_prob = float(preempt_max_time), float(preempt_probability)
         self.b, self.nb = int(block_size), int(num_blocks)
         self.s_pf, self.t_pf, self.t_max, self.gamma = int(pivot_forward_size), float(pivot_time), float(max_batch_time), float(gamma)
@@ -144,6 +152,7 @@ class Scheduler:
     def next_batch(self, now: float):
         live = list(self.reqs.values())
         self.batch, self.preempted_now = [], []
+        self.swap_out, self.swap_in = [], []
         if not live:
             self.token_budget = 0
             return self.batch
@@ -201,6 +210,12 @@ class Scheduler:
                 r.carry = (r.allowance + r.carry) - waited
             for _ in range(e.new_blocks):
                 e.req.blocks.append(self.free.pop())
+            if r.state == SWAPPED:
+                # back in: its content returns into the first of its fresh blocks, in order
+                for i, sb in enumerate(r.swap):
+                    self.swap_in.append((sb, r.blocks[i]))
+                    self.swap_free.append(sb)
+                r.swap, r.state = [], PREEMPTED
             if e.req.is_prompt:
                 e.req.started = True
                 self.chunk_tokens += e.tokens
@@ -210,6 +225,17 @@ class Scheduler:
     def preempt(self, r: Request, now: float, release: bool):
         self.preempted_now.append(r.id)
         r.t_enter = now
+        if r.state == SWAPPED:
+            return                       # it holds nothing here; it simply does not get in
+        if release and self._has_swap and len(r.blocks) <= len(self.swap_free):
+            # swap: its blocks move to the other pool and are free here
+            for blk in r.blocks:
+                sb = self.swap_free.pop()
+                self.swap_out.append((blk, sb))
+                r.swap.append(sb)
+                self.free.append(blk)
+            r.blocks, r.state = [], SWAPPED
+            return
         if release:
             # recompute: everything it holds goes back, all its tokens become a prompt again
             for blk in r.blocks:
@@ -281,6 +307,13 @@ class Scheduler:
                 slot_map.append(r.blocks[pos // self.b] * self.b + pos % self.b)
             tables.append(list(r.blocks[: -(-(prior + e.tokens) // self.b)]))
         return ids, chunk_starts, context_lens, slot_map, tables
+
+    def batch_swaps(self):
+        """Block copies this decision asks for, as (source, destination) pairs: first those out of
+        the cache pool into the swap pool, then those back in.  All of them come before the
+        iteration's append; the ones out before the ones in (a block given up may be handed to a
+        returning request in the same decision)."""
+        return list(self.swap_out), list(self.swap_in)
 
     # ---- the iteration has run
     def complete(self, now: float):

@@ -234,3 +234,49 @@ def test_offline_allowance_and_its_propagation():
     assert r.state == SO.RETURNED and r.carry == pytest.approx(0.25, abs=1e-12)
     s.next_batch(11.25)
     assert r.carry == pytest.approx(0.65, abs=1e-12)
+
+
+@pytest.mark.parametrize("seed,nb,swap", [(3, 600, 400), (2, 500, 64), (5, 700, 30000)])
+def test_swap_pool_keeps_preempted_tasks_whole(seed, nb, swap):
+    """With a swap pool a generation task preempted for KVC keeps its tokens: its blocks are copied
+    out (pairs reported), freed here, and copied back into fresh blocks when it runs again, its
+    context continuing where it stopped.  Both pools conserve their blocks; every copy's source is
+    owned by the victim at that moment and every destination is free; when the swap pool is too
+    small the task is recomputed instead."""
+    b = 16
+    trace = W.poisson_trace(150, seed, rate=8.0, max_prompt=3000, max_new=64)
+    s = SO.Scheduler(b, nb, 768, 0.05, 0.05, 0.75, 2048, None, swap_blocks=swap)
+    seen, stats = {}, {"out": 0, "in": 0, "recomputed": 0}
+    owner_before = {}
+
+    def check(s, batch, now):
+        out_pairs, in_pairs = s.batch_swaps()
+        held = [blk for r in s.reqs.values() for blk in r.blocks]
+        swapped = [blk for r in s.reqs.values() for blk in r.swap]
+        assert len(set(held)) == len(held) and len(held) + len(s.free) == nb
+        assert len(set(swapped)) == len(swapped) and len(swapped) + len(s.swap_free) == swap
+        assert len({d for _, d in out_pairs}) == len(out_pairs) and len({d for _, d in in_pairs}) == len(in_pairs)
+        for src, dst in out_pairs:
+            assert owner_before.get(src) is not None, "a block copied out belonged to somebody before this decision"
+        for src, dst in in_pairs:
+            assert dst in held
+        stats["out"] += len(out_pairs)
+        stats["in"] += len(in_pairs)
+        _, cs, ctx, slots, tables = s.batch_arrays()
+        for e, c in zip(batch, ctx):
+            prior = c - e.tokens
+            hist = seen.setdefault(e.req.id, [0])
+            if prior == 0 and hist[0] != 0:
+                stats["recomputed"] += 1
+                hist[0] = 0
+            assert prior == hist[0]
+            hist[0] = c
+        owner_before.clear()
+        owner_before.update({blk: r.id for r in s.reqs.values() for blk in r.blocks})
+
+    done = simulate(s, trace, 1500, lambda sf: 0.05 * max(sf, 64) / 768, check)
+    assert stats["out"] > 0 and stats["in"] > 0 and len(done) > 10
+    if swap >= 30000:
+        assert stats["recomputed"] == 0
+    if swap <= 64:
+        assert stats["recomputed"] > 0
