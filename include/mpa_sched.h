@@ -22,7 +22,10 @@
  * A request runs as prompt chunks until all its prompt tokens are cached; the last chunk yields
  * its first token.  From then on it is a generation task that feeds one token per iteration.  A
  * generation task preempted because blocks ran out gives its blocks back and re-enters as a
- * prompt over all its tokens (recomputation); one preempted for the token budget keeps them.
+ * prompt over all its tokens (recomputation) -- or, with a swap pool configured and room in it, has
+ * its blocks copied there and copied back into fresh blocks when it is scheduled again (the pairs
+ * to copy come with the batch; mpa_copy_blocks does the copying); one preempted for the token
+ * budget keeps its blocks.
  *
  * All pointers are host memory.  Functions return MPA_OK or a negative MPA_ERR_* of mpa.h.
  * One scheduler must not be used from two threads at once.
@@ -48,6 +51,7 @@ typedef struct {
     double gamma;               /* window of remaining times considered together (Sec. 4.4)     */
     double preempt_max_time;    /* P_max: longest preemption, seconds; offline requests only    */
     double preempt_probability; /* P: chance of a preemption after a generated token (Sec. 4.3) */
+    int32_t num_swap_blocks;    /* blocks of the swap pool; 0 = preempted tasks are recomputed    */
 } mpa_sched_config;
 
 typedef struct {
@@ -59,6 +63,8 @@ typedef struct {
     int32_t num_preempted;      /* requests taken out of the batch by this decision             */
     int32_t max_blocks_per_seq; /* widest block-table row of the batch                          */
     int32_t free_blocks;        /* blocks left in the pool after this batch's allocations       */
+    int32_t num_swap_out;       /* blocks to copy from the cache pool to the swap pool ...      */
+    int32_t num_swap_in;        /* ... and from the swap pool into the cache pool, see below    */
 } mpa_sched_batch;
 
 /* block_order: [num_blocks], a permutation of 0..num_blocks-1 giving the order in which fresh
@@ -92,6 +98,13 @@ int mpa_sched_next_batch(mpa_sched *s, double now, mpa_sched_batch *info);
 int mpa_sched_batch_arrays(const mpa_sched *s, int64_t *request_ids, int32_t *chunk_starts,
                            int32_t *context_lens, int64_t *slot_map, int32_t *block_table,
                            int32_t block_table_stride);
+
+/* Block copies the batch formed last asks for, as {source block, destination block} pairs in the
+ * layout mpa_copy_blocks takes: out_pairs [num_swap_out, 2] from the cache pool into the swap pool,
+ * in_pairs [num_swap_in, 2] from the swap pool into the cache pool.  Both come before the
+ * iteration's append, the copies out before the copies in (a block given up may be handed to a
+ * returning request by the same decision).  Either pointer may be NULL. */
+int mpa_sched_batch_swaps(const mpa_sched *s, int64_t *out_pairs, int64_t *in_pairs);
 
 /* The iteration has run and ended at `now`: prompts advance, finished prompts become generation
  * tasks, requests that produced their last token leave and free their blocks.  Up to `cap` ids

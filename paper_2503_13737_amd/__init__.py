@@ -35,7 +35,7 @@ EXPORTS = [
     "mpa_workspace_bytes_for_batch", "mpa_workspace_bytes", "mpa_kv_append", "mpa_copy_blocks", "mpa_append_and_attend",
     "mpa_mixed_paged_attention", "mpa_plan_describe", "mpa_profile_enable", "mpa_profile_read",
     "mpa_sched_create", "mpa_sched_destroy", "mpa_sched_add_request", "mpa_sched_add_offline_request", "mpa_sched_next_batch",
-    "mpa_sched_batch_arrays", "mpa_sched_complete", "mpa_sched_live_requests",
+    "mpa_sched_batch_arrays", "mpa_sched_batch_swaps", "mpa_sched_complete", "mpa_sched_live_requests",
 ]
 
 
@@ -48,12 +48,14 @@ class SchedConfig(ctypes.Structure):
     _fields_ = [("block_size", ctypes.c_int32), ("num_blocks", ctypes.c_int32),
                 ("pivot_forward_size", ctypes.c_int32), ("max_batch_tokens", ctypes.c_int32),
                 ("pivot_time", ctypes.c_double), ("max_batch_time", ctypes.c_double), ("gamma", ctypes.c_double),
-                ("preempt_max_time", ctypes.c_double), ("preempt_probability", ctypes.c_double)]
+                ("preempt_max_time", ctypes.c_double), ("preempt_probability", ctypes.c_double),
+                ("num_swap_blocks", ctypes.c_int32)]
 
 
 class SchedBatch(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in ("num_seqs", "num_tokens", "token_budget", "num_prompt_chunks",
-                                              "num_generation", "num_preempted", "max_blocks_per_seq", "free_blocks")]
+                                              "num_generation", "num_preempted", "max_blocks_per_seq", "free_blocks",
+                                              "num_swap_out", "num_swap_in")]
 
 
 class MpaError(RuntimeError):
@@ -116,6 +118,8 @@ def load() -> ctypes.CDLL:
         lib.mpa_sched_next_batch.restype = ctypes.c_int
         lib.mpa_sched_batch_arrays.argtypes = [vp, vp, vp, vp, vp, vp, i32]
         lib.mpa_sched_batch_arrays.restype = ctypes.c_int
+        lib.mpa_sched_batch_swaps.argtypes = [vp, vp, vp]
+        lib.mpa_sched_batch_swaps.restype = ctypes.c_int
         lib.mpa_sched_complete.argtypes = [vp, f64, vp, i32, vp]
         lib.mpa_sched_complete.restype = ctypes.c_int
         lib.mpa_sched_live_requests.argtypes = [vp]
@@ -280,11 +284,11 @@ class Scheduler:
 
     def __init__(self, block_size: int, num_blocks: int, pivot_forward_size: int, pivot_time: float,
                  max_batch_time: float, gamma: float, max_batch_tokens: int, block_order=None,
-                 preempt_max_time: float = 0.0, preempt_probability: float = 0.0):
+                 preempt_max_time: float = 0.0, preempt_probability: float = 0.0, swap_blocks: int = 0):
         self._lib = load()
         self._h = ctypes.c_void_p()
         cfg = SchedConfig(block_size, num_blocks, pivot_forward_size, max_batch_tokens, pivot_time, max_batch_time, gamma,
-                          preempt_max_time, preempt_probability)
+                          preempt_max_time, preempt_probability, swap_blocks)
         order = None if block_order is None else _host_i32(block_order)
         if order is not None and order.size != num_blocks:
             raise MpaError(MPA_ERR_INVALID_ARG, "mpa_sched_create")
@@ -336,6 +340,16 @@ class Scheduler:
         if st != MPA_OK:
             raise MpaError(st, "mpa_sched_batch_arrays")
         return ids, cs, ctx, slots, table
+
+    def batch_swaps(self):
+        """(out_pairs [n,2], in_pairs [m,2]) int64 {source, destination} block pairs for mpa_copy_blocks: out of
+        the cache pool into the swap pool, and back in; both before the iteration's append, out first."""
+        out = np.empty((self.info.num_swap_out, 2), dtype=np.int64)
+        inn = np.empty((self.info.num_swap_in, 2), dtype=np.int64)
+        st = self._lib.mpa_sched_batch_swaps(self._h, _ptr(out), _ptr(inn))
+        if st != MPA_OK:
+            raise MpaError(st, "mpa_sched_batch_swaps")
+        return out, inn
 
     def complete(self, now: float) -> np.ndarray:
         cap = max(self.info.num_seqs, 1)

@@ -21,7 +21,9 @@
 
 namespace {
 
-enum State : uint8_t { kPrompt = 0, kReturned = 1, kSetAside = 2 };
+// prompt; generation task back from the last iteration; set aside with its blocks; set aside with
+// its blocks moved to the swap pool
+enum State : uint8_t { kPrompt = 0, kReturned = 1, kSetAside = 2, kSwapped = 3 };
 
 struct Req {
     int64_t id;
@@ -35,6 +37,7 @@ struct Req {
     bool offline = false;     // JCT SLO: `allowance` seconds of waiting per iteration, `carry` moved on
     double allowance = 0.0, carry = 0.0;
     std::vector<int32_t> blocks;
+    std::vector<int32_t> swap;    // its blocks in the swap pool while it is swapped out
 
     bool is_prompt() const { return state == kPrompt; }
     // tokens whose K/V are cached; a generation task has not fed its newest token yet
@@ -55,6 +58,8 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 struct mpa_sched {
     mpa_sched_config cfg;
     std::vector<int32_t> free_blocks;                       // stack, next block at the back
+    std::vector<int32_t> swap_free;                         // the same for the swap pool
+    std::vector<int64_t> swap_out, swap_in;                 // {source, destination} pairs of the last decision
     std::unordered_map<int64_t, std::unique_ptr<Req>> live;
     std::vector<Entry> batch;
     int64_t chunk_tokens = 0, chunks = 0;                   // for L_c, the mean chunk length
@@ -97,7 +102,7 @@ struct mpa_sched {
         if (r.is_prompt()) {
             n_ck = std::ceil((double)(r.prompt_len - r.processed) / mean_chunk());
             waited = now - r.t_enter;
-        } else if (r.state == kSetAside) {
+        } else if (r.state != kReturned) {   // set aside, with its blocks or swapped out
             waited = now - r.t_enter;
         }
         const double slack = (r.is_prompt() ? r.slo_first : r.slo_token) - waited;
@@ -109,8 +114,22 @@ struct mpa_sched {
         ++evicted;
         r.evicted_now = true;
         r.t_enter = now;
+        if (r.state == kSwapped) return;   // it holds nothing here; it simply does not get in
         if (!give_back_blocks) {
             r.state = kSetAside;
+            return;
+        }
+        if (cfg.num_swap_blocks > 0 && r.blocks.size() <= swap_free.size()) {
+            for (int32_t blk : r.blocks) {   // its blocks move to the other pool and are free here
+                const int32_t sb = swap_free.back();
+                swap_free.pop_back();
+                swap_out.push_back(blk);
+                swap_out.push_back(sb);
+                r.swap.push_back(sb);
+                free_blocks.push_back(blk);
+            }
+            r.blocks.clear();
+            r.state = kSwapped;
             return;
         }
         for (int32_t blk : r.blocks) free_blocks.push_back(blk);
@@ -187,7 +206,7 @@ int mpa_sched_create(mpa_sched **out, const mpa_sched_config *cfg, const int32_t
     *out = nullptr;
     if (cfg->block_size < 1 || cfg->num_blocks < 1 || cfg->pivot_forward_size < 1 || cfg->max_batch_tokens < 1 ||
         !(cfg->pivot_time > 0.0) || !(cfg->max_batch_time > 0.0) || !(cfg->gamma >= 0.0) ||
-        !(cfg->preempt_max_time >= 0.0) || !(cfg->preempt_probability >= 0.0))
+        !(cfg->preempt_max_time >= 0.0) || !(cfg->preempt_probability >= 0.0) || cfg->num_swap_blocks < 0)
         return MPA_ERR_INVALID_ARG;
     std::unique_ptr<mpa_sched> s(new (std::nothrow) mpa_sched());
     if (!s) return MPA_ERR_INVALID_ARG;
@@ -201,6 +220,8 @@ int mpa_sched_create(mpa_sched **out, const mpa_sched_config *cfg, const int32_t
         seen[blk] = 1;
         s->free_blocks[n - 1 - i] = blk;   // handed out from the back
     }
+    s->swap_free.resize((size_t)cfg->num_swap_blocks);
+    for (int32_t i = 0; i < cfg->num_swap_blocks; ++i) s->swap_free[(size_t)(cfg->num_swap_blocks - 1 - i)] = i;
     *out = s.release();
     return MPA_OK;
 }
@@ -252,6 +273,8 @@ int mpa_sched_next_batch(mpa_sched *s, double now, mpa_sched_batch *info)
 {
     if (!s || !info) return MPA_ERR_INVALID_ARG;
     s->batch.clear();
+    s->swap_out.clear();
+    s->swap_in.clear();
     s->evicted = 0;
     s->token_budget = 0;
     *info = mpa_sched_batch{};
@@ -332,6 +355,15 @@ int mpa_sched_next_batch(mpa_sched *s, double now, mpa_sched_batch *info)
             e.r->blocks.push_back(s->free_blocks.back());
             s->free_blocks.pop_back();
         }
+        if (e.r->state == kSwapped) {   // back in: its content returns into the first of its fresh blocks
+            for (size_t k = 0; k < e.r->swap.size(); ++k) {
+                s->swap_in.push_back(e.r->swap[k]);
+                s->swap_in.push_back(e.r->blocks[k]);
+                s->swap_free.push_back(e.r->swap[k]);
+            }
+            e.r->swap.clear();
+            e.r->state = kSetAside;
+        }
         info->num_tokens += (int32_t)e.tokens;
         if (e.r->is_prompt()) {
             e.r->started = true;
@@ -347,6 +379,16 @@ int mpa_sched_next_batch(mpa_sched *s, double now, mpa_sched_batch *info)
     info->token_budget = s->token_budget;
     info->num_preempted = s->evicted;
     info->free_blocks = (int32_t)s->free_blocks.size();
+    info->num_swap_out = (int32_t)(s->swap_out.size() / 2);
+    info->num_swap_in = (int32_t)(s->swap_in.size() / 2);
+    return MPA_OK;
+}
+
+int mpa_sched_batch_swaps(const mpa_sched *s, int64_t *out_pairs, int64_t *in_pairs)
+{
+    if (!s) return MPA_ERR_INVALID_ARG;
+    if (out_pairs) std::copy(s->swap_out.begin(), s->swap_out.end(), out_pairs);
+    if (in_pairs) std::copy(s->swap_in.begin(), s->swap_in.end(), in_pairs);
     return MPA_OK;
 }
 

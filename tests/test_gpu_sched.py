@@ -11,13 +11,19 @@ from harness import assert_close, to_dev, to_host_u16
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("H,HK,D,bs,nb,dtype", [(4, 4, 128, 16, 1024, "bf16"), (8, 2, 64, 32, 60, "fp16")])
-def test_scheduler_batches_through_the_kernels(H, HK, D, bs, nb, dtype):
+@pytest.mark.parametrize("H,HK,D,bs,nb,dtype,swap", [(4, 4, 128, 16, 1024, "bf16", 0), (8, 2, 64, 32, 60, "fp16", 0),
+                                                         (4, 2, 128, 32, 60, "bf16", 80)])
+def test_scheduler_batches_through_the_kernels(H, HK, D, bs, nb, dtype, swap):
     import oracle
     import paper_2503_13737_amd as mpa
     import torch
     trace = W.poisson_trace(40, 5, rate=30.0, max_prompt=700, max_new=10)
-    sched = mpa.Scheduler(bs, nb, 256, 0.02, 0.02, 0.75, 512, block_order=W.permutation(nb, 5))
+    sched = mpa.Scheduler(bs, nb, 256, 0.02, 0.02, 0.75, 512, block_order=W.permutation(nb, 5), swap_blocks=swap)
+    # the swap pool: a second pair of caches, on the device here as well
+    sk = np.full((max(swap, 1), HK, bs, D), W.POISON, dtype=np.uint16)
+    sv = sk.copy()
+    d_sk, d_sv = to_dev(sk), to_dev(sv)
+    swapped = 0
     ctx = mpa.Context(H, D, block_size=bs, num_kv_heads=HK, dtype=mpa.MPA_FP16 if dtype == "fp16" else mpa.MPA_BF16)
     kc = np.full((nb, HK, bs, D), W.POISON, dtype=np.uint16)
     vc = kc.copy()
@@ -35,6 +41,18 @@ def test_scheduler_batches_through_the_kernels(H, HK, D, bs, nb, dtype):
         preempted += info.num_preempted
         chunks += info.num_prompt_chunks
         now += 0.02 * max(info.num_tokens, 16) / 256
+        # preempted tasks leave for the swap pool and return from it before anything else touches the blocks
+        out_pairs, in_pairs = sched.batch_swaps()
+        swapped += len(out_pairs)
+        if len(out_pairs):
+            ctx.copy_blocks(d_kc, d_vc, d_sk, d_sv, to_dev(out_pairs))
+            oracle.copy_blocks(kc, vc, sk, sv, out_pairs)
+            kc[out_pairs[:, 0]], vc[out_pairs[:, 0]] = W.POISON, W.POISON      # given up: nobody may read them
+            d_kc[torch.from_numpy(out_pairs[:, 0]).cuda()] = 0x7FFF
+            d_vc[torch.from_numpy(out_pairs[:, 0]).cuda()] = 0x7FFF
+        if len(in_pairs):
+            ctx.copy_blocks(d_sk, d_sv, d_kc, d_vc, to_dev(in_pairs))
+            oracle.copy_blocks(sk, sv, kc, vc, in_pairs)
         if info.num_seqs == 0:
             sched.complete(now)
             continue
@@ -62,3 +80,5 @@ def test_scheduler_batches_through_the_kernels(H, HK, D, bs, nb, dtype):
     assert chunks > 20 and finished > 5
     if nb * bs < 8000:
         assert preempted > 0
+    if swap:
+        assert swapped > 0

@@ -10,13 +10,13 @@ import workloads as W
 from oracle import sched_oracle as SO
 
 
-def run_both(trace, n_iter, b, nb, s_pf, t_pf, t_max, gamma, max_tokens, order, iter_time, offline_every=0):
+def run_both(trace, n_iter, b, nb, s_pf, t_pf, t_max, gamma, max_tokens, order, iter_time, offline_every=0, swap=0):
     """offline_every = k > 0: every k-th request is an offline one with a JCT SLO of 40 times its
     first-token SLO and a predicted length of half its real one."""
-    o = SO.Scheduler(b, nb, s_pf, t_pf, t_max, gamma, max_tokens, order, 1.5, 0.1)
-    c = mpa.Scheduler(b, nb, s_pf, t_pf, t_max, gamma, max_tokens, order, 1.5, 0.1)
+    o = SO.Scheduler(b, nb, s_pf, t_pf, t_max, gamma, max_tokens, order, 1.5, 0.1, swap)
+    c = mpa.Scheduler(b, nb, s_pf, t_pf, t_max, gamma, max_tokens, order, 1.5, 0.1, swap)
     now, nxt, n = 0.0, 0, len(trace["arrival"])
-    stats = {"batches": 0, "tokens": 0, "preempted": 0, "finished": 0, "chunks": 0}
+    stats = {"batches": 0, "tokens": 0, "preempted": 0, "finished": 0, "chunks": 0, "swapped": 0}
     for it in range(n_iter):
         while nxt < n and trace["arrival"][nxt] <= now:
             args = (nxt, int(trace["prompt_len"][nxt]), int(trace["max_new"][nxt]), float(trace["slo_first"][nxt]),
@@ -39,6 +39,10 @@ def run_both(trace, n_iter, b, nb, s_pf, t_pf, t_max, gamma, max_tokens, order, 
         assert info.num_prompt_chunks == sum(1 for e in ob if e.req.is_prompt), what
         g_ids, g_cs, g_ctx, g_slots, g_tab = c.batch_arrays()
         assert g_ids.tolist() == ids and g_cs.tolist() == cs and g_ctx.tolist() == ctx and g_slots.tolist() == slots, what
+        o_out, o_in = o.batch_swaps()
+        c_out, c_in = c.batch_swaps()
+        assert c_out.tolist() == [list(x) for x in o_out] and c_in.tolist() == [list(x) for x in o_in], what
+        stats["swapped"] += len(o_out)
         for row, ref in zip(g_tab, tables):
             assert row[: len(ref)].tolist() == ref and (row[len(ref):] == -1).all(), what
         now += iter_time(info.num_tokens)
@@ -69,6 +73,16 @@ def test_same_batches_with_offline_requests_in_the_mix(seed, nb, every):
     st = run_both(trace, 1200, 16, nb, 768, 0.05, 0.05, 0.75, 2048, W.permutation(nb, seed),
                   lambda sf: 0.05 * max(sf, 64) / 768, offline_every=every)
     assert st["batches"] > 300 and st["chunks"] > 50
+
+
+@pytest.mark.parametrize("seed,b,nb,swap", [(3, 16, 600, 400), (2, 16, 500, 64), (4, 32, 300, 1000), (7, 16, 600, 5)])
+def test_same_batches_with_a_swap_pool(seed, b, nb, swap):
+    """Preemption by swapping: the same block pairs out and in, the same fall-back to recomputation
+    when the swap pool is full."""
+    trace = W.poisson_trace(150, seed, rate=8.0, max_prompt=3000, max_new=64)
+    st = run_both(trace, 1200, b, nb, 768, 0.05, 0.05, 0.75, 2048, W.permutation(nb, seed + 40),
+                  lambda sf: 0.05 * max(sf, 64) / 768, offline_every=5, swap=swap)
+    assert st["preempted"] > 0 and st["swapped"] > 0
 
 
 def test_same_batches_with_tight_slos_and_a_small_budget():
