@@ -1,6 +1,8 @@
-// HIP kernels for gfx950 (MI355X): KV-cache append, the unified mixed-batch attention kernel
-// (row-streaming body for generation rows, matrix-core body for prompt tiles) and the merge of
-// split partial results.
+// HIP kernels for gfx950 (MI355X): KV-cache append, work-list upload (alone or sharing a launch
+// with the append), block copies between cache pools, the unified mixed-batch attention kernel
+// (row-streaming body for generation rows, matrix-core body for prompt tiles and for grouped
+// generation rows) and the merge of split partial results.  Every kernel that touches K/V
+// elements exists for both 16-bit storage types.
 #include <type_traits>
 #include <hip/hip_runtime.h>
 
@@ -223,7 +225,7 @@ copy_blocks_kernel(const u32x4 *__restrict__ src_k, const u32x4 *__restrict__ sr
 // ------------------------------------------------------------------------------------------
 // Row-streaming body: one wavefront, one query row, one head, a contiguous range of KV blocks.
 //
-// A (block, head) tile of K is 16 tokens x D bf16, contiguous.  A 1 KiB load (16 B per lane)
+// A (page, head) tile of K is 16 tokens x D 16-bit elements, contiguous.  A 1 KiB load (16 B per lane)
 // covers 64/LPR whole tokens (LPR = D/8 lanes per token): lane l holds elements
 // (l % LPR)*8 .. +7 of token l / LPR.  The LPR lanes of a token reduce their partial dot
 // products with DPP adds; each group of LPR lanes then runs its own online softmax over "its"
@@ -974,7 +976,8 @@ __device__ __forceinline__ WorkItem load_item(const WorkItem *src)
 }
 
 // ------------------------------------------------------------------------------------------
-// Unified kernel: work-groups [0, n_tile_items*H) run prompt tiles, the rest run row items
+// Unified kernel: the first n_tile_wgs work-groups walk the matrix-core units (a prompt tile for one
+// head, or one grouped generation row), each taking every n_tile_wgs-th; the rest run row items
 // (one wavefront per head, kWaves consecutive heads per work-group).
 // ------------------------------------------------------------------------------------------
 template <class E, int D>
