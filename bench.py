@@ -12,7 +12,7 @@ kernel of the mixed step (HBM bound: the generation rows dominate); `roofline_tg
 `roofline_pp` are the same kernel timed on the generation-only and prompt-only parts of the
 batch, against the HBM and bf16 matrix-core peaks respectively; `cpu_baseline` is the fp64
 oracle timed on the host cores on a sample of the same batch.  Other workloads (--workload): cfg1,
-cfg2, cfg4, cfg5[:iteration], gqa, <cfg>@bs32|64|128, <cfg>@fp16, sched13b (batches formed by the
+cfg2, cfg3:p<prior>, cfg4, cfg5[:iteration], gqa, <cfg>@bs32|64|128, <cfg>@fp16, sched13b (batches formed by the
 scheduler from a Poisson trace), swap13b (block copies).
 """
 from __future__ import annotations
@@ -31,6 +31,16 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix, published
+# what plain micro-kernels reach on this part (measured on the same machine, see the design notes):
+# a streaming non-temporal read of 8 GiB, and v_mfma_f32_32x32x16_bf16 back to back from registers
+HBM_ACHIEVABLE_GBS = 7150.0
+MFMA_ACHIEVABLE_TFLOPS = 2150.0
+
+
+def spread(ms) -> dict:
+    """Median and 10th / 90th percentile of the sampled kernel durations."""
+    p10, p50, p90 = (float(x) for x in np.percentile(ms, [10, 50, 90]))
+    return {"kernel_ms_p10": p10, "kernel_ms_p50": p50, "kernel_ms_p90": p90}
 
 
 def make_workload(name: str):
@@ -48,6 +58,8 @@ def make_workload(name: str):
         return W.config2(bs) if name.startswith("cfg2") else W.config3(bs=bs)
     if name == "cfg3":
         return W.config3()
+    if name.startswith("cfg3:p"):    # the same batch with the prompt chunk at a chosen prior context
+        return W.config3(prior=int(name[len("cfg3:p"):]))
     if name == "cfg2":
         return W.config2()
     if name == "cfg4":
@@ -453,7 +465,8 @@ def main():
         "roofline": {"kernel": "attention_kernel (mixed)", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes": bytes_alg, "kernel_ms": attn_avg_ms,
-                     "kernel_ms_samples": int(attn_ms.size)},
+                     "kernel_ms_samples": int(attn_ms.size), **spread(attn_ms),
+                     "achievable_peak": HBM_ACHIEVABLE_GBS, "frac_of_achievable": achieved / HBM_ACHIEVABLE_GBS},
     }
 
     if not args.no_parts:
@@ -466,7 +479,8 @@ def main():
             a = by / (float(ms.mean()) * 1e-3) / 1e9
             result["roofline_tg"] = {"kernel": "attention_kernel (generation rows only)", "bound": "hbm",
                                      "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": a / HBM_PEAK_GBS,
-                                     "algorithmic_bytes": by, "kernel_ms": float(ms.mean())}
+                                     "algorithmic_bytes": by, "kernel_ms": float(ms.mean()), **spread(ms),
+                                     "achievable_peak": HBM_ACHIEVABLE_GBS, "frac_of_achievable": a / HBM_ACHIEVABLE_GBS}
         if pp:
             sub, q, out, ws = sub_batch(dw, pp)
             _, ms = time_kernel(dw, lambda: dw.attention_only(sub, q, out, ws), args.steps, args.warmup)
@@ -475,7 +489,12 @@ def main():
             result["roofline_pp"] = {"kernel": "attention_kernel (prompt chunks only)", "bound": "mfma",
                                      "achieved": a, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                      "frac": a / MFMA_BF16_PEAK_TFLOPS, "algorithmic_flops": fl,
-                                     "kernel_ms": float(ms.mean())}
+                                     "kernel_ms": float(ms.mean()), **spread(ms),
+                                     "achievable_peak": MFMA_ACHIEVABLE_TFLOPS,
+                                     "frac_of_achievable": a / MFMA_ACHIEVABLE_TFLOPS}
+        if tg and pp:
+            # how much of the two parts' time the one launch hides: 1.0 = no overlap, lower is better
+            result["mixed_over_parts"] = attn_avg_ms / (result["roofline_tg"]["kernel_ms"] + result["roofline_pp"]["kernel_ms"])
 
     if args.calibrate_append_tokens > 0:
         n = args.calibrate_append_tokens
