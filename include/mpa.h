@@ -223,7 +223,9 @@ int mpa_profile_read(mpa_ctx *ctx, float *ms, int32_t cap, int32_t *n_out);
  * and returns the total number of items (which may exceed cap), or a negative status.
  * kind & 0xFF: 0 = a row for all heads on the streaming body, 1 = a tile of prompt rows for all
  * heads on the matrix-core body, 2 = one generation row for the query heads of K/V head
- * kind >> 8 on the matrix-core body (grouped K/V heads, group size >= 4).
+ * kind >> 8 on the matrix-core body (grouped K/V heads, group size >= 4).  Bit 8 of a tile's kind
+ * is set when no other tile of the batch reads its keys (and no K/V head is shared): its K/V is
+ * then fetched as data that is read once.
  * counts (optional, 4 int32): {matrix-core items, row items, merge rows, partial rows}.
  */
 int64_t mpa_plan_describe(const mpa_ctx *ctx, const int32_t *chunk_starts,

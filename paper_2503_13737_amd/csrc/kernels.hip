@@ -456,6 +456,7 @@ struct TileNext {
     uint32_t koff[TileCfg<D>::NL];        // this lane's byte offset inside the block for load i (K swizzle)
     uint32_t voff[TileCfg<D>::NL];        // same with the V swizzle
     uint32_t lds_w;                       // LDS address of the wavefront's 16 rows in the K tile of buffer 0
+    bool stream;                          // K/V of this item are read once (see load_to_lds_16)
 };
 
 // 16 bytes per lane from base + off (base wavefront-uniform, in scalar registers) straight into
@@ -465,12 +466,22 @@ struct TileNext {
 // operations: whoever needs the data waits for vmcnt(0) explicitly.  M0 is written and consumed
 // inside the statement and named as clobbered; nothing else in these kernels uses M0 (LDS
 // instructions of this architecture take none).
-__device__ __forceinline__ void load_to_lds_16(const char *base, uint32_t off, uint32_t lds_dst)
+// `stream` (wavefront-uniform) marks data that is read once: the load then carries the
+// non-temporal hint, as the loads of the row body do.  Measured on grouped generation rows: 8-10 %
+// more bytes per second than without it (prompt tiles, whose K/V other tiles read again from cache,
+// go without).
+__device__ __forceinline__ void load_to_lds_16(const char *base, uint32_t off, uint32_t lds_dst, bool stream)
 {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-                 :
-                 : "v"(off), "s"(base), "s"(lds_dst)
-                 : "m0");
+    if (stream)
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1 nt"
+                     :
+                     : "v"(off), "s"(base), "s"(lds_dst)
+                     : "m0");
+    else
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                     :
+                     : "v"(off), "s"(base), "s"(lds_dst)
+                     : "m0");
 }
 __device__ __forceinline__ void wait_loads_to_lds() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
@@ -492,8 +503,8 @@ __device__ __forceinline__ void tile_load(const TileNext<D> &n, int bufi, bool h
         const int row = wave * kPage + i * C::RPL + lane / C::CPR;   // row inside the tile
         const uint32_t dst = n.lds_w + bufi * (C::K_BYTES + C::V_BYTES) + i * C::RPL * C::ROW;
         if (have_block && row < keys_valid) {
-            load_to_lds_16(n.gk, n.koff[i], dst);
-            load_to_lds_16(n.gv, n.voff[i], dst + C::K_BYTES);
+            load_to_lds_16(n.gk, n.koff[i], dst, n.stream);
+            load_to_lds_16(n.gv, n.voff[i], dst + C::K_BYTES, n.stream);
         } else {
             *reinterpret_cast<lds_u32x4 *>(static_cast<uintptr_t>(dst + C::K_BYTES + lane * 16)) = u32x4{0u, 0u, 0u, 0u};
         }
@@ -619,8 +630,8 @@ __device__ __forceinline__ void tile_compute(const uint32_t (&kaddr)[TileCfg<D>:
     // inside the item's key range.
     auto load_part = [&](int i) {
         const uint32_t dst = next.lds_w + (BUFI ^ 1) * BUF + i * C::RPL * C::ROW;
-        load_to_lds_16(next.gk, next.koff[i], dst);
-        load_to_lds_16(next.gv, next.voff[i], dst + C::K_BYTES);
+        load_to_lds_16(next.gk, next.koff[i], dst, false);     // (items that stream do not load from in here)
+        load_to_lds_16(next.gv, next.voff[i], dst + C::K_BYTES, false);
     };
     auto mask_half = [&](f32x16 &sv, int kb) {
 #pragma unroll
@@ -852,6 +863,7 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
         }
         next.lds_w = __builtin_amdgcn_readfirstlane(lds0 + wave * kPage * C::ROW);
         next.gk = next.gv = nullptr;
+        next.stream = grouped || (it.kind & kSoloTile) != 0;
     }
 
     // Pipeline: while step s is computed from LDS buffer s&1, the direct loads of step s+1 fill the
@@ -893,7 +905,7 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
             if (lane < team.size) mates = progress_load(pace + lane);
         }
         if (more) point_at(blk_n);
-        if (active && blk_n >= 0 && keys_n >= kKvTile) {
+        if (active && blk_n >= 0 && keys_n >= kKvTile && !next.stream) {
             tile_compute<E, D, true, BUFI>(kaddr, vaddr, qf, o, m, l, c2, k0, pos, half, masked, next);
         } else {
             if (more) tile_load<D>(next, BUFI ^ 1, blk_n >= 0, keys_n, wave, lane);

@@ -21,6 +21,10 @@ constexpr int kWaves = kThreads / 64;
 // the tile are the H/HK query heads that share one K/V head (its index sits in kind >> 8), all at
 // the position of the one token q_row0; q_rows stays 1 (one token) in the work list.
 enum ItemKind : int32_t { kRowItem = 0, kTileItem = 1, kGroupItem = 2 };
+// Flag in the kind of a tile item: no other tile reads its keys (a chunk of one tile, or the ranges
+// only the chunk's last tile reaches) and no other head does (every query head has its own K/V
+// head), so its K/V passes through the caches once.
+constexpr int32_t kSoloTile = 1 << 8;
 
 // One unit of work.  A tile item is executed by one work-group per head; a row item by one
 // wavefront per head (a work-group covers kWaves consecutive heads).

@@ -334,6 +334,13 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
             return a.q_row0 < b.q_row0;
         });
         for (size_t i = 0; i < tiles.size(); ++i) tiles[i] = keyed[i].w;
+        // a tile that is alone on its (sequence, key range) reads K/V nobody else reads -- unless
+        // query heads share K/V heads: then the tile's units for those heads read it again
+        for (size_t i = 0; i < tiles.size() && group == 1; ++i) {
+            auto same = [&](size_t j) { return tiles[j].seq == tiles[i].seq && tiles[j].kv_begin == tiles[i].kv_begin; };
+            const bool shared = (i > 0 && same(i - 1)) || (i + 1 < tiles.size() && same(i + 1));
+            if (!shared) tiles[i].kind |= kSoloTile;
+        }
     }
     std::stable_sort(rows.begin(), rows.end(), longer);
     std::stable_sort(groups.begin(), groups.end(), longer);

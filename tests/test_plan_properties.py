@@ -21,7 +21,12 @@ def test_random_batches_plan_invariants(seed):
     items, counts = c.plan_describe(b.chunk_starts, b.context_lens)
     n_tile, n_row, n_merge, n_part = (int(x) for x in counts)
     assert n_tile + n_row == len(items)
-    assert (items[:n_tile, 7] == 1).all() and (items[n_tile:, 7] == 0).all()
+    assert ((items[:n_tile, 7] & 0xFF) == 1).all() and (items[n_tile:, 7] == 0).all()
+    # bit 8 of a tile's kind: no other tile starts at the same key of the same sequence
+    tiles = items[:n_tile]
+    for it in tiles:
+        alone = ((tiles[:, 0] == it[0]) & (tiles[:, 4] == it[4])).sum() == 1
+        assert (it[7] >> 8) == int(alone)
     assert (items[:, 4] % 16 == 0).all() and (items[:n_tile, 4] % 64 == 0).all()
     assert (items[:, 5] > items[:, 4]).all()
     assert (items[n_tile:, 2] == 1).all() and (items[:n_tile, 2] <= 128).all() and (items[:, 2] >= 1).all()
@@ -86,6 +91,8 @@ def test_grouped_heads_plan(H, HK):
         items, counts = c.plan_describe(b.chunk_starts, b.context_lens)
         kinds = items[:, 7] & 0xFF
         assert counts[0] + counts[1] == len(items)
+        if H != HK:   # shared K/V heads: no tile is marked as the only reader of its keys
+            assert ((items[kinds == 1][:, 7] >> 8) == 0).all()
         if 4 <= H // HK <= 128:
             assert counts[1] == 0 and (kinds == 2).sum() > 0 and (items[kinds == 2][:, 4] % 64 == 0).all()
             # group items sit between the prompt tiles and the (absent) row items
