@@ -992,6 +992,8 @@ __device__ __forceinline__ WorkItem load_item(const WorkItem *src)
 // head, or one grouped generation row), each taking every n_tile_wgs-th; the rest run row items
 // (one wavefront per head, kWaves consecutive heads per work-group).
 // ------------------------------------------------------------------------------------------
+constexpr int kXcds = 8;   // accelerator dies of the chip, each with its own L2
+
 template <class E, int D>
 __global__ void __launch_bounds__(kThreads, 2)
 attention_kernel(const AttnParams p)
@@ -1013,7 +1015,13 @@ attention_kernel(const AttnParams p)
             const bool is_tile = u < n_tile_units;
             const int32_t item = is_tile ? u / H : p.n_tile_items + (u - n_tile_units);
             const WorkItem it = load_item(p.items + item);
-            const int head = is_tile ? u % H : (it.kind >> 8) * p.group;
+            // Query heads that share a K/V head read the same K/V tiles: their units are placed
+            // kXcds launch positions apart, i.e. on the same XCD (work-groups go to the XCDs in
+            // turn), so that one L2 serves the group instead of one fetch from memory per head.
+            // Position j of an item is head (j mod kXcds) * (H / kXcds) + j / kXcds.
+            const int j = u % H;
+            const int tile_head = (p.group > 1 && H % kXcds == 0) ? (j % kXcds) * (H / kXcds) + j / kXcds : j;
+            const int head = is_tile ? tile_head : (it.kind >> 8) * p.group;
             TeamRef team = {-1, 0, 1, 0};
             if (is_tile) {
                 team.base = __builtin_amdgcn_readfirstlane(p.teams[item].base);
