@@ -12,7 +12,7 @@ kernel of the mixed step (HBM bound: the generation rows dominate); `roofline_tg
 `roofline_pp` are the same kernel timed on the generation-only and prompt-only parts of the
 batch, against the HBM and bf16 matrix-core peaks respectively; `cpu_baseline` is the fp64
 oracle timed on the host cores on a sample of the same batch.  Other workloads (--workload): cfg1,
-cfg2, cfg3:p<prior>, cfg4, cfg5[:iteration], gqa, <cfg>@bs32|64|128, <cfg>@fp16, sched13b (batches formed by the
+cfg2, cfg3:p<prior>, cfg4, cfg5[:iteration], gqa, gqa-decode, <cfg>@bs32|64|128, <cfg>@fp16, sched13b (batches formed by the
 scheduler from a Poisson trace), swap13b (block copies).
 """
 from __future__ import annotations
@@ -68,6 +68,8 @@ def make_workload(name: str):
         return W.config1()
     if name == "gqa":
         return W.config_gqa()
+    if name == "gqa-decode":
+        return W.config_gqa_decode()
     if name.startswith("cfg5"):
         it = int(name.split(":")[1]) if ":" in name else 47
         return W.config5(it)

@@ -104,6 +104,12 @@ def test_grouped_kv_layer():
     check_config(W.config_gqa())
 
 
+def test_grouped_kv_decode_of_a_whole_layer():
+    """64 query / 8 K/V heads, 64 generation rows at 4-12 K: every row runs as group items over
+    several key ranges (streamed K/V, partials, merge)."""
+    check_config(W.config_gqa_decode())
+
+
 @pytest.mark.parametrize("iteration", [0, 24, 48])
 def test_config5_long_prompt(iteration):
     check_config(W.config5(iteration))

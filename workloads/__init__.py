@@ -375,6 +375,16 @@ def config_gqa() -> Batch:
     return make_batch("gqa-16q-2kv-mixed", s, 16, 128, 16, 32768, ql, ctx, Hkv=2)
 
 
+def config_gqa_decode() -> Batch:
+    """Decode batch of a whole grouped-query layer (not one of the benchmark's five configs): 64 query
+    heads over 8 K/V heads, head_dim 128 (the head layout of the Llama-3-70B model the paper also
+    serves), 64 generation rows with contexts uniform on [4096, 12288]: 2 GB of K/V per step."""
+    s = config_seed(7)
+    ctx = uniform_ints(64, 4096, 12288, s * 4 + 2)
+    nb = int(sum((int(c) + 15) // 16 for c in ctx)) + 8
+    return make_batch("gqa-64q-8kv-decode", s, 64, 128, 16, nb, np.ones(64, dtype=np.int64), ctx, Hkv=8)
+
+
 CFG5_PROMPT = 100_000
 CFG5_CHUNK = 2048
 CFG5_ITERS = (CFG5_PROMPT + CFG5_CHUNK - 1) // CFG5_CHUNK  # 49
