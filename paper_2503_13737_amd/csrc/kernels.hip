@@ -988,9 +988,10 @@ __device__ __forceinline__ WorkItem load_item(const WorkItem *src)
 }
 
 // ------------------------------------------------------------------------------------------
-// Unified kernel: the first n_tile_wgs work-groups walk the matrix-core units (a prompt tile for one
-// head, or one grouped generation row), each taking every n_tile_wgs-th; the rest run row items
-// (one wavefront per head, kWaves consecutive heads per work-group).
+// Unified kernel: the first n_tile_wgs work-groups walk the prompt tiles' units (a tile for one
+// head), each taking every n_tile_wgs-th; then one work-group per group item (a generation row of
+// grouped K/V heads, on the matrix-core body as well); the rest run row items (one wavefront per
+// head, kWaves consecutive heads per work-group).
 // ------------------------------------------------------------------------------------------
 constexpr int kXcds = 8;   // accelerator dies of the chip, each with its own L2
 
@@ -1002,40 +1003,42 @@ attention_kernel(const AttnParams p)
     const int wave = threadIdx.x >> 6;
     const int H = p.heads;
     const int32_t n_tile_wg = p.n_tile_wgs;
+    // K/V tiles of the matrix-core body (the kernel's LDS is allocated for every work-group alike)
+    __shared__ __attribute__((aligned(16))) char lds[2 * (TileCfg<D>::K_BYTES + TileCfg<D>::V_BYTES)];
     if ((int32_t)blockIdx.x < n_tile_wg) {
         // Tile units (item, head) are dealt round-robin to the tile work-groups.  With as many
-        // work-groups as units each takes one; with fewer (mixed batches: half of the resident
-        // slots, so that generation rows stream through the other half from the start) each
+        // work-groups as units each takes one; with fewer (mixed batches: part of the resident
+        // slots, so that generation rows stream through the others from the start) each
         // walks its share, longest units first.
-        __shared__ __attribute__((aligned(16))) char lds[2 * (TileCfg<D>::K_BYTES + TileCfg<D>::V_BYTES)];
         const int32_t n_tile_units = p.n_tile_items * H;   // the launcher checks that this fits
-        const int32_t n_units = n_tile_units + p.n_group_items;
-        for (int32_t u = (int32_t)blockIdx.x; u < n_units; u += n_tile_wg) {
-            // a tile item is one unit per head; a group item is one unit and names its K/V head
-            const bool is_tile = u < n_tile_units;
-            const int32_t item = is_tile ? u / H : p.n_tile_items + (u - n_tile_units);
+        for (int32_t u = (int32_t)blockIdx.x; u < n_tile_units; u += n_tile_wg) {
+            const int32_t item = u / H;
             const WorkItem it = load_item(p.items + item);
             // Query heads that share a K/V head read the same K/V tiles: their units are placed
             // kXcds launch positions apart, i.e. on the same XCD (work-groups go to the XCDs in
             // turn), so that one L2 serves the group instead of one fetch from memory per head.
             // Position j of an item is head (j mod kXcds) * (H / kXcds) + j / kXcds.
             const int j = u % H;
-            const int tile_head = (p.group > 1 && H % kXcds == 0) ? (j % kXcds) * (H / kXcds) + j / kXcds : j;
-            const int head = is_tile ? tile_head : (it.kind >> 8) * p.group;
-            TeamRef team = {-1, 0, 1, 0};
-            if (is_tile) {
-                team.base = __builtin_amdgcn_readfirstlane(p.teams[item].base);
-                team.member = __builtin_amdgcn_readfirstlane(p.teams[item].member);
-                team.size = __builtin_amdgcn_readfirstlane(p.teams[item].size);
-                team.stride = __builtin_amdgcn_readfirstlane(p.teams[item].stride);
-            }
+            const int head = (p.group > 1 && H % kXcds == 0) ? (j % kXcds) * (H / kXcds) + j / kXcds : j;
+            TeamRef team;
+            team.base = __builtin_amdgcn_readfirstlane(p.teams[item].base);
+            team.member = __builtin_amdgcn_readfirstlane(p.teams[item].member);
+            team.size = __builtin_amdgcn_readfirstlane(p.teams[item].size);
+            team.stride = __builtin_amdgcn_readfirstlane(p.teams[item].stride);
             tile_body<E, D>(p, it, team, head, lds);
             __syncthreads();   // the next unit's first loads overwrite the tile buffers
         }
         return;
     }
+    if ((int32_t)blockIdx.x < n_tile_wg + p.n_group_items) {
+        // a group item (a generation row of grouped K/V heads) names its K/V head; one work-group each
+        const WorkItem it = load_item(p.items + p.n_tile_items + ((int32_t)blockIdx.x - n_tile_wg));
+        const TeamRef team = {-1, 0, 1, 0};
+        tile_body<E, D>(p, it, team, (it.kind >> 8) * p.group, lds);
+        return;
+    }
     const int hg = (H + kWaves - 1) / kWaves;
-    const int32_t idx = (int32_t)blockIdx.x - n_tile_wg;
+    const int32_t idx = (int32_t)blockIdx.x - n_tile_wg - p.n_group_items;
     const int32_t item = p.n_tile_items + p.n_group_items + idx / hg;
     const int head = (idx % hg) * kWaves + wave;
     if (head >= H) return;
@@ -1139,7 +1142,7 @@ int launch_copy_blocks(const void *src_k, const void *src_v, void *dst_k, void *
 int launch_attention(const AttnParams &p, int32_t D, bool fp16, void *stream)
 {
     const int hg = (p.heads + kWaves - 1) / kWaves;
-    const int64_t grid = (int64_t)p.n_tile_wgs + (int64_t)p.n_row_items * hg;
+    const int64_t grid = (int64_t)p.n_tile_wgs + p.n_group_items + (int64_t)p.n_row_items * hg;
     if (grid == 0) return 0;
     const int64_t units = (int64_t)p.n_tile_items * p.heads + p.n_group_items;
     if (grid > 0x7FFFFFFF || units > 0x7FFFFFFF) return (int)hipErrorInvalidConfiguration;

@@ -83,7 +83,7 @@ struct Plan {
     int32_t n_tile_items = 0;
     int32_t n_group_items = 0;
     int32_t n_row_items = 0;
-    int32_t n_tile_wgs = 0;       // work-groups that share the n_tile_items * heads + n_group_items units
+    int32_t n_tile_wgs = 0;       // work-groups that share the n_tile_items * heads tile units
     int64_t part_rows = 0;
 
     // workspace layout (byte offsets)

@@ -384,19 +384,21 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
     // streaming wavefront that shares its SIMD with a matrix-core wavefront gets about a third of
     // the issue slots it needs).
     {
-        const int64_t units = (int64_t)tiles.size() * opt.heads + (int64_t)groups.size();
+        const int64_t units = (int64_t)tiles.size() * opt.heads;   // group items have work-groups of their own
         int64_t steps = 0;
         for (int64_t st : tile_steps) steps += st;
         const double tile_us = (double)steps * opt.heads * kStepUs / (double)kTileSlots;
         int64_t wgs = units;
         if (opt.pp_resident_wgs > 0) wgs = std::min(units, opt.pp_resident_wgs);
-        else if (!rows.empty() && row_us > 0.15 * tile_us) {
+        else if ((!rows.empty() || !groups.empty()) && row_us > 0.15 * tile_us) {
             wgs = std::min(units, kTileSlots * 3 / 4);
             // Rows that last more than twice as long as the tiles hide them anyway: then only as
             // many work-groups walk the tile units as finish them within 0.7 of the rows' time
             // (a step takes kStepBesideRowsUs while the rows saturate HBM), and the slots they
             // leave go to rows from the start (measured: config 3 2 % shorter, prior 0 3 %).
-            if (row_us > 2.0 * tile_us) {
+            // (Not beside group items: measured on 32 query / 8 K/V heads, fewer tile work-groups
+            // than three quarters of the slots only lengthen the launch.)
+            if (row_us > 2.0 * tile_us && groups.empty()) {
                 const double need = (double)steps * opt.heads * kStepBesideRowsUs / (0.7 * row_us);
                 wgs = std::min(wgs, std::max<int64_t>((int64_t)need + 1, (units + 3) / 4));
             }
@@ -411,7 +413,7 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
     {
         const int64_t min_steps = opt.pp_team_min_steps > 0 ? opt.pp_team_min_steps : kTeamMinSteps;
         const bool want = opt.pp_team_min_steps > 0 ||
-                          plan->n_tile_wgs < (int64_t)tiles.size() * opt.heads + (int64_t)groups.size();
+                          plan->n_tile_wgs < (int64_t)tiles.size() * opt.heads;
         plan->teams.assign(tiles.size(), TeamRef{-1, 0, 1, 0});
         for (size_t i = 0; want && i < tiles.size();) {
             size_t j = i + 1;
