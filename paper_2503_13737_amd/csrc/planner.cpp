@@ -396,9 +396,7 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
             // many work-groups walk the tile units as finish them within 0.7 of the rows' time
             // (a step takes kStepBesideRowsUs while the rows saturate HBM), and the slots they
             // leave go to rows from the start (measured: config 3 2 % shorter, prior 0 3 %).
-            // (Not beside group items: measured on 32 query / 8 K/V heads, fewer tile work-groups
-            // than three quarters of the slots only lengthen the launch.)
-            if (row_us > 2.0 * tile_us && groups.empty()) {
+            if (row_us > 2.0 * tile_us) {
                 const double need = (double)steps * opt.heads * kStepBesideRowsUs / (0.7 * row_us);
                 wgs = std::min(wgs, std::max<int64_t>((int64_t)need + 1, (units + 3) / 4));
             }
