@@ -130,3 +130,23 @@ def test_workspace_bound_is_monotone():
     a = c.workspace_bytes(64, 64, 2048)
     assert c.workspace_bytes(128, 128, 2048) >= a and c.workspace_bytes(64, 64, 4096) >= a
     assert c.workspace_bytes(0, 0, 0) >= 0
+
+
+def test_range_lengths_of_generation_only_batches_fill_rounds_of_resident_work_groups():
+    """Batches of generation rows alone, few rounds: the range length is the one near the target
+    whose work-groups fill whole rounds of the 512 resident slots best -- for row items (a
+    work-group covers 4 heads of an item) and for group items (one work-group each)."""
+    z = W.uniform_ints(256, 2048, 8192, 77)
+    cs = np.arange(257, dtype=np.int32)
+    cl = z.astype(np.int32)
+    for H, HK in ((8, 1), (8, 8)):
+        c = mpa.Context(H, 128, num_kv_heads=HK)
+        items, counts = c.plan_describe(cs, cl)
+        kinds = items[:, 7] & 0xFF
+        wgs = int((kinds == 2).sum()) if HK == 1 else int((kinds == 0).sum()) * (H // 4)
+        assert wgs > 0
+        fill = wgs / (-(-wgs // 512) * 512)
+        assert fill >= 0.93, (H, HK, wgs, fill)
+        # and the plan is a function of the batch alone
+        items2, _ = c.plan_describe(cs, cl)
+        assert np.array_equal(items, items2)
