@@ -118,6 +118,7 @@ int64_t auto_group_split_keys(const PlanOptions &opt, int64_t total_tokens, cons
 // for `row_us` anyway), and the longest range within a few percent of the best score wins.
 constexpr int64_t kTileSlots = 512;      // 2 resident work-groups per compute unit
 constexpr double kStepBesideRowsUs = 3.5; // the same while generation rows saturate HBM (loads take longer), fitted
+constexpr double kStepBesideGroupsUs = 1.7;
 constexpr double kStepUs = 1.9;          // one 64-key step of a 128-row tile with the chip full, measured
 constexpr double kPieceOverheadSteps = 5.0;  // item and Q loads, first tile, partial result, its share of the merge
 constexpr double kRowBytesPerUs = 6.0e6; // generation rows stream at about 6 TB/s
@@ -397,7 +398,10 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
             // (a step takes kStepBesideRowsUs while the rows saturate HBM), and the slots they
             // leave go to rows from the start (measured: config 3 2 % shorter, prior 0 3 %).
             if (row_us > 2.0 * tile_us) {
-                const double need = (double)steps * opt.heads * kStepBesideRowsUs / (0.7 * row_us);
+                // (beside group items a tile step is shorter than beside row items -- measured on 32
+                // query / 8 K/V heads: the best counts of tile work-groups correspond to ~1.7 us)
+                const double step_us = groups.empty() ? kStepBesideRowsUs : kStepBesideGroupsUs;
+                const double need = (double)steps * opt.heads * step_us / (0.7 * row_us);
                 wgs = std::min(wgs, std::max<int64_t>((int64_t)need + 1, (units + 3) / 4));
             }
         }
