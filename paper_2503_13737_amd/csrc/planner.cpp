@@ -9,6 +9,7 @@
 // ranges when it is long.  Every item that is one of several over the same rows writes a
 // partial result, and the rows are listed for the merge pass.
 #include <algorithm>
+#include <cmath>
 #include <functional>
 #include <map>
 #include <numeric>
@@ -117,8 +118,6 @@ int64_t auto_group_split_keys(const PlanOptions &opt, int64_t total_tokens, cons
 // occupies one of the kTileSlots resident work-groups; generation rows keep the memory pipe busy
 // for `row_us` anyway), and the longest range within a few percent of the best score wins.
 constexpr int64_t kTileSlots = 512;      // 2 resident work-groups per compute unit
-constexpr double kStepBesideRowsUs = 3.5; // the same while generation rows saturate HBM (loads take longer), fitted
-constexpr double kStepBesideGroupsUs = 1.7;
 constexpr double kStepUs = 1.9;          // one 64-key step of a 128-row tile with the chip full, measured
 constexpr double kPieceOverheadSteps = 5.0;  // item and Q loads, first tile, partial result, its share of the merge
 constexpr double kRowBytesPerUs = 6.0e6; // generation rows stream at about 6 TB/s
@@ -378,12 +377,10 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
     plan->n_group_items = (int32_t)groups.size();
     plan->n_row_items = (int32_t)rows.size();
     // Work-groups for the tile units.  Alone, every unit gets its own and the hardware deals them
-    // out as slots free up.  Next to a substantial amount of generation rows the tiles get three
-    // quarters of the resident slots and keep them for the whole launch, while the rows stream
-    // through the rest from the first microsecond: measured 8-10 % shorter launches on
-    // prompt-heavy mixed batches than tiles first, rows after (more is not to be had this way: a
-    // streaming wavefront that shares its SIMD with a matrix-core wavefront gets about a third of
-    // the issue slots it needs).
+    // out as slots free up.  Next to a substantial amount of generation rows the tiles get a part
+    // of the resident slots and keep them for the whole launch, while the rows stream through
+    // the rest from the first microsecond: measured 8-15 % shorter launches on prompt-heavy
+    // mixed batches than tiles first, rows after.
     {
         const int64_t units = (int64_t)tiles.size() * opt.heads;   // group items have work-groups of their own
         int64_t steps = 0;
@@ -392,18 +389,19 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
         int64_t wgs = units;
         if (opt.pp_resident_wgs > 0) wgs = std::min(units, opt.pp_resident_wgs);
         else if ((!rows.empty() || !groups.empty()) && row_us > 0.15 * tile_us) {
-            wgs = std::min(units, kTileSlots * 3 / 4);
-            // Rows that last more than twice as long as the tiles hide them anyway: then only as
-            // many work-groups walk the tile units as finish them within 0.7 of the rows' time
-            // (a step takes kStepBesideRowsUs while the rows saturate HBM), and the slots they
-            // leave go to rows from the start (measured: config 3 2 % shorter, prior 0 3 %).
-            if (row_us > 2.0 * tile_us) {
-                // (beside group items a tile step is shorter than beside row items -- measured on 32
-                // query / 8 K/V heads: the best counts of tile work-groups correspond to ~1.7 us)
-                const double step_us = groups.empty() ? kStepBesideRowsUs : kStepBesideGroupsUs;
-                const double need = (double)steps * opt.heads * step_us / (0.7 * row_us);
-                wgs = std::min(wgs, std::max<int64_t>((int64_t)need + 1, (units + 3) / 4));
-            }
+            // The more prompt work there is for the generation rows' streaming time, the more of
+            // the slots the tiles keep: 256 (one per compute unit, a row work-group beside each)
+            // when the tiles alone would take half the rows' time, 64 more per doubling of that
+            // ratio.  Fitted to the best counts measured (config 3: 128, config 5 at iteration 8:
+            // 192-256, config 4 and config 5 at iteration 24: 320, iteration 47: 384-448; grouped K/V
+            // heads, 512 rows beside a 2048-token chunk: 128, 256 rows beside a 4096-token chunk:
+            // 384-448); with too few the tiles outlast the rows (half the best count costs 20-70 %),
+            // with too many the rows start late (all slots: 7-10 %).
+            const double rho = tile_us / row_us;
+            // (a multiple of 32: team mates sit heads * k units apart, and a count that is not a
+            // multiple of the number of XCDs moves them to different XCDs from the second turn on)
+            const int64_t by_ratio = 32 * (int64_t)std::llround((256.0 + 64.0 * std::log2(2.0 * rho)) / 32.0);
+            wgs = std::min(units, std::min<int64_t>(kTileSlots * 7 / 8, std::max<int64_t>(by_ratio, 128)));
         }
         plan->n_tile_wgs = (int32_t)wgs;
     }
