@@ -1012,13 +1012,25 @@ attention_kernel(const AttnParams p)
         // walks its share, longest units first.
         const int32_t n_tile_units = p.n_tile_items * H;   // the launcher checks that this fits
         for (int32_t u = (int32_t)blockIdx.x; u < n_tile_units; u += n_tile_wg) {
-            const int32_t item = u / H;
+            // Launch order inside a run of tiles that read the same keys (see TeamRef: member, size):
+            // eight heads at a time, the run's tiles of one head kXcds positions apart -- so the
+            // tiles that share K/V run at the same time, on one XCD, whatever the number of
+            // work-groups (in plain item order a run spans size * H units and its late members
+            // find the K/V gone from L2).
+            int32_t item = u / H, j = u % H;
+            if (H % kXcds == 0) {
+                const int32_t m = __builtin_amdgcn_readfirstlane(p.teams[item].member);
+                const int32_t size = __builtin_amdgcn_readfirstlane(p.teams[item].size);
+                const int32_t first = item - m, v = u - first * H;          // v in [0, size * H)
+                const int32_t block = v / (kXcds * size), within = v % (kXcds * size);
+                item = first + within / kXcds;
+                j = block * kXcds + within % kXcds;
+            }
             const WorkItem it = load_item(p.items + item);
             // Query heads that share a K/V head read the same K/V tiles: their units are placed
             // kXcds launch positions apart, i.e. on the same XCD (work-groups go to the XCDs in
             // turn), so that one L2 serves the group instead of one fetch from memory per head.
             // Position j of an item is head (j mod kXcds) * (H / kXcds) + j / kXcds.
-            const int j = u % H;
             const int head = (p.group > 1 && H % kXcds == 0) ? (j % kXcds) * (H / kXcds) + j / kXcds : j;
             TeamRef team;
             team.base = __builtin_amdgcn_readfirstlane(p.teams[item].base);

@@ -46,9 +46,9 @@ static_assert(sizeof(WorkItem) == 32, "work item layout");
 // has finished in progress[base + head * stride + member] (kNotRunning before its first and after
 // its last step), and members that get ahead of a running team mate pause briefly.
 struct TeamRef {
-    int32_t base;      // first word of the team's [heads][stride] progress array, or -1: no team
-    int32_t member;    // this item's index in the team
-    int32_t size;      // members (<= kTeamMax)
+    int32_t base;      // first word of the team's [heads][stride] progress array, or -1: no pacing
+    int32_t member;    // this item's index in its run of tiles over the same keys (set with or without pacing)
+    int32_t size;      // tiles of the run (<= kTeamMax)
     int32_t stride;    // words per head
 };
 constexpr uint32_t kNotRunning = 0xFFFFFFFFu;

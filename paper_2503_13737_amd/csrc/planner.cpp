@@ -415,18 +415,20 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
         const bool want = opt.pp_team_min_steps > 0 ||
                           plan->n_tile_wgs < (int64_t)tiles.size() * opt.heads;
         plan->teams.assign(tiles.size(), TeamRef{-1, 0, 1, 0});
-        for (size_t i = 0; want && i < tiles.size();) {
+        // Every run of tiles over one (sequence, first key) is recorded (member, size): the
+        // kernel keeps a run's units for one head next to each other in launch order.  Only where
+        // pacing is wanted does the run get progress words (base >= 0).
+        for (size_t i = 0; i < tiles.size();) {
             size_t j = i + 1;
             while (j < tiles.size() && j - i < (size_t)kTeamMax && tiles[j].seq == tiles[i].seq &&
                    tiles[j].kv_begin == tiles[i].kv_begin)
                 ++j;
             const int64_t steps = ceil_div((int64_t)tiles[i].kv_end - tiles[i].kv_begin, kKvTile);
-            if (j - i >= 2 && steps >= min_steps) {
-                const int32_t size = (int32_t)(j - i), stride = (size + 15) / 16 * 16;
-                for (size_t k = i; k < j; ++k)
-                    plan->teams[k] = TeamRef{(int32_t)plan->progress_words, (int32_t)(k - i), size, stride};
-                plan->progress_words += (int64_t)stride * opt.heads;
-            }
+            const int32_t size = (int32_t)(j - i), stride = (size + 15) / 16 * 16;
+            const bool paced = want && size >= 2 && steps >= min_steps;
+            for (size_t k = i; k < j; ++k)
+                plan->teams[k] = TeamRef{paced ? (int32_t)plan->progress_words : -1, (int32_t)(k - i), size, paced ? stride : 0};
+            if (paced) plan->progress_words += (int64_t)stride * opt.heads;
             i = j;
         }
     }
