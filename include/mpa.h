@@ -80,9 +80,10 @@ enum {
                                     (slow; cross-check of the matrix-core body)               */
     MPA_OPT_PP_RESIDENT_WGS = 4, /* work-groups that share the prompt-tile work (each takes
                                     every n-th unit); 0 = automatic                           */
-    MPA_OPT_PP_TEAM_MIN_STEPS = 5, /* shortest key range, in 64-key steps, whose query tiles keep
-                                    pace with each other to share K/V through L2; 0 = automatic,
-                                    a huge value switches pacing off                          */
+    MPA_OPT_PP_TEAM_MIN_STEPS = 5, /* > 0: the query tiles over one key range of at least this
+                                    many 64-key steps keep pace with each other (bounded
+                                    pauses of those ahead); 0 (default) = no pacing: such
+                                    tiles are launched next to each other and stay together */
     MPA_OPT_PROFILE_EVERY = 7,   /* with mpa_profile_enable: time every k-th attention call only
                                     (default 1); a pair of timing events costs the queue about
                                     ten microseconds per call                                 */

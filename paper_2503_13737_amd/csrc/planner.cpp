@@ -406,14 +406,13 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
         plan->n_tile_wgs = (int32_t)wgs;
     }
     // Teams: runs of adjacent tiles with the same (sequence, first key) -- see TeamRef.
-    // Pacing pays when the tiles' K/V fetches compete with the generation rows for HBM (measured:
-    // 2-5 % shorter launches on prompt-heavy mixed batches, 3-5 % longer ones on prompts alone,
-    // where the pauses cost more than the re-fetches), so teams exist in the shared-slot mode
-    // above, or when the option asks for them.
+    // Pacing is on request only: since a run's units are launched next to each other the tiles
+    // stay together by themselves (K/V fetched 1.08 x), and the pauses only cost (measured with
+    // pacing in every mixed launch: 2-4 % longer on configs 4 and 5, up to 8 % on grouped-head
+    // mixes; 1.5 % longer on prompts alone).
     {
         const int64_t min_steps = opt.pp_team_min_steps > 0 ? opt.pp_team_min_steps : kTeamMinSteps;
-        const bool want = opt.pp_team_min_steps > 0 ||
-                          plan->n_tile_wgs < (int64_t)tiles.size() * opt.heads;
+        const bool want = opt.pp_team_min_steps > 0;
         plan->teams.assign(tiles.size(), TeamRef{-1, 0, 1, 0});
         // Every run of tiles over one (sequence, first key) is recorded (member, size): the
         // kernel keeps a run's units for one head next to each other in launch order.  Only where
