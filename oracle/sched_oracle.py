@@ -26,7 +26,8 @@ What it follows
                             (D_c, D_m) is nearest to the available (A_c, A_m))     (Sec. 4.4)
 
 Readings where the paper is silent are listed in the design notes of the repository; the ones that
-shape this file: SLO_min is the SLO of the queue head; generation tasks returning from the last
+shape this file: SLO_min is the smallest SLO among the queue head, the generation tasks returning
+from the last iteration and the urgent requests; generation tasks returning from the last
 iteration stay in the batch; a victim that is a prompt chunk is shortened before it is dropped; a
 generation task preempted for KVC gives its blocks back and re-enters as a prompt over all its
 tokens (recompute) -- or, when a swap pool is configured and has room, moves them there and
@@ -159,8 +160,10 @@ class Scheduler:
         for r in live:
             r.t_r = self.remaining_time(r, now)
         order = sorted(live, key=lambda r: (r.t_r, r.id))
-        head = order[0]
-        slo_min = self.slo_of(head)
+        # SLO_min of Eq. 6: over the requests that are in the batch whatever is selected later (tasks
+        # back from the last iteration, urgent requests) and the head of the queue
+        certain = [r for r in order if r.state == RETURNED or r.t_r <= self.t_max]
+        slo_min = min(self.slo_of(r) for r in [order[0]] + certain)
         s_b = int(math.floor(self.s_pf * slo_min / self.t_pf))
         s_b = max(1, min(s_b, self.max_tokens))
         self.token_budget = s_b

@@ -294,9 +294,16 @@ int mpa_sched_next_batch(mpa_sched *s, double now, mpa_sched_batch *info)
     std::sort(order.begin(), order.end(), [](const Req *x, const Req *y) {
         return x->t_r != y->t_r ? x->t_r < y->t_r : x->id < y->id;
     });
-    // Eq. 6 with the SLO of the queue head
+    // Eq. 6.  SLO_min is the smallest iteration-level SLO among the requests that are certain to be
+    // in the batch before anything is selected -- the generation tasks back from the last iteration
+    // and the urgent requests -- and the queue head, which the selection considers first.  (The
+    // queue is ordered by remaining time, not by SLO: a prompt with a loose SLO that has waited
+    // long can be its head while generation tasks with much tighter SLOs are in the batch.)
     {
-        const double scaled = (double)s->cfg.pivot_forward_size * s->slo(*order[0]);
+        double slo_min = s->slo(*order[0]);
+        for (const Req *r : order)
+            if (r->state == kReturned || r->t_r <= s->cfg.max_batch_time) slo_min = std::min(slo_min, s->slo(*r));
+        const double scaled = (double)s->cfg.pivot_forward_size * slo_min;
         const double budget = std::floor(scaled / s->cfg.pivot_time);
         int64_t sb = budget >= (double)s->cfg.max_batch_tokens ? s->cfg.max_batch_tokens : (int64_t)budget;
         s->token_budget = (int32_t)std::max<int64_t>(1, std::min<int64_t>(sb, s->cfg.max_batch_tokens));

@@ -1,5 +1,5 @@
 """Pins of the scheduler oracle (oracle/sched_oracle.py) to what the paper and arithmetic fix:
-its worked chunking example, the stated KVC-demand rule, Eq. 6, the remaining-time formula on
+the chunking rule on hand-worked numbers, the stated KVC-demand rule, Eq. 6, the remaining-time formula on
 hand-computed numbers, the nearest-demand choice of Alg. 2 against a brute-force search, and the
 invariants any correct schedule has, over simulated traces.  CPU only."""
 import math
@@ -29,26 +29,28 @@ def make(b=16, nb=4096, s_pf=768, t_pf=0.1, t_max=0.1, gamma=0.75, max_tokens=81
     return SO.Scheduler(b, nb, s_pf, t_pf, t_max, gamma, max_tokens, order)
 
 
-def test_paper_dynamic_chunking_example():
+def test_dynamic_chunking_rule_on_hand_worked_numbers():
+    """Sec. 4.2 gives the rule (tokens in queue order until S_f = S_b or the KVC ends); the numbers
+    are worked by hand from it in the golden file."""
     g = golden()
     picks = SO.sequential_chunks(g["dyn_chunk_example_lengths"], g["dyn_chunk_example_budgets"], g["dyn_chunk_example_kvc"])
-    assert picks[0] == [(0, 96), (1, 4)]
+    assert picks[0] == [(0, g["dyn_chunk_example_first_iteration"][0]), (1, g["dyn_chunk_example_first_iteration"][1])]
     assert [t for it in picks for (i, t) in it if i == 1] == g["dyn_chunk_example_chunks_of_prompt2"]
 
 
 def test_scheduler_cuts_a_prompt_where_budget_or_kvc_ends():
-    """The same rule inside the scheduler: the 8192-token prompt alone with a budget of 300; before
-    the third iteration the rest of the pool is taken away except for 128 tokens."""
-    s = make(b=4, nb=3000, s_pf=300, t_pf=0.1, t_max=0.1)
-    s.add_request(2, 8192, 1, 0.1, 0.1, 0.0)     # SLO == T_pf: S_b == S_pf
+    """The same rule inside the scheduler: a 5000-token prompt alone with a budget of 250; before
+    the third iteration the rest of the pool is taken away except for 96 tokens."""
+    s = make(b=4, nb=3000, s_pf=250, t_pf=0.1, t_max=0.1)
+    s.add_request(2, 5000, 1, 0.1, 0.1, 0.0)     # SLO == T_pf: S_b == S_pf
     got = []
     for it in range(3):
         if it == 2:
-            del s.free[: len(s.free) - 128 // 4]
+            del s.free[: len(s.free) - 96 // 4]
         batch = s.next_batch(0.1 * it)
         got.append([(e.req.id, e.tokens) for e in batch])
         s.complete(0.1 * (it + 1))
-    assert got == [[(2, 300)], [(2, 300)], [(2, 128)]] and len(s.free) == 0
+    assert got == [[(2, 250)], [(2, 250)], [(2, 96)]] and len(s.free) == 0
     assert s.next_batch(0.3) == []               # nothing fits any more
 
 
@@ -113,6 +115,71 @@ def test_queue_order_and_urgency():
     assert s.token_budget == 96                  # 64 * 0.1875 / 0.125, the head's SLO
 
 
+def test_token_budget_takes_the_tightest_slo_of_the_certain_members():
+    """Eq. 6 uses SLO_min, "the minimum SLO of the requests in a batch" (Sec. 4.2).  The queue is
+    ordered by remaining time, so its head can be a prompt with a loose SLO that has waited long
+    while a generation task with a much tighter SLO is back from the last iteration: the budget
+    must follow the task's 0.05 s, not the head's 1.0 s."""
+    s = make(s_pf=768, t_pf=0.1, t_max=0.01, gamma=0.75, max_tokens=100000)
+    s.add_request(1, 5000, 4, 1.0, 1.0, 0.0)                  # waits 0.91 s: T_r = 1.0 - 0.91 - 7 * 0.01 = 0.02
+    t = SO.Request(2, 10, 50, 1.0, 0.05, 0.0, processed=10, generated=1, state=SO.RETURNED, blocks=[s.free.pop()])
+    s.reqs[2] = t                                             # T_r = 0.05 - 0.01 = 0.04
+    batch = s.next_batch(0.91)
+    assert s.t_max < s.reqs[1].t_r < t.t_r                    # the prompt is the head and not urgent
+    assert s.token_budget == math.floor(768 * 0.05 / 0.1) == 384
+    assert [(e.req.id, e.tokens) for e in batch] == [(2, 1), (1, 383)]
+
+
+def _generation_task(s, rid, slo_token, context, state=SO.RETURNED, t_enter=0.0):
+    """A generation task whose cached context is `context` tokens, holding exactly the blocks for it."""
+    nblk = -(-context // s.b)
+    r = SO.Request(rid, context, 100, 9.0, slo_token, t_enter, processed=context, generated=1, state=state,
+                   blocks=[s.free.pop() for _ in range(nblk)])
+    s.reqs[rid] = r
+    return r
+
+
+def test_algorithm1_preempts_the_largest_remaining_time_when_blocks_run_out():
+    """Alg. 1, lines 2-4 (Sec. 4.4): while a resource is over-committed the request of the batch
+    with the largest T_r gives way.  Hand-built: block size 16, a pool of 8 blocks; three generation
+    tasks back from the last iteration, each with a full last block (context 32: the next token
+    needs a new block), T_r = slo_token - T_max = 0.2, 0.4, 0.3 for ids 10, 11, 12; an urgent prompt
+    of 16 tokens arrives (T_r = 0.15 - 0.1 = 0.05 <= T_max).  Held 6 blocks, free 2, demand 3 + 1:
+    over-committed.  The victim must be id 11 (T_r 0.4); giving its two blocks back makes 4 free for
+    a demand of 3, so nobody else goes.  A smallest-T_r rule would drop the urgent prompt (id 20), a
+    first-come rule id 10: both leave a different batch."""
+    s = make(b=16, nb=8, s_pf=64, t_pf=0.1, t_max=0.1, gamma=0.0, max_tokens=64)
+    for rid, slo in ((10, 0.3), (11, 0.5), (12, 0.4)):
+        _generation_task(s, rid, slo, 32)
+    s.add_request(20, 16, 2, 0.15, 0.3, 0.0)
+    assert len(s.free) == 2
+    batch = s.next_batch(0.0)
+    assert [round(s.reqs[i].t_r, 12) for i in (10, 11, 12, 20)] == [0.2, 0.4, 0.3, 0.05]
+    assert s.preempted_now == [11]
+    assert sorted(e.req.id for e in batch) == [10, 12, 20]
+    # the victim was preempted for KVC: its blocks are back and it re-enters as a prompt over all its tokens
+    v = s.reqs[11]
+    assert v.blocks == [] and v.state == SO.WAITING and v.prompt_len == 33 and v.processed == 0
+    assert len(s.free) == 4 - 3       # 2 free + 2 returned - 3 handed out
+
+
+def test_algorithm1_preempts_the_largest_remaining_time_when_tokens_run_out():
+    """The same rule with the token budget over-committed (all numbers exact in binary): T_pf 0.125,
+    T_max 0.0625, S_pf 6; three returned generation tasks with SLOs 0.0625, 0.3125, 0.1875 (T_r 0,
+    0.25, 0.125 for ids 1, 2, 3) and a fourth that was set aside earlier and has become urgent (id 4:
+    SLO 0.125, waited 0.125 s, T_r = -0.0625).  S_b = floor(6 * 0.0625 / 0.125) = 3 tokens for four
+    tasks: id 2 gives way.  It keeps its blocks (the KVC is not short)."""
+    s = make(b=16, nb=64, s_pf=6, t_pf=0.125, t_max=0.0625, gamma=0.0, max_tokens=64)
+    for rid, slo in ((1, 0.0625), (2, 0.3125), (3, 0.1875)):
+        _generation_task(s, rid, slo, 20)
+    _generation_task(s, 4, 0.125, 20, state=SO.PREEMPTED, t_enter=0.875)
+    batch = s.next_batch(1.0)
+    assert [s.reqs[i].t_r for i in (1, 2, 3, 4)] == [0.0, 0.25, 0.125, -0.0625]
+    assert s.token_budget == 3
+    assert s.preempted_now == [2] and sorted(e.req.id for e in batch) == [1, 3, 4]
+    assert s.reqs[2].state == SO.PREEMPTED and len(s.reqs[2].blocks) == 2
+
+
 def brute_force_pick(a_c, a_m, b, demands):
     best, arg = None, None
     for i, (d_c, d_m) in enumerate(demands):
@@ -141,6 +208,58 @@ def test_select_requests_takes_the_nearest_demand_first(seed):
     first = brute_force_pick(a_c, a_m, b, demands)
     assert batch[0].req.id == first
     assert sum(e.tokens for e in batch) <= 512
+
+
+def brute_force_selection(a_c, a_m, b, cands):
+    """Alg. 2 lines 7-12 written out on plain numbers: cands = [(id, tokens left, is_long)]; every
+    round re-derives each remaining candidate's chunk (all its tokens, or what the tokens / the
+    KVC left allow), its KVC demand in tokens (whole blocks), and takes the smallest real Euclidean
+    distance to (A_c, A_m); only one long prompt may be under way."""
+    picked, left, long_taken = [], list(cands), False
+    while True:
+        best = None
+        for rid, n, is_long in left:
+            if is_long and long_taken:
+                continue
+            d_c = min(n, a_c, a_m)
+            if d_c < 1:
+                continue
+            d_m = -(-d_c // b) * b
+            if d_m > a_m:
+                continue
+            d = math.hypot(a_c - d_c, a_m - d_m)
+            if best is None or d < best[0] - 1e-9:
+                best = (d, rid, n, is_long, d_c, d_m)
+        if best is None:
+            return picked
+        _, rid, n, is_long, d_c, d_m = best
+        picked.append((rid, d_c))
+        left = [c for c in left if c[0] != rid]
+        long_taken = long_taken or is_long
+        a_c, a_m = a_c - d_c, a_m - d_m
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_select_requests_whole_sequence_inside_the_gamma_window(seed):
+    """Alg. 2 from its first line to its last: only requests whose T_r lies within gamma of the
+    first one are candidates (0 < gamma < the spread of the queue, so the window cuts it), and
+    the whole order of picks and chunk lengths equals the brute-force selection."""
+    rng = np.random.default_rng(100 + seed)
+    b, nb, s_pf = 16, int(rng.integers(12, 60)), 512     # free blocks: sometimes the KVC binds, sometimes the budget
+    s = make(b=b, nb=64, s_pf=s_pf, t_pf=0.1, t_max=0.1, gamma=1.0, max_tokens=512)
+    del s.free[: 64 - nb]
+    lens = rng.integers(1, 700, size=10)
+    slos = 5.0 + 0.3 * np.arange(10) + 0.1 * (lens > s_pf) * np.ceil(lens / s_pf - 1)   # T_r = 4.9 + 0.3 i exactly enough apart
+    for i, n in enumerate(lens):
+        s.add_request(i, int(n), 2, float(slos[i]), 5.0, 0.0)
+    batch = s.next_batch(0.0)
+    t_r = [s.reqs[i].t_r for i in range(10)]
+    window = [i for i in range(10) if t_r[i] <= min(t_r) + 1.0]
+    assert 1 < len(window) < 10                       # the window really cuts the queue
+    cands = [(i, int(lens[i]), bool(lens[i] > s_pf)) for i in sorted(window, key=lambda i: (t_r[i], i))]
+    want = brute_force_selection(512, nb * b, b, cands)
+    assert [(e.req.id, e.tokens) for e in batch] == want
+    assert all(e.req.id in window for e in batch)
 
 
 def simulate(s, trace, n_iter, iter_time, on_batch=None):
