@@ -87,6 +87,14 @@ enum {
     MPA_OPT_PROFILE_EVERY = 7,   /* with mpa_profile_enable: time every k-th attention call only
                                     (default 1); a pair of timing events costs the queue about
                                     ten microseconds per call                                 */
+    MPA_OPT_STAGING_TIMEOUT_MS = 8, /* how long a call waits for the upload kernel that last used a
+                                    staging buffer to report that it has read it (default 5000;
+                                    normally it has, long before the ring of buffers comes round).
+                                    After that the call fails with MPA_ERR_HIP (hipErrorNotReady)
+                                    before it writes to the buffer or launches anything          */
+    MPA_OPT_TEST_STUCK_UPLOAD = 9, /* value 1, for tests of that error path: the staging buffer the
+                                    next call would use is marked as still being read by an upload
+                                    that never reports back (no GPU involved)                    */
     MPA_OPT_PLAN_CACHE = 6       /* 1 (default) = a call whose chunk_starts / context_lens equal
                                     the previous call's reuses its work list (the layers of one
                                     model iteration all present the same batch); 0 = plan anew
@@ -96,7 +104,10 @@ enum {
                                     not to write to the workspace between such calls          */
 };
 
-/* Create a context for one cache geometry.  Validates cfg; makes no HIP call.
+/* Create a context for one cache geometry: the head layout of the attention layer (Sec. 2.1: the
+ * attention operations run per head; Sec. 6.1 for layers whose query heads share K/V heads), the
+ * block size of the block-based KVC (Sec. 2.2) and the 16-bit element type (Sec. 6.1).  Validates
+ * cfg; makes no HIP call.
  * Errors: INVALID_ARG (null), UNSUPPORTED (shape or dtype not built). */
 int mpa_create(mpa_ctx **out, const mpa_config *cfg);
 
@@ -110,7 +121,10 @@ int mpa_last_hip_error(const mpa_ctx *ctx);
 
 const char *mpa_status_string(int status);
 
-/* Bytes of device workspace mpa_mixed_paged_attention needs for this very batch
+/* The attention call cuts long contexts into key ranges that run in parallel and merges their
+ * partial results (an exact re-association of the softmax sums of Sec. 2.1); the partial results and
+ * the work list live in a caller-provided device workspace.
+ * Bytes of device workspace mpa_mixed_paged_attention needs for this very batch
  * (chunk_starts [num_seqs+1] and context_lens [num_seqs] are host pointers, as below).
  * Returns 0 on a malformed batch. */
 size_t mpa_workspace_bytes_for_batch(const mpa_ctx *ctx, const int32_t *chunk_starts,
@@ -155,7 +169,11 @@ int mpa_copy_blocks(mpa_ctx *ctx, const void *src_k, const void *src_v, void *ds
                     const int64_t *pairs, int32_t num_pairs, void *stream);
 
 /*
- * Attention of every query row of a mixed batch over its sequence's cached K/V.
+ * Attention of every query row of a mixed batch over its sequence's cached K/V: the self-attention
+ * equation of Sec. 2.1, softmax(Q K^T / sqrt(d_k)) V per head, for a batch that holds prompt chunks
+ * (Sec. 2.3 chunking; Sec. 4.2: a chunk is whatever run of a prompt's tokens the token budget and
+ * the KVC admitted, so it starts and ends anywhere) next to generation tasks, which contribute one
+ * token per iteration once their prompt is done (Sec. 2.3), over the block-based KVC of Sec. 2.2.
  *
  * Sequence i owns rows chunk_starts[i] .. chunk_starts[i+1]-1 of q/out (q_len_i of them; the
  * row boundaries of the ragged batch).  context_lens[i] is the sequence's KV length including

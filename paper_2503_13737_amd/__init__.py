@@ -29,6 +29,8 @@ MPA_OPT_PP_RESIDENT_WGS = 4
 MPA_OPT_PP_TEAM_MIN_STEPS = 5
 MPA_OPT_PLAN_CACHE = 6
 MPA_OPT_PROFILE_EVERY = 7
+MPA_OPT_STAGING_TIMEOUT_MS = 8
+MPA_OPT_TEST_STUCK_UPLOAD = 9
 
 EXPORTS = [
     "mpa_create", "mpa_destroy", "mpa_set_option", "mpa_last_hip_error", "mpa_status_string",

@@ -3,6 +3,7 @@
 
 #include <cmath>
 #include <chrono>
+#include <cstdlib>
 #include <cstring>
 #include <thread>
 #include <mutex>
@@ -30,19 +31,28 @@ struct Staging {
 
     volatile uint64_t *flag() const { return static_cast<volatile uint64_t *>(host); }
     char *data() const { return static_cast<char *>(host) + kStagingHeader; }
-    // The upload kernels of a slot finish long before the ring comes round; if one does not show
-    // up for seconds (a failed launch), the device is drained rather than the host left spinning.
-    void wait() {
-        if (!in_flight || !host) return;
+    bool pinned = true;    // false: ordinary host memory (the stuck slot that a test plants; no GPU reads it)
+
+    // The upload kernel of a slot finishes long before the ring comes round.  Returns true once
+    // the slot's ticket has shown up (or nothing was in flight); false when it has not after
+    // `timeout_ms` -- a launch that failed after it was queued, or a device that has stopped.  The
+    // slot then stays marked as in flight: its memory may still be read and is not touched.
+    bool wait(int64_t timeout_ms) {
+        if (!in_flight || !host) return true;
         const auto t0 = std::chrono::steady_clock::now();
         while (*flag() < ticket) {
+            if (std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(timeout_ms)) return false;
             std::this_thread::yield();
-            if (std::chrono::steady_clock::now() - t0 > std::chrono::seconds(5)) {
-                (void)hipDeviceSynchronize();
-                break;
-            }
         }
         in_flight = false;
+        return true;
+    }
+    void release() {
+        if (!host) return;
+        if (pinned) (void)hipHostFree(host);
+        else std::free(host);
+        host = nullptr;
+        bytes = 0;
     }
 };
 }  // namespace
@@ -54,6 +64,7 @@ struct mpa_ctx {
     Staging staging[kStagingSlots];
     int next_slot = 0;
     uint64_t next_ticket = 1;
+    int64_t staging_timeout_ms = 5000;   // MPA_OPT_STAGING_TIMEOUT_MS
     Plan plan;  // the plan of the last batch; reused as it is when the next batch is the same
                 // (all layers of one model iteration present the same batch)
     std::vector<int32_t> plan_key;   // chunk_starts then context_lens of that batch
@@ -113,8 +124,8 @@ int mpa_destroy(mpa_ctx *ctx)
 {
     if (!ctx) return MPA_OK;
     for (auto &s : ctx->staging) {
-        s.wait();
-        if (s.host) (void)hipHostFree(s.host);
+        // a slot whose upload never reported back may still be read by the GPU: it is left allocated
+        if (s.wait(ctx->staging_timeout_ms) || !s.pinned) s.release();
     }
     for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
     delete ctx;
@@ -185,6 +196,26 @@ int mpa_set_option(mpa_ctx *ctx, int32_t option, int64_t value)
         if (value < 0) return MPA_ERR_INVALID_ARG;
         ctx->opt.pp_team_min_steps = value;
         return MPA_OK;
+    case MPA_OPT_STAGING_TIMEOUT_MS:
+        if (value < 1 || value > 600000) return MPA_ERR_INVALID_ARG;
+        ctx->staging_timeout_ms = value;
+        return MPA_OK;
+    case MPA_OPT_TEST_STUCK_UPLOAD: {
+        // The slot the next upload would use is made to look like one whose upload kernel never
+        // reported back (ordinary host memory, a ticket that no kernel will write): the error
+        // path of the staging ring can then be driven from the host, without a GPU.
+        if (value != 1) return MPA_ERR_INVALID_ARG;
+        Staging &st = ctx->staging[ctx->next_slot];
+        if (st.in_flight) return MPA_ERR_INVALID_ARG;
+        st.release();
+        st.host = std::calloc(1, kStagingHeader + 4096);
+        if (!st.host) return MPA_ERR_INVALID_ARG;
+        st.pinned = false;
+        st.bytes = 4096;
+        st.ticket = ctx->next_ticket++;
+        st.in_flight = true;
+        return MPA_OK;
+    }
     default: return MPA_ERR_INVALID_ARG;
     }
 }
@@ -339,12 +370,18 @@ int attend(mpa_ctx *ctx, const AppendArgs *app, const void *q, const void *k_cac
         // stage the work list in pinned memory; a small kernel carries it into the workspace on the stream
         const size_t list_bytes = plan.off_acc;  // items, merge rows, teams, progress words; padded
         Staging &st = ctx->staging[ctx->next_slot];
+        if (!st.wait(ctx->staging_timeout_ms)) {
+            // The upload that last used this slot never reported back.  Nothing is written to the
+            // slot and nothing is launched; the work list this context believes to be on the
+            // device is not trusted any more.  The ring does not advance: the next call finds the
+            // same slot and succeeds once its ticket has arrived.
+            ctx->plan_valid = false;
+            return fail(hipErrorNotReady);
+        }
         ctx->next_slot = (ctx->next_slot + 1) % kStagingSlots;
-        st.wait();
-        if (st.bytes < list_bytes) {
-            if (st.host) (void)hipHostFree(st.host);
-            st.host = nullptr;
-            st.bytes = 0;
+        if (st.bytes < list_bytes || !st.pinned) {
+            st.release();
+            st.pinned = true;
             size_t want = list_bytes * 2;
             if ((e = hipHostMalloc(&st.host, kStagingHeader + want, hipHostMallocCoherent)) != hipSuccess)
                 return fail(e);

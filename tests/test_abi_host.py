@@ -3,6 +3,7 @@ declares, rejects bad arguments before touching the GPU, and plans batches consi
 import ctypes
 import os
 import re
+import time
 
 import numpy as np
 import pytest
@@ -170,3 +171,32 @@ def test_one_call_form_and_block_copy_reject_bad_arguments_without_gpu():
     assert lib.mpa_copy_blocks(None, fake, fake, fake, fake, fake, 1, None) == mpa.MPA_ERR_INVALID_ARG
     with pytest.raises(mpa.MpaError):
         c.set_option(mpa.MPA_OPT_PROFILE_EVERY, 0)
+
+
+def test_an_upload_that_never_reports_back_fails_the_call_before_anything_is_touched():
+    """The staging ring's error path, driven from the host: the buffer the next call would use is
+    marked as still being read by an upload whose ticket never arrives.  The call must wait the
+    configured time, then return MPA_ERR_HIP with hipErrorNotReady -- before it writes to the buffer
+    or launches anything (no HIP call at all has been made when it returns: this runs without a
+    GPU) -- and the next call must find the same buffer and fail the same way."""
+    HIP_ERROR_NOT_READY = 600
+    lib = mpa.load()
+    c = mpa.Context(4, 64)
+    c.set_option(mpa.MPA_OPT_STAGING_TIMEOUT_MS, 60)
+    c.set_option(mpa.MPA_OPT_TEST_STUCK_UPLOAD, 1)
+    with pytest.raises(mpa.MpaError):
+        c.set_option(mpa.MPA_OPT_TEST_STUCK_UPLOAD, 1)        # the slot is taken already
+    cs = np.array([0, 3, 4], dtype=np.int32)
+    cl = np.array([5, 9], dtype=np.int32)
+    fake = ctypes.c_void_p(0x1000)   # aligned, never dereferenced: the call fails before any launch
+    for attempt in range(2):
+        t0 = time.perf_counter()
+        rc = lib.mpa_mixed_paged_attention(c._h, fake, fake, fake, fake, 4, mpa._ptr(cs), mpa._ptr(cl), 2, 4, 0.0,
+                                           fake, fake, 1 << 20, None)
+        dt = time.perf_counter() - t0
+        assert rc == mpa.MPA_ERR_HIP and lib.mpa_last_hip_error(c._h) == HIP_ERROR_NOT_READY, attempt
+        assert 0.05 <= dt < 2.0
+    rc = lib.mpa_append_and_attend(c._h, fake, fake, fake, fake, fake, fake, fake, 4, mpa._ptr(cs), mpa._ptr(cl), 2, 4,
+                                   0.0, fake, fake, 1 << 20, None)
+    assert rc == mpa.MPA_ERR_HIP and lib.mpa_last_hip_error(c._h) == HIP_ERROR_NOT_READY
+    c.close()   # a planted slot is ordinary memory and is freed
