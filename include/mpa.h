@@ -224,6 +224,31 @@ int mpa_append_and_attend(mpa_ctx *ctx, const void *k_new, const void *v_new, co
                           size_t workspace_bytes, void *stream);
 
 /*
+ * mpa_mixed_paged_attention for callers that cannot allocate device memory or hand over a
+ * workspace: code running under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments without the workspace, same kernels, same results bit for bit.  The
+ * work list and the partial results of split key ranges live in a device array of
+ * MPA_STATIC_SCRATCH_BYTES that is part of the library (every GPU the library runs on holds its
+ * copy until the process ends); the work list reaches it as kernel arguments.  The call makes no
+ * hipMalloc / hipHostMalloc / hipFree and uses no pinned staging buffer.
+ *
+ *   - A batch whose work list and partial results need more than MPA_STATIC_SCRATCH_BYTES (what
+ *     mpa_workspace_bytes_for_batch returns) is refused with MPA_ERR_WORKSPACE before any HIP call;
+ *     use the workspace form for such batches.
+ *   - Every context and every call on a GPU shares that GPU's array: calls that may overlap on one
+ *     GPU (different streams, different threads) race.  Calls on one stream are ordered and safe;
+ *     nothing is assumed to be in the array from an earlier call.
+ *   - The device that is current at the call must be the one `stream` belongs to.
+ * Errors: INVALID_ARG, BAD_BATCH, WORKSPACE (batch too large for the array), HIP.
+ */
+#define MPA_STATIC_SCRATCH_BYTES ((size_t)64 << 20)
+int mpa_mixed_paged_attention_static(mpa_ctx *ctx, const void *q, const void *k_cache,
+                                     const void *v_cache, const int32_t *block_table,
+                                     int32_t block_table_stride, const int32_t *chunk_starts,
+                                     const int32_t *context_lens, int32_t num_seqs,
+                                     int32_t num_tokens, float scale, void *out, void *stream);
+
+/*
  * Kernel timing for benchmarks.  mpa_profile_enable(ctx, n) with n > 0 makes every following
  * mpa_mixed_paged_attention call record a pair of HIP events on its stream directly around the
  * launch of the main attention kernel (after the work-list copy, before the merge), for up to n

@@ -31,11 +31,12 @@ MPA_OPT_PLAN_CACHE = 6
 MPA_OPT_PROFILE_EVERY = 7
 MPA_OPT_STAGING_TIMEOUT_MS = 8
 MPA_OPT_TEST_STUCK_UPLOAD = 9
+MPA_STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = [
     "mpa_create", "mpa_destroy", "mpa_set_option", "mpa_last_hip_error", "mpa_status_string",
     "mpa_workspace_bytes_for_batch", "mpa_workspace_bytes", "mpa_kv_append", "mpa_copy_blocks", "mpa_append_and_attend",
-    "mpa_mixed_paged_attention", "mpa_plan_describe", "mpa_profile_enable", "mpa_profile_read",
+    "mpa_mixed_paged_attention", "mpa_mixed_paged_attention_static", "mpa_plan_describe", "mpa_profile_enable", "mpa_profile_read",
     "mpa_sched_create", "mpa_sched_destroy", "mpa_sched_add_request", "mpa_sched_add_offline_request", "mpa_sched_next_batch",
     "mpa_sched_batch_arrays", "mpa_sched_batch_swaps", "mpa_sched_complete", "mpa_sched_live_requests",
 ]
@@ -98,6 +99,9 @@ def load() -> ctypes.CDLL:
         lib.mpa_mixed_paged_attention.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, i32, i32,
                                                   ctypes.c_float, vp, vp, sz, vp]
         lib.mpa_mixed_paged_attention.restype = ctypes.c_int
+        lib.mpa_mixed_paged_attention_static.argtypes = [vp, vp, vp, vp, vp, i32, vp, vp, i32, i32,
+                                                         ctypes.c_float, vp, vp]
+        lib.mpa_mixed_paged_attention_static.restype = ctypes.c_int
         lib.mpa_append_and_attend.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, i32, vp, vp, i32, i32,
                                               ctypes.c_float, vp, vp, sz, vp]
         lib.mpa_append_and_attend.restype = ctypes.c_int
@@ -239,6 +243,17 @@ class Context:
             cl.size, int(q.shape[0]), float(scale), _ptr(out), _ptr(workspace), wsb, _stream_ptr(stream))
         if rc != MPA_OK:
             raise MpaError(rc, "mpa_mixed_paged_attention")
+
+    def mixed_paged_attention_static(self, q, k_cache, v_cache, block_table, chunk_starts, context_lens, out,
+                                     scale: float = 0.0, stream=None, block_table_stride=None):
+        """The form that allocates nothing and takes no workspace (the library's own device array)."""
+        cs, cl = _host_i32(chunk_starts), _host_i32(context_lens)
+        stride = int(block_table.shape[1]) if block_table_stride is None else int(block_table_stride)
+        rc = load().mpa_mixed_paged_attention_static(
+            self._h, _ptr(q), _ptr(k_cache), _ptr(v_cache), _ptr(block_table), stride, _ptr(cs), _ptr(cl),
+            cl.size, int(q.shape[0]), float(scale), _ptr(out), _stream_ptr(stream))
+        if rc != MPA_OK:
+            raise MpaError(rc, "mpa_mixed_paged_attention_static")
 
     def append_and_attend(self, k_new, v_new, slot_map, q, k_cache, v_cache, block_table, chunk_starts, context_lens,
                           out, workspace, scale: float = 0.0, stream=None, block_table_stride=None,

@@ -68,6 +68,7 @@ struct mpa_ctx {
     Plan plan;  // the plan of the last batch; reused as it is when the next batch is the same
                 // (all layers of one model iteration present the same batch)
     std::vector<int32_t> plan_key;   // chunk_starts then context_lens of that batch
+    std::vector<char> list_host;     // the work list as the entry point that allocates nothing sends it
     bool plan_valid = false;         // cleared by mpa_set_option
     bool plan_cache = true;
     bool keep_upload = false;            // MPA_OPT_PLAN_CACHE == 2
@@ -311,7 +312,7 @@ struct AppendArgs {
 int attend(mpa_ctx *ctx, const AppendArgs *app, const void *q, const void *k_cache, const void *v_cache,
            const int32_t *block_table, int32_t block_table_stride, const int32_t *chunk_starts,
            const int32_t *context_lens, int32_t num_seqs, int32_t num_tokens, float scale, void *out,
-           void *workspace, size_t workspace_bytes, void *stream)
+           void *workspace, size_t workspace_bytes, bool static_ws, void *stream)
 {
     if (!ctx || num_seqs < 0 || num_tokens < 0) return MPA_ERR_INVALID_ARG;
     if (num_seqs == 0) return num_tokens == 0 ? MPA_OK : MPA_ERR_BAD_BATCH;
@@ -345,20 +346,31 @@ int attend(mpa_ctx *ctx, const AppendArgs *app, const void *q, const void *k_cac
     for (int32_t i = 0; i < num_seqs; ++i)
         if (((int64_t)context_lens[i] + ctx->cfg.block_size - 1) / ctx->cfg.block_size > block_table_stride)
             return MPA_ERR_BAD_BATCH;
-    if (!workspace || !aligned(workspace, 256) || workspace_bytes < plan.total_bytes)
+    static_assert(kStaticScratchBytes == MPA_STATIC_SCRATCH_BYTES, "the header states the limit");
+    if (static_ws) {
+        if (plan.total_bytes > kStaticScratchBytes) return MPA_ERR_WORKSPACE;   // before any HIP call
+    } else if (!workspace || !aligned(workspace, 256) || workspace_bytes < plan.total_bytes) {
         return MPA_ERR_WORKSPACE;
+    }
 
     auto fail = [&](hipError_t e) {
         ctx->last_hip = (int)e;
         ctx->uploaded_valid = false;
         return MPA_ERR_HIP;
     };
+    if (static_ws) {
+        // The library's own device array stands in for the workspace.  Every context and every
+        // call on this GPU shares it, so nothing is assumed to be in it from an earlier call.
+        const int se = static_scratch(&workspace);
+        if (se != 0) return fail((hipError_t)se);
+        ctx->uploaded_valid = false;
+    }
 
     // The work list of this very plan may still sit in this workspace from the previous call on
     // this stream (the kernels only read it, and every progress word is back at its start value
     // when a launch has finished): then nothing is copied.
-    const bool list_in_place = same && ctx->keep_upload && ctx->uploaded_valid && ctx->uploaded_ws == workspace &&
-                               ctx->uploaded_stream == stream;
+    const bool list_in_place = !static_ws && same && ctx->keep_upload && ctx->uploaded_valid &&
+                               ctx->uploaded_ws == workspace && ctx->uploaded_stream == stream;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
     if (list_in_place && app) {
@@ -366,7 +378,22 @@ int attend(mpa_ctx *ctx, const AppendArgs *app, const void *q, const void *k_cac
                                   ctx->cfg.head_dim, ctx->cfg.block_size, app->k_cache, app->v_cache, stream);
         if (ae != 0) return fail((hipError_t)ae);
     }
-    if (!list_in_place) {
+    auto write_list = [&](char *h) {
+        std::memcpy(h + plan.off_items, plan.items.data(), plan.items.size() * sizeof(WorkItem));
+        std::memcpy(h + plan.off_merge, plan.merge.data(), plan.merge.size() * sizeof(MergeRow));
+        std::memcpy(h + plan.off_teams, plan.teams.data(), plan.teams.size() * sizeof(TeamRef));
+        std::memset(h + plan.off_progress, 0xFF, (size_t)plan.progress_words * sizeof(uint32_t));  // kNotRunning
+    };
+    if (static_ws) {
+        // No staging memory: the list is put together in ordinary host memory and handed to the
+        // device as kernel arguments.
+        const size_t list_bytes = plan.off_acc;
+        if (list_bytes % 16 != 0) return MPA_ERR_WORKSPACE;
+        ctx->list_host.assign(list_bytes, 0);
+        write_list(ctx->list_host.data());
+        const int le = launch_list_chunks(ctx->list_host.data(), workspace, list_bytes, stream);
+        if (le != 0) return fail((hipError_t)le);
+    } else if (!list_in_place) {
         // stage the work list in pinned memory; a small kernel carries it into the workspace on the stream
         const size_t list_bytes = plan.off_acc;  // items, merge rows, teams, progress words; padded
         Staging &st = ctx->staging[ctx->next_slot];
@@ -389,10 +416,7 @@ int attend(mpa_ctx *ctx, const AppendArgs *app, const void *q, const void *k_cac
             *st.flag() = 0;
         }
         char *h = st.data();
-        std::memcpy(h + plan.off_items, plan.items.data(), plan.items.size() * sizeof(WorkItem));
-        std::memcpy(h + plan.off_merge, plan.merge.data(), plan.merge.size() * sizeof(MergeRow));
-        std::memcpy(h + plan.off_teams, plan.teams.data(), plan.teams.size() * sizeof(TeamRef));
-        std::memset(h + plan.off_progress, 0xFF, (size_t)plan.progress_words * sizeof(uint32_t));  // kNotRunning
+        write_list(h);
         if (list_bytes % 16 != 0) return MPA_ERR_WORKSPACE;   // the plan pads its sections
         st.ticket = ctx->next_ticket++;
         const int ue = app ? launch_append_upload(app->k_new, app->v_new, app->slot_map, num_tokens, ctx->cfg.num_kv_heads,
@@ -456,7 +480,16 @@ int mpa_mixed_paged_attention(mpa_ctx *ctx, const void *q, const void *k_cache, 
                               void *workspace, size_t workspace_bytes, void *stream)
 {
     return attend(ctx, nullptr, q, k_cache, v_cache, block_table, block_table_stride, chunk_starts, context_lens,
-                  num_seqs, num_tokens, scale, out, workspace, workspace_bytes, stream);
+                  num_seqs, num_tokens, scale, out, workspace, workspace_bytes, false, stream);
+}
+
+int mpa_mixed_paged_attention_static(mpa_ctx *ctx, const void *q, const void *k_cache, const void *v_cache,
+                                     const int32_t *block_table, int32_t block_table_stride,
+                                     const int32_t *chunk_starts, const int32_t *context_lens,
+                                     int32_t num_seqs, int32_t num_tokens, float scale, void *out, void *stream)
+{
+    return attend(ctx, nullptr, q, k_cache, v_cache, block_table, block_table_stride, chunk_starts, context_lens,
+                  num_seqs, num_tokens, scale, out, nullptr, 0, true, stream);
 }
 
 int mpa_append_and_attend(mpa_ctx *ctx, const void *k_new, const void *v_new, const int64_t *slot_map,
@@ -467,7 +500,7 @@ int mpa_append_and_attend(mpa_ctx *ctx, const void *k_new, const void *v_new, co
 {
     const AppendArgs app = {k_new, v_new, slot_map, k_cache, v_cache};
     return attend(ctx, &app, q, k_cache, v_cache, block_table, block_table_stride, chunk_starts, context_lens,
-                  num_seqs, num_tokens, scale, out, workspace, workspace_bytes, stream);
+                  num_seqs, num_tokens, scale, out, workspace, workspace_bytes, false, stream);
 }
 
 }  // extern "C"

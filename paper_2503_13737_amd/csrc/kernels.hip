@@ -3,6 +3,8 @@
 // (row-streaming body for generation rows, matrix-core body for prompt tiles and for grouped
 // generation rows) and the merge of split partial results.  Every kernel that touches K/V
 // elements exists for both 16-bit storage types.
+#include <cstring>
+#include <mutex>
 #include <type_traits>
 #include <hip/hip_runtime.h>
 
@@ -1101,7 +1103,67 @@ merge_kernel(const AttnParams p)
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Scratch memory of the entry point that allocates nothing (mpa_mixed_paged_attention_static):
+// what the other entry points take as the caller's workspace -- the work list and the partial
+// results of split key ranges -- lives in this array instead.  Every GPU the library runs on holds
+// its own copy, at its own address, until the process ends.  In host code the array's name is only
+// a handle for hipGetSymbolAddress: kernels get the address that call returns.
+// ------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+// The work list reaches the scratch array as kernel arguments, kListChunkBytes at a time: no
+// staging memory on either side, nothing for the host to keep alive after the launch call.
+struct ListChunk {
+    u32x4 v[kListChunkBytes / 16];
+};
+static_assert(sizeof(ListChunk) + 16 <= 4096, "kernel arguments are limited to 4 KiB");
+
+__global__ void __launch_bounds__(256)
+list_chunk_kernel(const ListChunk chunk, u32x4 *__restrict__ dst, int32_t n)
+{
+    if ((int32_t)threadIdx.x < n) dst[threadIdx.x] = chunk.v[threadIdx.x];
+}
+static_assert(kListChunkBytes / 16 <= 256, "one thread per 16 bytes");
+
 }  // namespace
+
+int static_scratch(void **ptr)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void *ptrs[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> g(mu);
+    if (!ptrs[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));   // the current device's copy of the array
+        if (e != hipSuccess) return (int)e;
+        if (!p) return (int)hipErrorInvalidSymbol;
+        ptrs[dev] = p;
+    }
+    *ptr = ptrs[dev];
+    return 0;
+}
+
+int launch_list_chunks(const void *host_src, void *dst, size_t bytes, void *stream)
+{
+    const char *src = static_cast<const char *>(host_src);
+    char *d = static_cast<char *>(dst);
+    for (size_t off = 0; off < bytes; off += kListChunkBytes) {
+        const size_t n = bytes - off < (size_t)kListChunkBytes ? bytes - off : (size_t)kListChunkBytes;   // a multiple of 16
+        ListChunk c;
+        std::memcpy(c.v, src + off, n);
+        hipLaunchKernelGGL(list_chunk_kernel, dim3(1), dim3(256), 0, (hipStream_t)stream, c,
+                           reinterpret_cast<u32x4 *>(d + off), (int32_t)(n / 16));
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return (int)e;
+    }
+    return 0;
+}
 
 int launch_kv_append(const void *k_new, const void *v_new, const int64_t *slot_map, int32_t T,
                      int32_t H, int32_t D, int32_t block_size, void *k_cache, void *v_cache, void *stream)

@@ -122,6 +122,15 @@ struct AttnParams {
     uint32_t *progress;
 };
 
+// The entry point that allocates nothing keeps work list and partial results in a device array of
+// this size that is part of the library; the list travels there as kernel arguments.
+constexpr size_t kStaticScratchBytes = (size_t)64 << 20;
+constexpr int kListChunkBytes = 3584;
+// Device address of that array on the current device (looked up once per device).
+int static_scratch(void **ptr);
+// bytes: a multiple of 16; host_src is read before the call returns
+int launch_list_chunks(const void *host_src, void *dst, size_t bytes, void *stream);
+
 // Kernel launchers (kernels.hip).  Return the raw hipError_t as int.
 int launch_kv_append(const void *k_new, const void *v_new, const int64_t *slot_map, int32_t T,
                      int32_t H, int32_t D, int32_t block_size, void *k_cache, void *v_cache, void *stream);
