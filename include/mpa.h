@@ -87,6 +87,13 @@ enum {
     MPA_OPT_PROFILE_EVERY = 7,   /* with mpa_profile_enable: time every k-th attention call only
                                     (default 1); a pair of timing events costs the queue about
                                     ten microseconds per call                                 */
+    MPA_OPT_TILE_MODE = 10,      /* work-group shape of the attention launch: 0 or 1 (default) = four
+                                    wavefronts, 128-row prompt tiles, two work-groups per compute
+                                    unit; 2 = eight wavefronts, 256-row prompt tiles over a ring of
+                                    five K/V tiles, one work-group per compute unit (prompt tiles and
+                                    generation rows then run on separate compute units).  Same
+                                    results; measured within 2 % of the default on prompts alone and
+                                    slower on mixed batches, so it is never chosen automatically   */
     MPA_OPT_STAGING_TIMEOUT_MS = 8, /* how long a call waits for the upload kernel that last used a
                                     staging buffer to report that it has read it (default 5000;
                                     normally it has, long before the ring of buffers comes round).

@@ -31,6 +31,7 @@ MPA_OPT_PLAN_CACHE = 6
 MPA_OPT_PROFILE_EVERY = 7
 MPA_OPT_STAGING_TIMEOUT_MS = 8
 MPA_OPT_TEST_STUCK_UPLOAD = 9
+MPA_OPT_TILE_MODE = 10
 MPA_STATIC_SCRATCH_BYTES = 64 << 20
 
 EXPORTS = [

@@ -197,6 +197,10 @@ int mpa_set_option(mpa_ctx *ctx, int32_t option, int64_t value)
         if (value < 0) return MPA_ERR_INVALID_ARG;
         ctx->opt.pp_team_min_steps = value;
         return MPA_OK;
+    case MPA_OPT_TILE_MODE:
+        if (value > 2) return MPA_ERR_INVALID_ARG;
+        ctx->opt.tile_mode = value;
+        return MPA_OK;
     case MPA_OPT_STAGING_TIMEOUT_MS:
         if (value < 1 || value > 600000) return MPA_ERR_INVALID_ARG;
         ctx->staging_timeout_ms = value;
@@ -455,6 +459,7 @@ int attend(mpa_ctx *ctx, const AppendArgs *app, const void *q, const void *k_cac
     p.n_merge = (int32_t)plan.merge.size();
     p.teams = reinterpret_cast<const TeamRef *>(ws + plan.off_teams);
     p.progress = reinterpret_cast<uint32_t *>(ws + plan.off_progress);
+    p.wide = plan.wide ? 1 : 0;
 
     const bool prof = (size_t)(2 * ctx->prof_used + 1) < ctx->prof_events.size() &&
                       ctx->prof_calls++ % ctx->prof_every == 0;

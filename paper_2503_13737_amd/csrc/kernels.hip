@@ -234,7 +234,7 @@ copy_blocks_kernel(const u32x4 *__restrict__ src_k, const u32x4 *__restrict__ sr
 // tokens and accumulates p*v for its 8 elements, so the main loop has no traffic across
 // groups.  The groups are combined once at the end.
 // ------------------------------------------------------------------------------------------
-constexpr int kRowSets = 3;   // register sets of a row-streaming wavefront
+constexpr int kRowSets = 3;   // register sets of a row-streaming wavefront (more were measured: no gain, narrow or wide)
 
 template <int D>
 struct RowCfg {
@@ -426,7 +426,7 @@ __device__ __forceinline__ void row_body(const AttnParams &p, const WorkItem &it
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
-template <int D>
+template <int D, int WAVES = kWaves>
 struct TileCfg {
     static constexpr int KS = D / 16;                   // k-steps of K Q^T
     static constexpr int DB = D / 32;                   // 32-row blocks of O^T
@@ -444,7 +444,9 @@ struct TileCfg {
     static constexpr int V_BYTES = TILE_BYTES;
     static constexpr int CPR = D / 8;                   // 16-byte chunks per key row
     static constexpr int RPL = 64 / CPR;                // key rows covered by one wavefront-wide load
-    static constexpr int NL = kPage / RPL;              // loads per wavefront per operand and page
+    static constexpr int KPW = kKvTile / WAVES;         // key rows of a step that one wavefront loads
+    static constexpr int NL = KPW / RPL;                // loads per wavefront per operand and step
+    static_assert(NL >= 1 && KPW <= kPage, "a wavefront loads whole rows of one page");
     static constexpr int VSW = CPR / 4;                 // 4 for D = 128, 2 for D = 64
 };
 
@@ -452,11 +454,11 @@ struct TileCfg {
 // tile_compute.  Only gk/gv change from step to step, and they are wavefront-uniform, so the
 // loads address memory as scalar base + per-lane 32-bit offset and the loop spends no vector
 // arithmetic on them.
-template <int D>
+template <int D, int WAVES = kWaves>
 struct TileNext {
-    const char *gk, *gv;                  // the wavefront's KV block (16 keys) in the K and V caches
-    uint32_t koff[TileCfg<D>::NL];        // this lane's byte offset inside the block for load i (K swizzle)
-    uint32_t voff[TileCfg<D>::NL];        // same with the V swizzle
+    const char *gk, *gv;                  // the page (16 keys) that holds the wavefront's rows, in the K and V caches
+    uint32_t koff[TileCfg<D, WAVES>::NL]; // this lane's byte offset inside the page for load i (K swizzle)
+    uint32_t voff[TileCfg<D, WAVES>::NL]; // same with the V swizzle
     uint32_t lds_w;                       // LDS address of the wavefront's 16 rows in the K tile of buffer 0
     bool stream;                          // K/V of this item are read once (see load_to_lds_16)
 };
@@ -494,16 +496,16 @@ __device__ __forceinline__ void wait_loads_to_lds() { asm volatile("s_waitcnt vm
 // rows at or past it (all rows if !have_block) are not loaded; the V rows among them are zeroed
 // instead (their scores are masked, but 0 * NaN would poison the PV product), the K rows may hold
 // anything.  Nothing is waited for here.
-template <int D>
-__device__ __forceinline__ void tile_load(const TileNext<D> &n, int bufi, bool have_block, int32_t keys_valid,
+template <int D, int WAVES = kWaves>
+__device__ __forceinline__ void tile_load(const TileNext<D, WAVES> &n, uint32_t buf_off, bool have_block, int32_t keys_valid,
                                           int wave, int lane)
 {
-    using C = TileCfg<D>;
+    using C = TileCfg<D, WAVES>;
     typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
 #pragma unroll
     for (int i = 0; i < C::NL; ++i) {
-        const int row = wave * kPage + i * C::RPL + lane / C::CPR;   // row inside the tile
-        const uint32_t dst = n.lds_w + bufi * (C::K_BYTES + C::V_BYTES) + i * C::RPL * C::ROW;
+        const int row = wave * C::KPW + i * C::RPL + lane / C::CPR;   // row inside the tile
+        const uint32_t dst = n.lds_w + buf_off + i * C::RPL * C::ROW;
         if (have_block && row < keys_valid) {
             load_to_lds_16(n.gk, n.koff[i], dst, n.stream);
             load_to_lds_16(n.gv, n.voff[i], dst + C::K_BYTES, n.stream);
@@ -613,14 +615,14 @@ __device__ __forceinline__ void k_wait(u32x4 &f)
 // weights are computed against the current m, and only if a lane's partial row sum comes out
 // above 2^64 (or m is still unset) does the wavefront take the row maxima, raise m, rescale l
 // and O, and recompute the weights of that half.
-template <class E, int D, bool LOAD_NEXT, int BUFI>
+template <class E, int D, bool LOAD_NEXT, int BUFI, int WAVES = kWaves>
 __device__ __forceinline__ void tile_compute(const uint32_t (&kaddr)[TileCfg<D>::KS],
                                              const uint32_t (&vaddr)[TileCfg<D>::DB],
                                              const typename E::x8 (&qf)[TileCfg<D>::KS], f32x16 (&o)[TileCfg<D>::DB],
                                              float &m, float &l, float c2, int32_t k0, int32_t pos, int half,
-                                             bool masked, const TileNext<D> &next)
+                                             bool masked, const TileNext<D, WAVES> &next)
 {
-    using C = TileCfg<D>;
+    using C = TileCfg<D, WAVES>;
     typedef typename E::x2 ex2;
     typedef typename E::x8 ex8;
     constexpr int BUF = C::K_BYTES + C::V_BYTES;
@@ -782,11 +784,11 @@ __device__ __forceinline__ void progress_store(uint32_t *w, uint32_t v)
 // head of the group of a group item (its rows are the group's heads, all at the token q_row0):
 // row r of the item is row (q_row0 * H + head) + r * rstride of q / out seen as [T * H, D], and
 // likewise in the partial buffers.
-template <class E, int D>
+template <class E, int D, int WAVES>
 __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &it, const TeamRef &team, int head,
                                           char *lds)
 {
-    using C = TileCfg<D>;
+    using C = TileCfg<D, WAVES>;
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int half = lane >> 5;
@@ -826,12 +828,13 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
     const int32_t npages_item = (it.kv_end - it.kv_begin + kPage - 1) / kPage;
     const int32_t page0 = it.kv_begin / kPage;
     auto load_entries = [&](int32_t step0) {   // page word of this wavefront's page in step step0 + lane
-        const int32_t b = (step0 + lane) * kWaves + wave;
+        const int32_t b = (step0 + lane) * (kKvTile / kPage) + wave * C::KPW / kPage;
         return (b < npages_item) ? page_word(tab, page0 + b, p.page_shift) : -1;
     };
     int32_t entries = load_entries(0);
 
-    uint32_t *const pace = team.base >= 0 ? p.progress + team.base + (size_t)head * team.stride : nullptr;
+    // (pacing exists for work-groups of four wavefronts only)
+    uint32_t *const pace = (WAVES == kWaves && team.base >= 0) ? p.progress + team.base + (size_t)head * team.stride : nullptr;
     if (pace && threadIdx.x == 0) progress_store(pace + team.member, 0u);
 
     auto step_block = [&](int32_t step) {
@@ -854,16 +857,16 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
         for (int db = 0; db < C::DB; ++db)
             vaddr[db] = lds0 + (half * 4 + (s16 >> 2)) * C::ROW + 8 * (s16 & 1) + (((vchunk + 4 * db) ^ vswz) * 16);
     }
-    TileNext<D> next;
+    TileNext<D, WAVES> next;
     {
         const int cpos = lane % C::CPR, r_in = lane / C::CPR;
 #pragma unroll
         for (int i = 0; i < C::NL; ++i) {
-            const int row_b = i * C::RPL + r_in, row = wave * kPage + row_b;
+            const int row = wave * C::KPW + i * C::RPL + r_in, row_b = row % kPage;   // in the tile, in its page
             next.koff[i] = row_b * C::ROW + ((cpos ^ (row & (C::CPR - 1))) * 16);
             next.voff[i] = row_b * C::ROW + ((cpos ^ (C::VSW * (row & 3))) * 16);
         }
-        next.lds_w = __builtin_amdgcn_readfirstlane(lds0 + wave * kPage * C::ROW);
+        next.lds_w = __builtin_amdgcn_readfirstlane(lds0 + wave * C::KPW * C::ROW);
         next.gk = next.gv = nullptr;
         next.stream = grouped || (it.kind & kSoloTile) != 0;
     }
@@ -877,10 +880,21 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
         next.gk = reinterpret_cast<const char *>(p.k_cache + tile);
         next.gv = reinterpret_cast<const char *>(p.v_cache + tile);
     };
-    {
+    constexpr uint32_t kBuf = C::K_BYTES + C::V_BYTES;
+    if constexpr (WAVES == kWaves) {
         const int32_t blk0 = step_block(0);
         point_at(blk0);
-        tile_load<D>(next, 0, blk0 >= 0, it.kv_end - it.kv_begin, wave, lane);
+        tile_load<D, WAVES>(next, 0, blk0 >= 0, it.kv_end - it.kv_begin, wave, lane);
+    } else {
+        // ring: the tiles of the first kRingAhead steps
+#pragma unroll
+        for (int t = 0; t < kRingAhead; ++t) {
+            if (t < nsteps) {
+                const int32_t blk = step_block(t);
+                point_at(blk);
+                tile_load<D, WAVES>(next, t * kBuf, blk >= 0, it.kv_end - it.kv_begin - t * kKvTile, wave, lane);
+            }
+        }
     }
     wait_loads_to_lds();
     // Everything the compiler loaded from memory for this item (Q fragments, table entries) is
@@ -910,7 +924,7 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
         if (active && blk_n >= 0 && keys_n >= kKvTile && !next.stream) {
             tile_compute<E, D, true, BUFI>(kaddr, vaddr, qf, o, m, l, c2, k0, pos, half, masked, next);
         } else {
-            if (more) tile_load<D>(next, BUFI ^ 1, blk_n >= 0, keys_n, wave, lane);
+            if (more) tile_load<D, WAVES>(next, (BUFI ^ 1) * kBuf, blk_n >= 0, keys_n, wave, lane);
             if (active) tile_compute<E, D, false, BUFI>(kaddr, vaddr, qf, o, m, l, c2, k0, pos, half, masked, next);
         }
         wait_loads_to_lds();
@@ -927,9 +941,55 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
         }
         __syncthreads();
     };
-    for (int32_t step = 0; step < nsteps; step += 2) {
-        do_step(step, std::integral_constant<int, 0>());
-        if (step + 1 < nsteps) do_step(step + 1, std::integral_constant<int, 1>());
+    if constexpr (WAVES == kWaves) {
+        for (int32_t step = 0; step < nsteps; step += 2) {
+            do_step(step, std::integral_constant<int, 0>());
+            if (step + 1 < nsteps) do_step(step + 1, std::integral_constant<int, 1>());
+        }
+    } else {
+        // Ring of kRingBufs tiles.  During step s the loads of step s + kRingAhead are issued (their
+        // buffer held step s + kRingAhead - kRingBufs, which every wavefront left before the last
+        // barrier); the wavefronts meet every kRingBarrier steps, after each has waited for its loads of
+        // the steps up to the next meeting, so between two barriers they may be a step apart.  Buffers
+        // are addressed through registers here (one loop body, the ring position is a scalar).
+        constexpr int kLoadsPerStep = 2 * C::NL;
+        const uint32_t lds_w0 = next.lds_w;
+        uint32_t ring_s = 0, ring_t = (kRingAhead % kRingBufs) * kBuf;   // byte offsets of the tiles of steps s and s + kRingAhead
+        for (int32_t step = 0; step < nsteps; ++step) {
+            const int32_t k0 = it.kv_begin + step * kKvTile;
+            const int32_t t = step + kRingAhead;
+            const bool more = t < nsteps;
+            const int32_t blk_t = more ? step_block(t) : -1;
+            const int32_t keys_t = it.kv_end - (it.kv_begin + t * kKvTile);
+            const bool active = k0 <= wave_last_pos;
+            const bool masked = k0 + kKvTile - 1 > wave_first_pos;
+            uint32_t ka[C::KS], va[C::DB];
+#pragma unroll
+            for (int ks = 0; ks < C::KS; ++ks) ka[ks] = kaddr[ks] + ring_s;
+#pragma unroll
+            for (int db = 0; db < C::DB; ++db) va[db] = vaddr[db] + ring_s;
+            if (more) point_at(blk_t);
+            if (active && more && blk_t >= 0 && keys_t >= kKvTile && !next.stream) {
+                next.lds_w = lds_w0 + ring_t - kBuf;   // tile_compute aims at "the other buffer" of buffer 0
+                tile_compute<E, D, true, 0, WAVES>(ka, va, qf, o, m, l, c2, k0, pos, half, masked, next);
+            } else {
+                next.lds_w = lds_w0;
+                if (more) tile_load<D, WAVES>(next, ring_t, blk_t >= 0, keys_t, wave, lane);
+                if (active) tile_compute<E, D, false, 0, WAVES>(ka, va, qf, o, m, l, c2, k0, pos, half, masked, next);
+            }
+            ring_s = ring_s + kBuf == kRingBufs * kBuf ? 0u : ring_s + kBuf;
+            ring_t = ring_t + kBuf == kRingBufs * kBuf ? 0u : ring_t + kBuf;
+            if (step % kRingBarrier == kRingBarrier - 1 && step + 1 < nsteps) {
+                // Landed must be everything up to step + kRingBarrier; the loads of the steps behind that
+                // may stay in flight -- counted on only while those steps are whole tiles (the last step
+                // of a range may be a partial tile with fewer loads).
+                if (step + kRingAhead < nsteps - 1)
+                    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(kLoadsPerStep * (kRingAhead - kRingBarrier)) : "memory");
+                else
+                    wait_loads_to_lds();
+                __syncthreads();
+            }
+        }
     }
 
     if (pace && threadIdx.x == 0) progress_store(pace + team.member, kNotRunning);
@@ -997,16 +1057,17 @@ __device__ __forceinline__ WorkItem load_item(const WorkItem *src)
 // ------------------------------------------------------------------------------------------
 constexpr int kXcds = 8;   // accelerator dies of the chip, each with its own L2
 
-template <class E, int D>
-__global__ void __launch_bounds__(kThreads, 2)
+template <class E, int D, int WAVES>
+__global__ void __launch_bounds__(WAVES * 64, 8 / WAVES)
 attention_kernel(const AttnParams p)
 {
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int H = p.heads;
     const int32_t n_tile_wg = p.n_tile_wgs;
-    // K/V tiles of the matrix-core body (the kernel's LDS is allocated for every work-group alike)
-    __shared__ __attribute__((aligned(16))) char lds[2 * (TileCfg<D>::K_BYTES + TileCfg<D>::V_BYTES)];
+    // K/V tiles of the matrix-core body (the kernel's LDS is allocated for every work-group alike):
+    // two buffers for work-groups of four wavefronts, the ring for wide ones
+    __shared__ __attribute__((aligned(16))) char lds[(WAVES == kWaves ? 2 : kRingBufs) * (TileCfg<D>::K_BYTES + TileCfg<D>::V_BYTES)];
     if ((int32_t)blockIdx.x < n_tile_wg) {
         // Tile units (item, head) are dealt round-robin to the tile work-groups.  With as many
         // work-groups as units each takes one; with fewer (mixed batches: part of the resident
@@ -1039,7 +1100,7 @@ attention_kernel(const AttnParams p)
             team.member = __builtin_amdgcn_readfirstlane(p.teams[item].member);
             team.size = __builtin_amdgcn_readfirstlane(p.teams[item].size);
             team.stride = __builtin_amdgcn_readfirstlane(p.teams[item].stride);
-            tile_body<E, D>(p, it, team, head, lds);
+            tile_body<E, D, WAVES>(p, it, team, head, lds);
             __syncthreads();   // the next unit's first loads overwrite the tile buffers
         }
         return;
@@ -1048,13 +1109,13 @@ attention_kernel(const AttnParams p)
         // a group item (a generation row of grouped K/V heads) names its K/V head; one work-group each
         const WorkItem it = load_item(p.items + p.n_tile_items + ((int32_t)blockIdx.x - n_tile_wg));
         const TeamRef team = {-1, 0, 1, 0};
-        tile_body<E, D>(p, it, team, (it.kind >> 8) * p.group, lds);
+        tile_body<E, D, WAVES>(p, it, team, (it.kind >> 8) * p.group, lds);
         return;
     }
-    const int hg = (H + kWaves - 1) / kWaves;
+    const int hg = (H + WAVES - 1) / WAVES;
     const int32_t idx = (int32_t)blockIdx.x - n_tile_wg - p.n_group_items;
     const int32_t item = p.n_tile_items + p.n_group_items + idx / hg;
-    const int head = (idx % hg) * kWaves + wave;
+    const int head = (idx % hg) * WAVES + wave;
     if (head >= H) return;
     const WorkItem it = load_item(p.items + item);
     row_body<E, D, kRowSets>(p, it, head, lane);
@@ -1215,15 +1276,20 @@ int launch_copy_blocks(const void *src_k, const void *src_v, void *dst_k, void *
 
 int launch_attention(const AttnParams &p, int32_t D, bool fp16, void *stream)
 {
-    const int hg = (p.heads + kWaves - 1) / kWaves;
+    const int waves = p.wide ? kWideWaves : kWaves;
+    const int hg = (p.heads + waves - 1) / waves;
     const int64_t grid = (int64_t)p.n_tile_wgs + p.n_group_items + (int64_t)p.n_row_items * hg;
     if (grid == 0) return 0;
     const int64_t units = (int64_t)p.n_tile_items * p.heads + p.n_group_items;
     if (grid > 0x7FFFFFFF || units > 0x7FFFFFFF) return (int)hipErrorInvalidConfiguration;
-    void (*kernel)(const AttnParams) =
-        fp16 ? (D == 128 ? attention_kernel<Fp16, 128> : attention_kernel<Fp16, 64>)
-             : (D == 128 ? attention_kernel<Bf16, 128> : attention_kernel<Bf16, 64>);
-    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(kThreads), 0, (hipStream_t)stream, p);
+    void (*kernel)(const AttnParams);
+    if (p.wide)
+        kernel = fp16 ? (D == 128 ? attention_kernel<Fp16, 128, kWideWaves> : attention_kernel<Fp16, 64, kWideWaves>)
+                      : (D == 128 ? attention_kernel<Bf16, 128, kWideWaves> : attention_kernel<Bf16, 64, kWideWaves>);
+    else
+        kernel = fp16 ? (D == 128 ? attention_kernel<Fp16, 128, kWaves> : attention_kernel<Fp16, 64, kWaves>)
+                      : (D == 128 ? attention_kernel<Bf16, 128, kWaves> : attention_kernel<Bf16, 64, kWaves>);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(waves * 64), 0, (hipStream_t)stream, p);
     return (int)hipGetLastError();
 }
 

@@ -16,6 +16,16 @@ constexpr int kTileRows = 128;   // query rows of one prompt tile (matrix-core b
 constexpr int kKvTile = 64;      // keys staged per step of the matrix-core body
 constexpr int kThreads = 256;    // work-group size of the attention kernel (4 wavefronts)
 constexpr int kWaves = kThreads / 64;
+// Wide launches: work-groups of 8 wavefronts, one per compute unit.  A prompt tile then has 256
+// query rows (32 per wavefront) over one shared K/V tile, which lives in a ring of kRingBufs
+// buffers: the loads of step s + kRingAhead are issued during step s and the wavefronts meet at a
+// barrier every kRingBarrier steps only.
+constexpr int kWideWaves = 8;
+constexpr int kWideTileRows = 256;
+constexpr int kRingBufs = 5;
+constexpr int kRingAhead = 3;
+constexpr int kRingBarrier = 2;
+static_assert(kRingAhead >= kRingBarrier && kRingBufs >= kRingAhead + kRingBarrier, "ring hazards");
 
 // kGroupItem: a generation row of a grouped-K/V-head layer on the matrix-core body -- the "rows" of
 // the tile are the H/HK query heads that share one K/V head (its index sits in kind >> 8), all at
@@ -73,6 +83,7 @@ struct PlanOptions {
     int64_t pp_rowstream = 0;
     int64_t pp_resident_wgs = 0;  // 0 = automatic
     int64_t pp_team_min_steps = 0; // shortest key range (in 64-key steps) whose q-tiles form a team; 0 = automatic
+    int64_t tile_mode = 0;        // 0, 1 = work-groups of 4 wavefronts, 2 = of 8 (wide)
 };
 
 struct Plan {
@@ -84,6 +95,7 @@ struct Plan {
     int32_t n_group_items = 0;
     int32_t n_row_items = 0;
     int32_t n_tile_wgs = 0;       // work-groups that share the n_tile_items * heads tile units
+    bool wide = false;            // work-groups of kWideWaves wavefronts, tiles of kWideTileRows rows
     int64_t part_rows = 0;
 
     // workspace layout (byte offsets)
@@ -120,6 +132,7 @@ struct AttnParams {
     int32_t n_merge;
     const TeamRef *teams;   // [n_tile_items]
     uint32_t *progress;
+    int32_t wide;           // Plan::wide
 };
 
 // The entry point that allocates nothing keeps work list and partial results in a device array of

@@ -24,6 +24,16 @@ namespace {
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// What depends on the launch's work-group shape: four wavefronts and 128-row prompt tiles, two
+// work-groups resident per compute unit -- or (wide) eight wavefronts and 256-row tiles, one
+// work-group per compute unit, so that a compute unit runs either prompt tiles or generation rows.
+struct Shape {
+    int64_t waves, tile_rows, slots;   // slots: work-groups resident on the chip at a time
+};
+constexpr Shape kNarrow = {kWaves, kTileRows, 512};
+constexpr Shape kWide = {kWideWaves, kWideTileRows, 256};
+constexpr int64_t kComputeUnits = 256;
+
 // Row items wanted from a batch: two per wavefront slot (256 compute units, 8 wavefronts each).
 // Every item costs a partial result and a share of the merge, so few long ranges beat many short
 // ones as long as the slots stay filled; beyond kMaxRowSplitTokens a range's own tail shows
@@ -31,7 +41,6 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 constexpr int64_t kRowItemTarget = 256 * 8 * 2;
 constexpr int64_t kMaxRowSplitTokens = 1536;
 constexpr int64_t kMinRowSplitTokens = 128;
-constexpr int64_t kRowSlots = 512;          // work-groups resident at a time (2 per compute unit)
 constexpr int64_t kMinTileSplitSteps = 8;   // 512 keys
 constexpr int64_t kTeamMinSteps = 16;       // shorter ranges do not drift apart far enough to matter
 // Grouped K/V heads: from this group size on a generation row runs on the matrix-core body, one
@@ -48,8 +57,9 @@ constexpr int64_t kMinGroupSplitSteps = 4;
 // best: the rows are bandwidth-bound, so a last round with few work-groups in it streams at a
 // fraction of the chip's rate for a whole range's time (measured on configs 2 and 3: kernel times
 // follow this fill factor, 2 % between good and bad lengths).
-int64_t auto_row_split_tokens(const PlanOptions &opt, int64_t total_tokens, const std::vector<int64_t> &row_keys)
+int64_t auto_row_split_tokens(const PlanOptions &opt, const Shape &sh, int64_t total_tokens, const std::vector<int64_t> &row_keys)
 {
+    const int64_t kRowSlots = sh.slots;
     const int64_t bs = opt.block_size;
     if (opt.tg_split_blocks > 0) return opt.tg_split_blocks * bs;
     const int64_t want = std::min(std::max<int64_t>(ceil_div(total_tokens * opt.heads, kRowItemTarget), kMinRowSplitTokens),
@@ -58,7 +68,7 @@ int64_t auto_row_split_tokens(const PlanOptions &opt, int64_t total_tokens, cons
     if (row_keys.empty() || row_keys.size() > 512) return want_blocks * bs;   // keeps the search to a few microseconds
     const int64_t lo = std::max<int64_t>(ceil_div(kMinRowSplitTokens, bs), want_blocks * 2 / 3);
     const int64_t hi = std::max(lo, std::min<int64_t>(kMaxRowSplitTokens / bs, want_blocks * 3 / 2));
-    const int64_t wgs_per_item = ceil_div(opt.heads, kWaves);
+    const int64_t wgs_per_item = ceil_div(opt.heads, sh.waves);
     {   // with many rounds the last one weighs little, and the longest ranges are the cheapest
         int64_t items = 0;
         for (int64_t keys : row_keys) items += ceil_div(keys, want_blocks * bs);
@@ -85,8 +95,9 @@ int64_t auto_row_split_tokens(const PlanOptions &opt, int64_t total_tokens, cons
 // for batches of generation rows alone and few rounds -- the length near that whose work-groups
 // fill whole rounds of the resident slots best (measured on 8 query / 1 K/V head, 256 rows at 2-8 K:
 // 1092 work-groups 62 %, 990 work-groups 69 % of the HBM peak).
-int64_t auto_group_split_keys(const PlanOptions &opt, int64_t total_tokens, const std::vector<int64_t> &row_keys)
+int64_t auto_group_split_keys(const PlanOptions &opt, const Shape &sh, int64_t total_tokens, const std::vector<int64_t> &row_keys)
 {
+    const int64_t kRowSlots = sh.slots;
     const int64_t want = std::max<int64_t>(ceil_div(ceil_div(total_tokens * opt.kv_heads, kGroupItemTarget), kKvTile),
                                            kMinGroupSplitSteps);
     if (row_keys.empty() || row_keys.size() > 512) return want * kKvTile;
@@ -117,10 +128,11 @@ int64_t auto_group_split_keys(const PlanOptions &opt, int64_t total_tokens, cons
 // each scored by a list-scheduling estimate of the launch (every piece exists once per head and
 // occupies one of the kTileSlots resident work-groups; generation rows keep the memory pipe busy
 // for `row_us` anyway), and the longest range within a few percent of the best score wins.
-constexpr int64_t kTileSlots = 512;      // 2 resident work-groups per compute unit
 constexpr double kStepUs = 1.9;          // one 64-key step of a 128-row tile with the chip full, measured
 constexpr double kPieceOverheadSteps = 5.0;  // item and Q loads, first tile, partial result, its share of the merge
 constexpr double kRowBytesPerUs = 6.0e6; // generation rows stream at about 6 TB/s
+
+constexpr double kRowUnitBytesPerUs = 5.0e4;   // one compute unit streams generation rows at about 50 GB/s
 
 // Pieces of one candidate, longest first: (length in steps incl. overhead, how many).
 typedef std::vector<std::pair<double, int64_t>> PieceList;
@@ -153,7 +165,7 @@ void pieces_of(const std::vector<int64_t> &tile_steps_desc, int64_t len_steps, P
 // piece: the estimate is the sum of the round leaders (exact for equal pieces, an upper bound of
 // the greedy schedule otherwise) but never less than the mean load.  O(pieces), no simulation:
 // the planner runs on the host in front of every launch.
-double tile_makespan_us(const PieceList &pieces, int64_t heads)
+double tile_makespan_us(const PieceList &pieces, int64_t heads, int64_t kTileSlots)
 {
     double sum = 0.0, rounds = 0.0;
     int64_t placed = 0;   // pieces (x heads) placed so far
@@ -168,8 +180,9 @@ double tile_makespan_us(const PieceList &pieces, int64_t heads)
     return std::max(rounds, sum / (double)kTileSlots) * kStepUs;
 }
 
-int64_t auto_tile_split_tokens(const PlanOptions &opt, std::vector<int64_t> tile_steps, double row_us)
+int64_t auto_tile_split_tokens(const PlanOptions &opt, const Shape &sh, std::vector<int64_t> tile_steps, double row_us)
 {
+    const int64_t kTileSlots = sh.slots;
     if (opt.pp_split_tokens > 0) return ceil_div(opt.pp_split_tokens, kKvTile) * kKvTile;
     if (tile_steps.empty()) return kKvTile;
     std::sort(tile_steps.begin(), tile_steps.end(), std::greater<int64_t>());
@@ -204,7 +217,7 @@ int64_t auto_tile_split_tokens(const PlanOptions &opt, std::vector<int64_t> tile
     double best = 1e300;
     for (size_t i = 0; i < cands.size(); ++i) {
         pieces_of(tile_steps, cands[i], &pieces);
-        score[i] = std::max(tile_makespan_us(pieces, opt.heads), row_us);
+        score[i] = std::max(tile_makespan_us(pieces, opt.heads, kTileSlots), row_us);
         best = std::min(best, score[i]);
     }
     for (size_t i = 0; i < cands.size(); ++i)
@@ -246,6 +259,15 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
     }
     if (cs[0] != 0) return MPA_ERR_BAD_BATCH;
     const int64_t bs = opt.block_size;
+    // Work-group shape of the launch: wide only on request.  Measured, the wide shape is within 2 % of
+    // the narrow one on prompts alone (better on long chunks, where it halves the K/V loads per row),
+    // and loses on mixed batches and on generation rows of grouped K/V heads, so nothing selects it
+    // by itself.
+    const bool wide = opt.tile_mode == 2 && !opt.pp_rowstream;
+    plan->wide = wide;
+    const Shape &sh = wide ? kWide : kNarrow;
+    const int64_t kTileRows = sh.tile_rows;   // (shadows the constant of the narrow shape)
+    const int64_t kTileSlots = sh.slots;
     int64_t row_tokens = 0;   // keys visited by generation rows, in whole blocks
     std::vector<int64_t> row_keys;   // the same per row
     std::vector<int64_t> tile_steps;
@@ -271,11 +293,11 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
     // (next to prompt tiles, which hold slots of their own for part of the launch, the rounds do
     // not come out as counted: there the plain target length stays)
     static const std::vector<int64_t> kNoRows;
-    const int64_t row_split = auto_row_split_tokens(opt, row_tokens, tile_steps.empty() ? row_keys : kNoRows);
+    const int64_t row_split = auto_row_split_tokens(opt, sh, row_tokens, tile_steps.empty() ? row_keys : kNoRows);
     // key range of a group item, in keys: enough items for the chip, whole 64-key steps
-    const int64_t group_split = auto_group_split_keys(opt, row_tokens, tile_steps.empty() ? row_keys : kNoRows);
+    const int64_t group_split = auto_group_split_keys(opt, sh, row_tokens, tile_steps.empty() ? row_keys : kNoRows);
     const double row_us = (double)row_tokens * 4.0 * opt.head_dim * opt.kv_heads / kRowBytesPerUs;
-    const int64_t tile_split = auto_tile_split_tokens(opt, tile_steps, row_us);
+    const int64_t tile_split = auto_tile_split_tokens(opt, sh, tile_steps, row_us);
 
     std::vector<WorkItem> tiles, groups, rows;
     auto emit = [&](std::vector<WorkItem> &dst, int32_t kind, int32_t seq, int32_t q_row0,
@@ -333,8 +355,8 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
             // ranges when its rows end earlier.
             const int64_t n_seq = ceil_div((int64_t)ctx[i], tile_split);
             const int64_t len_seq = ceil_div(ceil_div((int64_t)ctx[i], n_seq), kKvTile) * kKvTile;
-            for (int32_t r0 = 0; r0 < q_len; r0 += kTileRows) {
-                int32_t nr = std::min<int32_t>(kTileRows, q_len - r0);
+            for (int32_t r0 = 0; r0 < q_len; r0 += (int32_t)kTileRows) {
+                int32_t nr = (int32_t)std::min<int64_t>(kTileRows, q_len - r0);
                 emit(tiles, kTileItem, i, cs[i] + r0, nr, prior + r0, len_seq, kKvTile, true);
             }
         }
@@ -388,7 +410,26 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
         const double tile_us = (double)steps * opt.heads * kStepUs / (double)kTileSlots;
         int64_t wgs = units;
         if (opt.pp_resident_wgs > 0) wgs = std::min(units, opt.pp_resident_wgs);
-        else if ((!rows.empty() || !groups.empty()) && row_us > 0.15 * tile_us) {
+        else if (wide && (!rows.empty() || !groups.empty())) {
+            // One work-group per compute unit: the tiles get n compute units for the whole launch and
+            // the generation rows stream on the others, at kRowUnitBytesPerUs each up to the chip's
+            // rate; when the tiles are done first their compute units take rows as well.  n is the
+            // count with the shortest launch by that estimate, a multiple of the number of XCDs.
+            const double row_bytes = row_us * kRowBytesPerUs;
+            const double tile_unit_us = tile_us * (double)kTileSlots;   // on one compute unit
+            auto rate = [&](int64_t cus) { return std::min(kRowBytesPerUs, (double)cus * kRowUnitBytesPerUs); };
+            double best = 1e300;
+            for (int64_t n = 8; n <= kComputeUnits - 8; n += 8) {
+                const double t_tiles = tile_unit_us / (double)std::min(n, units);
+                const double t_rows = row_bytes / rate(kComputeUnits - n);
+                const double t = t_tiles >= t_rows ? t_tiles
+                                                   : t_tiles + (row_bytes - t_tiles * rate(kComputeUnits - n)) / rate(kComputeUnits);
+                if (t < best * 0.999) {
+                    best = t;
+                    wgs = std::min(n, units);
+                }
+            }
+        } else if ((!rows.empty() || !groups.empty()) && row_us > 0.15 * tile_us) {
             // The more prompt work there is for the generation rows' streaming time, the more of
             // the slots the tiles keep: 256 (one per compute unit, a row work-group beside each)
             // when the tiles alone would take half the rows' time, 64 more per doubling of that

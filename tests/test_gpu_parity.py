@@ -349,3 +349,67 @@ def test_random_combinations_of_geometry_dtype_and_options(mpa):
         ref, okc, ovc = oracle_run(b)
         assert np.array_equal(to_host_u16(db.k_cache), okc) and np.array_equal(to_host_u16(db.v_cache), ovc), what
         assert_close(to_host_u16(db.out), ref, what, dtype=dtype)
+
+
+# ---- the wide work-group shape (MPA_OPT_TILE_MODE 2): eight wavefronts, 256-row tiles, ring of K/V tiles
+
+WIDE = {"MPA_OPT_TILE_MODE": 2}
+
+
+@pytest.mark.parametrize("opts", [{}, {"MPA_OPT_PP_SPLIT_TOKENS": 64}, {"MPA_OPT_PP_SPLIT_TOKENS": 192, "MPA_OPT_TG_SPLIT_BLOCKS": 2},
+                                  {"MPA_OPT_PP_RESIDENT_WGS": 1}])
+def test_wide_shape_config1(mpa, opts):
+    b = W.config1()
+    ref, _, _ = oracle_run(b)
+    out, _, _ = gpu_run(ctx_for(mpa, b, **WIDE, **opts), b)
+    assert_close(out, ref, f"wide {opts}")
+
+
+@pytest.mark.parametrize("resident", [1, 3, 0])
+@pytest.mark.parametrize("split", [0, 64, 320, 1024])
+def test_wide_shape_chunks_of_several_tiles_and_every_ring_phase(mpa, resident, split):
+    """Chunks of 600, 300 and 257 rows (256-row tiles and their remainders: one full wavefront, a
+    wavefront of one row), contexts that make ranges of 1 to 40 steps (shorter than the ring's look-ahead,
+    ending on every phase of the barrier interval, partial last tiles), next to generation rows;
+    few work-groups walking all units, and one per unit."""
+    ql, ctx = [600, 300, 257, 1, 1, 1, 40], [1500, 300, 2560, 700, 64, 2000, 103]
+    b = W.make_batch("wide-multi", 123, 4, 128, 16, sum((c + 15) // 16 for c in ctx) + 3, ql, ctx)
+    ref, _, _ = oracle_run(b)
+    out, _, _ = gpu_run(ctx_for(mpa, b, **WIDE, MPA_OPT_PP_RESIDENT_WGS=resident, MPA_OPT_PP_SPLIT_TOKENS=split), b)
+    assert_close(out, ref, f"wide resident={resident} split={split}")
+    for i in range(b.S):
+        r0, r1 = b.chunk_starts[i], b.chunk_starts[i + 1]
+        assert_close(out[r0:r1], ref[r0:r1], f"wide resident={resident} split={split} seq {i}")
+
+
+@pytest.mark.parametrize("seed", range(4))
+@pytest.mark.parametrize("D,H,HK,dtype,bs", [(64, 2, 2, "bf16", 16), (128, 5, 5, "bf16", 32), (128, 12, 4, "bf16", 16),
+                                             (64, 8, 2, "fp16", 16), (128, 16, 2, "fp16", 128), (128, 9, 9, "fp16", 16)])
+def test_wide_shape_random_ragged_batches(mpa, seed, D, H, HK, dtype, bs):
+    """Both element types, both head dimensions, grouped K/V heads (group items on the wide tile
+    body), larger blocks; automatic ranges and forced short ones."""
+    b = W.random_ragged(5000 + seed, H=H, D=D, n_pp=2 + seed % 2, n_tg=3, max_q=520, max_prior=700, max_ctx=1200, Hkv=HK,
+                        dtype=dtype, bs=bs)
+    ref, okc, ovc = oracle_run(b)
+    for opts in ({}, {"MPA_OPT_PP_SPLIT_TOKENS": 128, "MPA_OPT_TG_SPLIT_BLOCKS": 3}):
+        out, kc, vc = gpu_run(ctx_for(mpa, b, **WIDE, **opts), b)
+        assert np.array_equal(kc, okc) and np.array_equal(vc, ovc)
+        assert_close(out, ref, f"wide {b.name} {opts}", dtype=dtype)
+
+
+def test_wide_shape_equals_the_narrow_one_on_unsplit_rows(mpa):
+    """A row's arithmetic does not depend on the work-group shape: same tile steps, same order of keys.
+    With every range unsplit the two shapes give the same bits."""
+    ql, ctx = [300, 129, 1, 1], [900, 129, 500, 31]
+    b = W.make_batch("wide-vs-narrow", 77, 4, 128, 16, sum((c + 15) // 16 for c in ctx) + 3, ql, ctx)
+    big = {"MPA_OPT_PP_SPLIT_TOKENS": 1 << 20, "MPA_OPT_TG_SPLIT_BLOCKS": 1 << 16}
+    out_n, _, _ = gpu_run(ctx_for(mpa, b, MPA_OPT_TILE_MODE=1, **big), b)
+    out_w, _, _ = gpu_run(ctx_for(mpa, b, **WIDE, **big), b)
+    assert np.array_equal(out_n, out_w)
+
+
+def test_wide_shape_steep_softmax(mpa):
+    b = W.random_ragged(4242, H=3, D=128, n_pp=2, n_tg=2, max_q=300, max_prior=500, max_ctx=900)
+    ref, _, _ = oracle_run(b, scale=4.0)
+    out, _, _ = gpu_run(ctx_for(mpa, b, **WIDE), b, scale=4.0)
+    assert_close(out, ref, "wide steep", abs_scale=max(1.0, float(np.abs(ref).max())))

@@ -9,12 +9,15 @@ import workloads as W
 from test_abi_host import check_plan_covers
 
 
+@pytest.mark.parametrize("wide", [False, True], ids=["narrow", "wide"])
 @pytest.mark.parametrize("seed", range(12))
-def test_random_batches_plan_invariants(seed):
+def test_random_batches_plan_invariants(seed, wide):
     H = [1, 4, 12, 40][seed % 4]
     b = W.random_ragged(500 + seed, H=H, D=128, n_pp=1 + seed % 3, n_tg=seed % 5, max_q=700, max_prior=3000,
                         max_ctx=5000)
     c = mpa.Context(H, 128)
+    c.set_option(mpa.MPA_OPT_TILE_MODE, 2 if wide else 1)
+    tile_rows = 256 if wide else 128
     if seed % 3 == 1:
         c.set_option(mpa.MPA_OPT_TG_SPLIT_BLOCKS, 1 + seed)
         c.set_option(mpa.MPA_OPT_PP_SPLIT_TOKENS, 64 * (1 + seed % 4))
@@ -29,7 +32,9 @@ def test_random_batches_plan_invariants(seed):
         assert (it[7] >> 8) == int(alone)
     assert (items[:, 4] % 16 == 0).all() and (items[:n_tile, 4] % 64 == 0).all()
     assert (items[:, 5] > items[:, 4]).all()
-    assert (items[n_tile:, 2] == 1).all() and (items[:n_tile, 2] <= 128).all() and (items[:, 2] >= 1).all()
+    assert (items[n_tile:, 2] == 1).all() and (items[:n_tile, 2] <= tile_rows).all() and (items[:, 2] >= 1).all()
+    if wide and n_tile:   # the chunks longer than a narrow tile really are cut into 256-row tiles
+        assert items[:n_tile, 2].max() == min(int(b.q_lens.max()), 256)
     check_plan_covers(b, items, counts, H)
     # partial rows: disjoint ranges [part_row, part_row + q_rows) inside [0, n_part)
     parts = sorted((int(it[6]), int(it[6]) + int(it[2])) for it in items if it[6] >= 0)
