@@ -12,8 +12,10 @@ kernel of the mixed step (HBM bound: the generation rows dominate); `roofline_tg
 `roofline_pp` are the same kernel timed on the generation-only and prompt-only parts of the
 batch, against the HBM and bf16 matrix-core peaks respectively; `cpu_baseline` is the fp64
 oracle timed on the host cores on a sample of the same batch.  Other workloads (--workload): cfg1,
-cfg2, cfg3:p<prior>, cfg4, cfg5[:iteration], gqa, gqa-decode, <cfg>@bs32|64|128, <cfg>@fp16, sched13b (batches formed by the
-scheduler from a Poisson trace), swap13b (block copies).
+cfg2, cfg3:p<prior>, cfg4, cfg5[:iteration], gqa, gqa-decode, <cfg>@bs32|64|128, <cfg>@fp16, held:<name> (scheduler-shaped
+batches no planner constant was fitted on), sched13b (batches formed by the scheduler from a Poisson trace), swap13b
+(block copies).  Modes: --ceilings (the library's micro-kernels: what this machine reaches), --planner-sweep (the planner's
+choices against a grid of forced ones), --only-part tg|pp.
 """
 from __future__ import annotations
 
@@ -31,10 +33,47 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 matrix, published
-# what plain micro-kernels reach on this part (measured on the same machine, see the design notes):
-# a streaming non-temporal read of 8 GiB, and v_mfma_f32_32x32x16_bf16 back to back from registers
-HBM_ACHIEVABLE_GBS = 7150.0
-MFMA_ACHIEVABLE_TFLOPS = 2150.0
+PART_REPEAT = 8   # launches between one pair of timing events when a part of the batch is timed alone
+
+
+def csrc_digest() -> str:
+    """Content hash of the kernel and planner sources: stored with every HBM-traffic figure taken
+    from a profiler run, so that a figure measured on other sources is recognised as stale."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in ("kernels.hip", "planner.cpp", "mpa_internal.h"):
+        with open(os.path.join(ROOT, "paper_2503_13737_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measure_ceilings(mpa, full: bool = False) -> dict:
+    """What plain micro-kernels of the library reach on this machine, measured now: a streaming
+    non-temporal read, matrix instructions back to back from registers and, with `full`, reads of
+    randomly placed 4 KiB and 16 KiB chunks (the access pattern of a paged cache)."""
+    import torch
+    nbytes = 4 << 30
+    buf = torch.zeros(nbytes, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(1, dtype=torch.int32, device="cuda")
+    kinds = [("stream_read_GBs", mpa.MPA_CEIL_STREAM_READ, 0, 1e9), ("mfma_bf16_TFLOPs", mpa.MPA_CEIL_MFMA_BF16, 2000, 1e12)]
+    if full:
+        kinds += [("random_4KiB_GBs", mpa.MPA_CEIL_RANDOM_4K, 32, 1e9), ("random_16KiB_GBs", mpa.MPA_CEIL_RANDOM_16K, 8, 1e9)]
+    out = {}
+    for name, kind, iters, unit in kinds:
+        mpa.ceiling_launch(kind, buf, nbytes, iters, sink)
+        torch.cuda.synchronize()
+        best = 0.0
+        for _ in range(3):
+            ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]   # the launches go to torch's current stream
+            ev[0].record()
+            work = sum(mpa.ceiling_launch(kind, buf, nbytes, iters, sink) for _ in range(5))
+            ev[1].record()
+            torch.cuda.synchronize()
+            best = max(best, work / (ev[0].elapsed_time(ev[1]) * 1e-3) / unit)
+        out[name] = best
+    del buf
+    torch.cuda.empty_cache()
+    return out
 
 
 def spread(ms) -> dict:
@@ -56,6 +95,8 @@ def make_workload(name: str):
     if name.startswith(("cfg2@bs", "cfg3@bs")):   # the same batch on KV blocks of 32, 64, 128 tokens
         bs = int(name.split("@bs")[1])
         return W.config2(bs) if name.startswith("cfg2") else W.config3(bs=bs)
+    if name.startswith("held:"):     # scheduler-shaped batches kept out of every fit (see workloads.held_out)
+        return W.held_out(name[len("held:"):])
     if name == "cfg3":
         return W.config3()
     if name.startswith("cfg3:p"):    # the same batch with the prompt chunk at a chosen prior context
@@ -137,14 +178,18 @@ def algorithmic_flops_pp(b, seqs) -> int:
     return 4 * b.D * b.H * pairs
 
 
-def time_kernel(dw, fn, steps, warmup, every: int = 1):
+def time_kernel(dw, fn, steps, warmup, every: int = 1, repeat: int = 1):
     """Wall time of `steps` calls of fn, and the attention kernel's duration (HIP events recorded by
-    the library around the launch) in every `every`-th of them."""
+    the library around the launch) in every `every`-th of them.  With repeat > 1 a timed call
+    launches the kernel that many times between its two events and the duration is per launch: a
+    pair of events holds the queue for about ten microseconds, which would be counted into a lone
+    launch (15 % of a 45 us kernel)."""
     import torch
     for _ in range(warmup):
         fn()
     torch.cuda.synchronize()
     dw.ctx.set_option(dw.mpa.MPA_OPT_PROFILE_EVERY, every)
+    dw.ctx.set_option(dw.mpa.MPA_OPT_PROFILE_REPEAT, repeat)
     dw.ctx.profile_enable(steps)
     t0 = time.perf_counter()
     for _ in range(steps):
@@ -153,6 +198,7 @@ def time_kernel(dw, fn, steps, warmup, every: int = 1):
     wall = time.perf_counter() - t0
     ms = dw.ctx.profile_read(steps)
     dw.ctx.profile_enable(0)
+    dw.ctx.set_option(dw.mpa.MPA_OPT_PROFILE_REPEAT, 1)
     return wall, ms
 
 
@@ -387,6 +433,43 @@ def run_copy_blocks(args, mpa):
                      "frac": a / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes": by, "kernel_ms": ms}}), flush=True)
 
 
+def run_planner_sweep(args, mpa, b):
+    """The planner's own choice of key-range length and of work-groups for the prompt tiles against
+    a grid of forced values, on one batch: the attention kernel's duration per setting (median of
+    the library's event timings).  Prints one JSON object with the whole table."""
+    import torch
+    dw = DeviceWorkload(b, mpa)
+    dw.ctx.kv_append(dw.k_new, dw.v_new, dw.slot_map, dw.k_cache, dw.v_cache)
+    torch.cuda.synchronize()
+    has_rows = bool((b.q_lens == 1).any())
+    residents = [0, 64, 128, 192, 256, 320, 384, 448] if has_rows else [0]
+    splits = [0, 512, 1024, 2048, 4096, 8192, 16384]
+
+    def measure(resident, split):
+        dw.ctx.set_option(mpa.MPA_OPT_PP_RESIDENT_WGS, resident)
+        dw.ctx.set_option(mpa.MPA_OPT_PP_SPLIT_TOKENS, split)
+        ws = torch.empty(dw.ctx.workspace_bytes_for_batch(b.chunk_starts, b.context_lens), dtype=torch.uint8, device="cuda")
+        fn = lambda: dw.ctx.mixed_paged_attention(dw.q, dw.k_cache, dw.v_cache, dw.block_table, b.chunk_starts,
+                                                  b.context_lens, dw.out, ws, scale=b.scale)
+        best = 1e9
+        for _ in range(3):
+            _, ms = time_kernel(dw, fn, 12, 3)
+            best = min(best, float(np.median(ms)))
+        return best
+
+    table = {}
+    for r in residents:
+        for sp in splits:
+            table[f"{r}/{sp}"] = measure(r, sp)
+    auto = min(measure(0, 0), table["0/0"])
+    table["0/0"] = auto
+    best_key = min(table, key=table.get)
+    print(json.dumps({"planner_sweep": b.name, "heads": b.H, "prompt_chunks": b.q_lens[b.q_lens > 1].tolist(),
+                      "priors": b.priors[b.q_lens > 1].tolist(), "generation_rows": int((b.q_lens == 1).sum()),
+                      "automatic_ms": auto, "best_ms": table[best_key], "best_setting_resident/split": best_key,
+                      "automatic_over_best": auto / table[best_key], "table_ms": table}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -398,6 +481,14 @@ def main():
     ap.add_argument("--only-part", choices=["tg", "pp"], default=None,
                     help="profiling aid: time ONLY the generation rows (tg) or ONLY the prompt chunks (pp) of the "
                          "workload, so that a profiler run sees one launch shape; prints that part's roofline")
+    ap.add_argument("--part-repeat", type=int, default=PART_REPEAT,
+                    help="launches between one pair of timing events when a part of the batch is timed alone")
+    ap.add_argument("--planner-sweep", action="store_true",
+                    help="time the attention kernel of the workload under the planner's own choices and under a grid of "
+                         "forced key-range lengths / tile work-group counts; prints the table")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="only measure what the library's micro-kernels reach on this machine (streaming read, random "
+                         "4 KiB / 16 KiB chunk reads, matrix instructions from registers) and print them")
     ap.add_argument("--calibrate-append-tokens", type=int, default=0,
                     help="also run kv_append on this many synthetic tokens (a plain copy kernel of known size, "
                          "used to scale the HBM byte counters of a profiler run)")
@@ -411,6 +502,9 @@ def main():
     import paper_2503_13737_amd as mpa
     mpa.load()  # fails loudly when the HIP library is missing
 
+    if args.ceilings:
+        print(json.dumps({"ceilings": measure_ceilings(mpa, full=True), "published_peaks": {"hbm_GBs": HBM_PEAK_GBS, "mfma_bf16_TFLOPs": MFMA_BF16_PEAK_TFLOPS}}), flush=True)
+        return
     if args.workload == "sched13b":
         run_scheduled(args, mpa)
         return
@@ -418,6 +512,9 @@ def main():
         run_copy_blocks(args, mpa)
         return
     b = make_workload(args.workload)
+    if args.planner_sweep:
+        run_planner_sweep(args, mpa, b)
+        return
     dw = DeviceWorkload(b, mpa)
     torch.cuda.synchronize()
 
@@ -426,7 +523,7 @@ def main():
         if not sel:
             raise SystemExit(f"workload has no {args.only_part} sequences")
         sub, q, out, ws = sub_batch(dw, sel)
-        _, ms = time_kernel(dw, lambda: dw.attention_only(sub, q, out, ws), args.steps, args.warmup)
+        _, ms = time_kernel(dw, lambda: dw.attention_only(sub, q, out, ws), args.steps, args.warmup, repeat=args.part_repeat)
         t = float(ms.mean()) * 1e-3
         if args.only_part == "tg":
             by = algorithmic_bytes(b, sel)
@@ -438,6 +535,7 @@ def main():
             part = {"kernel": "attention_kernel (prompt chunks only)", "bound": "mfma", "achieved": fl / t / 1e12,
                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": fl / t / 1e12 / MFMA_BF16_PEAK_TFLOPS,
                     "algorithmic_flops": fl, "kernel_ms": t * 1e3}
+        part["launches_per_event_pair"] = args.part_repeat
         print(json.dumps({"only_part": args.only_part, "workload": b.name, "steps": args.steps, "roofline": part}), flush=True)
         return
 
@@ -450,10 +548,18 @@ def main():
     attn_avg_ms = float(attn_ms.mean())
     bytes_alg = algorithmic_bytes(b)
     achieved = bytes_alg / (attn_avg_ms * 1e-3) / 1e9
-    traffic = None
+    # HBM bytes per launch from the profiler's counters (a stored figure: counters need a profiler
+    # run of their own); it counts only if it was taken on the kernel sources this library is built from
+    traffic, traffic_note = None, "no counter run stored for this workload"
     tpath = os.path.join(ROOT, "profiles", f"traffic_{args.workload.replace(':', '_')}.json")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        rec = json.load(open(tpath))
+        if rec.get("csrc_digest") == csrc_digest():
+            traffic, traffic_note = rec.get("hbm_bytes_per_launch"), f"rocprofv3 counters on these sources ({rec.get('csrc_digest')})"
+        else:
+            traffic_note = (f"stale: the stored figure ({rec.get('hbm_bytes_per_launch')}) was taken on other kernel sources "
+                            f"({rec.get('csrc_digest')} vs {csrc_digest()})")
+    ceil = measure_ceilings(mpa)
 
     result = {
         "metric": "mixed-batch paged-attn tokens/s", "value": tokens_per_s, "unit": "tokens/s",
@@ -467,8 +573,10 @@ def main():
         "roofline": {"kernel": "attention_kernel (mixed)", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes": bytes_alg, "kernel_ms": attn_avg_ms,
+                     "traffic_note": traffic_note,
                      "kernel_ms_samples": int(attn_ms.size), **spread(attn_ms),
-                     "achievable_peak": HBM_ACHIEVABLE_GBS, "frac_of_achievable": achieved / HBM_ACHIEVABLE_GBS},
+                     "achievable_peak": ceil["stream_read_GBs"], "frac_of_achievable": achieved / ceil["stream_read_GBs"]},
+        "ceilings": {**ceil, "note": "measured in this run with the library's micro-kernels (mpa_ceiling_launch)"},
     }
 
     if not args.no_parts:
@@ -476,24 +584,26 @@ def main():
         pp = [i for i in range(b.S) if b.q_lens[i] > 1]
         if tg:
             sub, q, out, ws = sub_batch(dw, tg)
-            _, ms = time_kernel(dw, lambda: dw.attention_only(sub, q, out, ws), args.steps, args.warmup)
+            _, ms = time_kernel(dw, lambda: dw.attention_only(sub, q, out, ws), args.steps, args.warmup, repeat=args.part_repeat)
             by = algorithmic_bytes(b, tg)
             a = by / (float(ms.mean()) * 1e-3) / 1e9
             result["roofline_tg"] = {"kernel": "attention_kernel (generation rows only)", "bound": "hbm",
                                      "achieved": a, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": a / HBM_PEAK_GBS,
                                      "algorithmic_bytes": by, "kernel_ms": float(ms.mean()), **spread(ms),
-                                     "achievable_peak": HBM_ACHIEVABLE_GBS, "frac_of_achievable": a / HBM_ACHIEVABLE_GBS}
+                                     "launches_per_event_pair": args.part_repeat,
+                                     "achievable_peak": ceil["stream_read_GBs"], "frac_of_achievable": a / ceil["stream_read_GBs"]}
         if pp:
             sub, q, out, ws = sub_batch(dw, pp)
-            _, ms = time_kernel(dw, lambda: dw.attention_only(sub, q, out, ws), args.steps, args.warmup)
+            _, ms = time_kernel(dw, lambda: dw.attention_only(sub, q, out, ws), args.steps, args.warmup, repeat=args.part_repeat)
             fl = algorithmic_flops_pp(b, pp)
             a = fl / (float(ms.mean()) * 1e-3) / 1e12
             result["roofline_pp"] = {"kernel": "attention_kernel (prompt chunks only)", "bound": "mfma",
                                      "achieved": a, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                                      "frac": a / MFMA_BF16_PEAK_TFLOPS, "algorithmic_flops": fl,
                                      "kernel_ms": float(ms.mean()), **spread(ms),
-                                     "achievable_peak": MFMA_ACHIEVABLE_TFLOPS,
-                                     "frac_of_achievable": a / MFMA_ACHIEVABLE_TFLOPS}
+                                     "launches_per_event_pair": args.part_repeat,
+                                     "achievable_peak": ceil["mfma_bf16_TFLOPs"],
+                                     "frac_of_achievable": a / ceil["mfma_bf16_TFLOPs"]}
         if tg and pp:
             # how much of the two parts' time the one launch hides: 1.0 = no overlap, lower is better
             result["mixed_over_parts"] = attn_avg_ms / (result["roofline_tg"]["kernel_ms"] + result["roofline_pp"]["kernel_ms"])

@@ -87,6 +87,13 @@ enum {
     MPA_OPT_PROFILE_EVERY = 7,   /* with mpa_profile_enable: time every k-th attention call only
                                     (default 1); a pair of timing events costs the queue about
                                     ten microseconds per call                                 */
+    MPA_OPT_PROFILE_REPEAT = 11, /* with mpa_profile_enable: a timed call launches the attention
+                                    kernel this many times back to back between its two events
+                                    (default 1) and mpa_profile_read reports the time per launch:
+                                    for timing launches of a few tens of microseconds, against
+                                    which a pair of events weighs 10-20 %.  The launches are
+                                    identical (same inputs, same outputs); set it before
+                                    profiling and leave it unchanged until the series is read  */
     MPA_OPT_TILE_MODE = 10,      /* work-group shape of the attention launch: 0 or 1 (default) = four
                                     wavefronts, 128-row prompt tiles, two work-groups per compute
                                     unit; 2 = eight wavefronts, 256-row prompt tiles over a ring of
@@ -266,6 +273,26 @@ int mpa_mixed_paged_attention_static(mpa_ctx *ctx, const void *q, const void *k_
  */
 int mpa_profile_enable(mpa_ctx *ctx, int32_t max_calls);
 int mpa_profile_read(mpa_ctx *ctx, float *ms, int32_t cap, int32_t *n_out);
+
+/*
+ * Measurement aid for benchmarks: launches one micro-kernel on `stream` and returns the amount of
+ * work it does (bytes read, or floating-point operations), or a negative status.  The caller
+ * times it (events on the stream) to learn what this machine reaches for the patterns the
+ * attention kernels are made of; the rates serve as "achievable" denominators next to the
+ * published peaks.
+ *   MPA_CEIL_STREAM_READ : every byte of buf[0, bytes) once, 16 bytes per lane, non-temporal
+ *                          (rounded down to whole passes of the grid; bytes >= 1 MiB)
+ *   MPA_CEIL_RANDOM_4K   : 16,384 wavefronts each read iters + 1 contiguous 4 KiB chunks at
+ *   MPA_CEIL_RANDOM_16K    pseudo-random chunk positions of buf (16 KiB chunks for the second
+ *                          kind), two chunks in flight; iters even, >= 2
+ *   MPA_CEIL_MFMA_BF16   : 4,096 wavefronts each issue 4 * iters 32x32x16 bf16 matrix
+ *                          instructions from registers (buf and bytes unused)
+ *   buf  : device, 16-byte aligned, read only;   sink : device, 4 bytes, practically never written
+ * Errors: INVALID_ARG, HIP.
+ */
+enum { MPA_CEIL_STREAM_READ = 1, MPA_CEIL_RANDOM_4K = 2, MPA_CEIL_RANDOM_16K = 3, MPA_CEIL_MFMA_BF16 = 4 };
+int64_t mpa_ceiling_launch(int32_t kind, const void *buf, size_t bytes, int32_t iters, void *sink,
+                           void *stream);
 
 /*
  * Host-only view of the work decomposition of a batch (no HIP call; usable without a GPU).

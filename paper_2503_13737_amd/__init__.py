@@ -32,12 +32,14 @@ MPA_OPT_PROFILE_EVERY = 7
 MPA_OPT_STAGING_TIMEOUT_MS = 8
 MPA_OPT_TEST_STUCK_UPLOAD = 9
 MPA_OPT_TILE_MODE = 10
+MPA_OPT_PROFILE_REPEAT = 11
 MPA_STATIC_SCRATCH_BYTES = 64 << 20
+MPA_CEIL_STREAM_READ, MPA_CEIL_RANDOM_4K, MPA_CEIL_RANDOM_16K, MPA_CEIL_MFMA_BF16 = 1, 2, 3, 4
 
 EXPORTS = [
     "mpa_create", "mpa_destroy", "mpa_set_option", "mpa_last_hip_error", "mpa_status_string",
     "mpa_workspace_bytes_for_batch", "mpa_workspace_bytes", "mpa_kv_append", "mpa_copy_blocks", "mpa_append_and_attend",
-    "mpa_mixed_paged_attention", "mpa_mixed_paged_attention_static", "mpa_plan_describe", "mpa_profile_enable", "mpa_profile_read",
+    "mpa_mixed_paged_attention", "mpa_mixed_paged_attention_static", "mpa_plan_describe", "mpa_profile_enable", "mpa_profile_read", "mpa_ceiling_launch",
     "mpa_sched_create", "mpa_sched_destroy", "mpa_sched_add_request", "mpa_sched_add_offline_request", "mpa_sched_next_batch",
     "mpa_sched_batch_arrays", "mpa_sched_batch_swaps", "mpa_sched_complete", "mpa_sched_live_requests",
 ]
@@ -110,6 +112,8 @@ def load() -> ctypes.CDLL:
         lib.mpa_profile_enable.restype = ctypes.c_int
         lib.mpa_profile_read.argtypes = [vp, vp, i32, vp]
         lib.mpa_profile_read.restype = ctypes.c_int
+        lib.mpa_ceiling_launch.argtypes = [i32, vp, sz, i32, vp, vp]
+        lib.mpa_ceiling_launch.restype = i64
         lib.mpa_plan_describe.argtypes = [vp, vp, vp, i32, vp, i64, vp]
         lib.mpa_plan_describe.restype = i64
         f64 = ctypes.c_double
@@ -133,6 +137,14 @@ def load() -> ctypes.CDLL:
         lib.mpa_sched_live_requests.restype = i32
         _lib = lib
     return _lib
+
+
+def ceiling_launch(kind: int, buf, nbytes: int, iters: int, sink, stream=None) -> int:
+    """One launch of a ceiling micro-kernel (see include/mpa.h); returns its bytes or flops."""
+    work = load().mpa_ceiling_launch(int(kind), _ptr(buf), int(nbytes), int(iters), _ptr(sink), _stream_ptr(stream))
+    if work < 0:
+        raise MpaError(int(work), "mpa_ceiling_launch")
+    return int(work)
 
 
 def status_string(status: int) -> str:

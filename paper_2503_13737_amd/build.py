@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmpa.so")
-SOURCES = ["kernels.hip", "planner.cpp", "api.cpp", "sched.cpp"]
+SOURCES = ["kernels.hip", "ceilings.hip", "planner.cpp", "api.cpp", "sched.cpp"]
 FLAGS = [
     "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

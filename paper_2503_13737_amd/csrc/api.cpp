@@ -78,6 +78,7 @@ struct mpa_ctx {
     std::vector<hipEvent_t> prof_events;  // start/stop pairs
     int32_t prof_used = 0;                // pairs recorded in the current series
     int32_t prof_every = 1;               // MPA_OPT_PROFILE_EVERY
+    int32_t prof_repeat = 1;              // MPA_OPT_PROFILE_REPEAT
     int64_t prof_calls = 0;               // attention calls since profiling was enabled
     std::mutex mu;
 };
@@ -161,6 +162,7 @@ int mpa_profile_read(mpa_ctx *ctx, float *ms, int32_t cap, int32_t *n_out)
     for (int32_t i = 0; i < n; ++i) {
         hipError_t rc = hipEventSynchronize(ctx->prof_events[2 * i + 1]);
         if (rc == hipSuccess) rc = hipEventElapsedTime(&ms[i], ctx->prof_events[2 * i], ctx->prof_events[2 * i + 1]);
+        if (rc == hipSuccess) ms[i] /= (float)ctx->prof_repeat;
         if (rc != hipSuccess) {
             ctx->last_hip = (int)rc;
             return MPA_ERR_HIP;
@@ -196,6 +198,10 @@ int mpa_set_option(mpa_ctx *ctx, int32_t option, int64_t value)
     case MPA_OPT_PP_TEAM_MIN_STEPS:
         if (value < 0) return MPA_ERR_INVALID_ARG;
         ctx->opt.pp_team_min_steps = value;
+        return MPA_OK;
+    case MPA_OPT_PROFILE_REPEAT:
+        if (value < 1 || value > 1024) return MPA_ERR_INVALID_ARG;
+        ctx->prof_repeat = (int32_t)value;
         return MPA_OK;
     case MPA_OPT_TILE_MODE:
         if (value > 2) return MPA_ERR_INVALID_ARG;
@@ -466,6 +472,13 @@ int attend(mpa_ctx *ctx, const AppendArgs *app, const void *q, const void *k_cac
     if (prof && (e = hipEventRecord(ctx->prof_events[2 * ctx->prof_used], s)) != hipSuccess) return fail(e);
     int he = launch_attention(p, ctx->cfg.head_dim, ctx->cfg.dtype == MPA_FP16, stream);
     if (he != 0) return fail((hipError_t)he);
+    // A timed call may launch the kernel several times back to back between its two events (the
+    // launch only reads its inputs and rewrites the same outputs and partial results), so that
+    // the events' own cost in the queue is shared by all of them.
+    for (int32_t r = 1; prof && r < ctx->prof_repeat; ++r) {
+        he = launch_attention(p, ctx->cfg.head_dim, ctx->cfg.dtype == MPA_FP16, stream);
+        if (he != 0) return fail((hipError_t)he);
+    }
     if (prof) {
         if ((e = hipEventRecord(ctx->prof_events[2 * ctx->prof_used + 1], s)) != hipSuccess) return fail(e);
         ++ctx->prof_used;

@@ -385,6 +385,46 @@ def config_gqa_decode() -> Batch:
     return make_batch("gqa-64q-8kv-decode", s, 64, 128, 16, nb, np.ones(64, dtype=np.int64), ctx, Hkv=8)
 
 
+HELD_OUT = ("fwd768-13b", "fwd1280-13b", "fwd1280-12h", "fwd768-24h", "small-chunks-13b", "two-long-13b")
+
+
+def held_out(name: str) -> Batch:
+    """Scheduler-shaped batches that no planner constant was fitted on (not among the benchmark's
+    five configs): forward sizes of the paper's two pivot values, 768 and 1280 tokens (Sec. 3.1),
+    made of several dynamic chunks of unequal lengths that start anywhere in their prompts
+    (Sec. 4.2) next to generation rows; 13B-shaped layers (40 heads) and 12- and 24-head shares of a
+    96-head layer."""
+    i = HELD_OUT.index(name)
+    s = config_seed(20 + i)
+    if name == "fwd768-13b":        # 650 prompt tokens in three chunks + 118 generation rows
+        H, chunks = 40, [(300, 1000), (200, 0), (150, 3500)]
+        ctx_tg = uniform_ints(118, 256, 4096, s * 4 + 2)
+    elif name == "fwd1280-13b":     # one long prompt under way, three short ones, 50 generation rows
+        H, chunks = 40, [(1000, 6000), (100, 0), (90, 700), (40, 40)]
+        ctx_tg = uniform_ints(50, 128, 8192, s * 4 + 2)
+    elif name == "fwd1280-12h":     # a 12-head share: long priors, lognormal generation contexts
+        H, chunks = 12, [(640, 9000), (400, 0), (200, 20000)]
+        z = standard_normals(40, s * 4 + 2)
+        ctx_tg = np.clip(np.rint(np.exp(math.log(2048.0) + 1.0 * z)), 1, 16384).astype(np.int64)
+    elif name == "fwd768-24h":      # a 24-head share: eight chunks of about 90 tokens
+        H = 24
+        lens = uniform_ints(8, 60, 120, s * 4 + 1)
+        chunks = list(zip(lens.tolist(), uniform_ints(8, 0, 8000, s * 4 + 3).tolist()))
+        ctx_tg = uniform_ints(768 - int(lens.sum()), 512, 4096, s * 4 + 2)
+    elif name == "small-chunks-13b":   # prompts only: sixteen chunks of 20-200 tokens
+        H = 40
+        lens = uniform_ints(16, 20, 200, s * 4 + 1)
+        chunks = list(zip(lens.tolist(), uniform_ints(16, 0, 6000, s * 4 + 3).tolist()))
+        ctx_tg = np.zeros(0, dtype=np.int64)
+    else:                           # two long prompts' chunks in one batch (urgent ones are not held back)
+        H, chunks = 40, [(768, 12000), (512, 30000)]
+        ctx_tg = uniform_ints(64, 1024, 6000, s * 4 + 2)
+    ql = np.concatenate([[c[0] for c in chunks], np.ones(ctx_tg.size, dtype=np.int64)]).astype(np.int64)
+    ctx = np.concatenate([[c[0] + c[1] for c in chunks], ctx_tg]).astype(np.int64)
+    nb = int(((ctx + 15) // 16).sum()) + 64
+    return make_batch("held-" + name, s, H, 128, 16, nb, ql, ctx)
+
+
 CFG5_PROMPT = 100_000
 CFG5_CHUNK = 2048
 CFG5_ITERS = (CFG5_PROMPT + CFG5_CHUNK - 1) // CFG5_CHUNK  # 49
