@@ -541,7 +541,7 @@ def main():
 
     # a pair of timing events costs the queue about ten microseconds, so the kernel is timed in every
     # fourth step of the timed region: 1/4 of the steps carry them
-    every = 4 if args.steps >= 40 else 1
+    every = 4 if args.steps >= 16 else 1
     wall, attn_ms = time_kernel(dw, dw.step, args.steps, args.warmup, every)
     ms_per_step = wall * 1e3 / args.steps
     tokens_per_s = b.T * args.steps / wall

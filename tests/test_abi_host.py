@@ -200,3 +200,29 @@ def test_an_upload_that_never_reports_back_fails_the_call_before_anything_is_tou
                                    0.0, fake, fake, 1 << 20, None)
     assert rc == mpa.MPA_ERR_HIP and lib.mpa_last_hip_error(c._h) == HIP_ERROR_NOT_READY
     c.close()   # a planted slot is ordinary memory and is freed
+
+
+def test_options_and_measurement_aid_reject_bad_arguments_without_gpu():
+    lib = mpa.load()
+    c = mpa.Context(4, 64)
+    for opt, bad in ((mpa.MPA_OPT_TILE_MODE, 3), (mpa.MPA_OPT_PROFILE_REPEAT, 0), (mpa.MPA_OPT_PROFILE_REPEAT, 5000),
+                     (mpa.MPA_OPT_STAGING_TIMEOUT_MS, 0), (mpa.MPA_OPT_PLAN_CACHE, 3), (99, 1)):
+        with pytest.raises(mpa.MpaError):
+            c.set_option(opt, bad)
+    for opt, good in ((mpa.MPA_OPT_TILE_MODE, 2), (mpa.MPA_OPT_TILE_MODE, 0), (mpa.MPA_OPT_PROFILE_REPEAT, 8),
+                      (mpa.MPA_OPT_STAGING_TIMEOUT_MS, 100)):
+        c.set_option(opt, good)
+    # the work-group shape changes the tiles of the plan, not the coverage
+    b = W.config1()
+    c.set_option(mpa.MPA_OPT_TILE_MODE, 2)
+    items, counts = c.plan_describe(b.chunk_starts, b.context_lens)
+    check_plan_covers(b, items, counts, b.H)
+    fake = ctypes.c_void_p(0x1000)
+    call = lib.mpa_ceiling_launch
+    assert call(mpa.MPA_CEIL_STREAM_READ, fake, 1 << 30, 0, None, None) == mpa.MPA_ERR_INVALID_ARG      # no sink
+    assert call(mpa.MPA_CEIL_STREAM_READ, None, 1 << 30, 0, fake, None) == mpa.MPA_ERR_INVALID_ARG      # no buffer
+    assert call(mpa.MPA_CEIL_STREAM_READ, fake, 1000, 0, fake, None) == mpa.MPA_ERR_INVALID_ARG         # too small
+    assert call(mpa.MPA_CEIL_RANDOM_4K, fake, 1 << 30, 3, fake, None) == mpa.MPA_ERR_INVALID_ARG        # odd chunk count
+    assert call(mpa.MPA_CEIL_RANDOM_16K, fake, 1 << 16, 4, fake, None) == mpa.MPA_ERR_INVALID_ARG       # fewer than 64 chunks
+    assert call(mpa.MPA_CEIL_MFMA_BF16, None, 0, 0, fake, None) == mpa.MPA_ERR_INVALID_ARG              # no iterations
+    assert call(17, fake, 1 << 30, 2, fake, None) == mpa.MPA_ERR_INVALID_ARG
