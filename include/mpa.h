@@ -286,11 +286,15 @@ int mpa_profile_read(mpa_ctx *ctx, float *ms, int32_t cap, int32_t *n_out);
  *   MPA_CEIL_RANDOM_16K    pseudo-random chunk positions of buf (16 KiB chunks for the second
  *                          kind), two chunks in flight; iters even, >= 2
  *   MPA_CEIL_MFMA_BF16   : 4,096 wavefronts each issue 4 * iters 32x32x16 bf16 matrix
- *                          instructions from registers (buf and bytes unused)
+ *                          instructions from registers (buf and bytes unused); operands with few
+ *                          mantissa bits set
+ *   MPA_CEIL_MFMA_BF16_NOISY : the same with pseudo-random operands of unit scale (the chip
+ *                          sustains a lower clock under them)
  *   buf  : device, 16-byte aligned, read only;   sink : device, 4 bytes, practically never written
  * Errors: INVALID_ARG, HIP.
  */
-enum { MPA_CEIL_STREAM_READ = 1, MPA_CEIL_RANDOM_4K = 2, MPA_CEIL_RANDOM_16K = 3, MPA_CEIL_MFMA_BF16 = 4 };
+enum { MPA_CEIL_STREAM_READ = 1, MPA_CEIL_RANDOM_4K = 2, MPA_CEIL_RANDOM_16K = 3, MPA_CEIL_MFMA_BF16 = 4,
+       MPA_CEIL_MFMA_BF16_NOISY = 5 };
 int64_t mpa_ceiling_launch(int32_t kind, const void *buf, size_t bytes, int32_t iters, void *sink,
                            void *stream);
 

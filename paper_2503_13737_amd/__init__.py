@@ -34,7 +34,7 @@ MPA_OPT_TEST_STUCK_UPLOAD = 9
 MPA_OPT_TILE_MODE = 10
 MPA_OPT_PROFILE_REPEAT = 11
 MPA_STATIC_SCRATCH_BYTES = 64 << 20
-MPA_CEIL_STREAM_READ, MPA_CEIL_RANDOM_4K, MPA_CEIL_RANDOM_16K, MPA_CEIL_MFMA_BF16 = 1, 2, 3, 4
+MPA_CEIL_STREAM_READ, MPA_CEIL_RANDOM_4K, MPA_CEIL_RANDOM_16K, MPA_CEIL_MFMA_BF16, MPA_CEIL_MFMA_BF16_NOISY = 1, 2, 3, 4, 5
 
 EXPORTS = [
     "mpa_create", "mpa_destroy", "mpa_set_option", "mpa_last_hip_error", "mpa_status_string",

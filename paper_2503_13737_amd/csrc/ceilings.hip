@@ -77,13 +77,26 @@ random_chunk_kernel(const u32x4 *__restrict__ p, uint64_t n_chunks, int32_t chun
 }
 
 // Four independent accumulators per wavefront, `iters` rounds of four 32x32x16 bf16 products.
+// Operands: a smooth pattern with few mantissa bits set, or (noisy) pseudo-random values of unit
+// scale with full mantissas, like the q/K/V of the benchmark batches -- the second kind makes the
+// matrix pipe draw more power, and the clock the chip sustains under it is lower.
 __global__ void __launch_bounds__(256)
-mfma_loop_kernel(float *sink, int32_t iters)
+mfma_loop_kernel(float *sink, int32_t iters, int32_t noisy)
 {
     bf16x8 a, b;
     for (int i = 0; i < 8; ++i) {
         a[i] = (__bf16)(threadIdx.x * 0.001f + i);
         b[i] = (__bf16)(i * 0.5f);
+    }
+    if (noisy) {
+        for (int i = 0; i < 8; ++i) {
+            const uint64_t r = mix(((uint64_t)blockIdx.x * 256 + threadIdx.x) * 8 + i);
+            // two uniforms in (-1, 1) with 23 random bits each, summed: unit-scale, full mantissa after rounding
+            const float u = (float)(int32_t)(r & 0xFFFFFF) * (1.f / 8388608.f) - 1.f;
+            const float v = (float)(int32_t)((r >> 24) & 0xFFFFFF) * (1.f / 8388608.f) - 1.f;
+            a[i] = (__bf16)(u + v);
+            b[i] = (__bf16)(u - v);
+        }
     }
     f32x16 c[4];
     for (int k = 0; k < 4; ++k)
@@ -128,9 +141,11 @@ extern "C" int64_t mpa_ceiling_launch(int32_t kind, const void *buf, size_t byte
         work = (int64_t)kWgs * 4 * ((int64_t)iters + 1) * kib * 1024;   // chunks 0 .. iters are read
         break;
     }
-    case MPA_CEIL_MFMA_BF16: {
+    case MPA_CEIL_MFMA_BF16:
+    case MPA_CEIL_MFMA_BF16_NOISY: {
         if (iters < 1) return MPA_ERR_INVALID_ARG;
-        hipLaunchKernelGGL(mfma_loop_kernel, dim3(kMfmaWgs), dim3(256), 0, s, (float *)sink, iters);
+        hipLaunchKernelGGL(mfma_loop_kernel, dim3(kMfmaWgs), dim3(256), 0, s, (float *)sink, iters,
+                           kind == MPA_CEIL_MFMA_BF16_NOISY ? 1 : 0);
         work = (int64_t)kMfmaWgs * 4 * (int64_t)iters * 4 * (2ll * 32 * 32 * 16);
         break;
     }

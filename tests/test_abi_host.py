@@ -225,4 +225,6 @@ def test_options_and_measurement_aid_reject_bad_arguments_without_gpu():
     assert call(mpa.MPA_CEIL_RANDOM_4K, fake, 1 << 30, 3, fake, None) == mpa.MPA_ERR_INVALID_ARG        # odd chunk count
     assert call(mpa.MPA_CEIL_RANDOM_16K, fake, 1 << 16, 4, fake, None) == mpa.MPA_ERR_INVALID_ARG       # fewer than 64 chunks
     assert call(mpa.MPA_CEIL_MFMA_BF16, None, 0, 0, fake, None) == mpa.MPA_ERR_INVALID_ARG              # no iterations
+    assert call(mpa.MPA_CEIL_MFMA_BF16_NOISY, None, 0, 0, fake, None) == mpa.MPA_ERR_INVALID_ARG        # no iterations
+    assert call(mpa.MPA_CEIL_MFMA_BF16_NOISY + 1, None, 0, 4, fake, None) == mpa.MPA_ERR_INVALID_ARG    # no such kind
     assert call(17, fake, 1 << 30, 2, fake, None) == mpa.MPA_ERR_INVALID_ARG
