@@ -109,6 +109,17 @@ enum {
     MPA_OPT_TEST_STUCK_UPLOAD = 9, /* value 1, for tests of that error path: the staging buffer the
                                     next call would use is marked as still being read by an upload
                                     that never reports back (no GPU involved)                    */
+    MPA_OPT_FUSE_APPEND = 12,    /* 1 = mpa_append_and_attend stores the iteration's K/V from inside the
+                                    attention launch (extra work-groups at the end of its grid) instead
+                                    of in a launch before it, and every row takes the keys of its own
+                                    sequence's new positions -- the chunk's own tokens, a generation
+                                    row's own token -- from k_new / v_new, since the cache slots are
+                                    being written meanwhile (Sec. 2.2: the K/V of a step's tokens are
+                                    computed, stored in the KVC and used by that step).  One launch
+                                    fewer per layer; same results bit for bit provided no token of the
+                                    batch has a negative slot (such a token is still attended to here,
+                                    whereas the two-call form reads whatever its cache slot holds).
+                                    0 (default) = the append precedes the attention launch            */
     MPA_OPT_PLAN_CACHE = 6       /* 1 (default) = a call whose chunk_starts / context_lens equal
                                     the previous call's reuses its work list (the layers of one
                                     model iteration all present the same batch); 0 = plan anew
@@ -307,7 +318,8 @@ int64_t mpa_ceiling_launch(int32_t kind, const void *buf, size_t bytes, int32_t 
  * heads on the matrix-core body, 2 = one generation row for the query heads of K/V head
  * kind >> 8 on the matrix-core body (grouped K/V heads, group size >= 4).  Bit 8 of a tile's kind
  * is set when no other tile of the batch reads its keys (and no K/V head is shared): its K/V is
- * then fetched as data that is read once.
+ * then fetched as data that is read once; kind >> 9 of a tile is its first row counted from the
+ * first row of its chunk.
  * counts (optional, 4 int32): {matrix-core items, row items, merge rows, partial rows}.
  */
 int64_t mpa_plan_describe(const mpa_ctx *ctx, const int32_t *chunk_starts,

@@ -33,6 +33,7 @@ MPA_OPT_STAGING_TIMEOUT_MS = 8
 MPA_OPT_TEST_STUCK_UPLOAD = 9
 MPA_OPT_TILE_MODE = 10
 MPA_OPT_PROFILE_REPEAT = 11
+MPA_OPT_FUSE_APPEND = 12
 MPA_STATIC_SCRATCH_BYTES = 64 << 20
 MPA_CEIL_STREAM_READ, MPA_CEIL_RANDOM_4K, MPA_CEIL_RANDOM_16K, MPA_CEIL_MFMA_BF16, MPA_CEIL_MFMA_BF16_NOISY = 1, 2, 3, 4, 5
 

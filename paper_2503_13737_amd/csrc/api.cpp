@@ -72,6 +72,7 @@ struct mpa_ctx {
     bool plan_valid = false;         // cleared by mpa_set_option
     bool plan_cache = true;
     bool keep_upload = false;            // MPA_OPT_PLAN_CACHE == 2
+    bool fuse_append = false;            // MPA_OPT_FUSE_APPEND
     const void *uploaded_ws = nullptr;   // where, and on which stream, the cached plan's work list was last uploaded
     const void *uploaded_stream = nullptr;
     bool uploaded_valid = false;
@@ -202,6 +203,10 @@ int mpa_set_option(mpa_ctx *ctx, int32_t option, int64_t value)
     case MPA_OPT_PROFILE_REPEAT:
         if (value < 1 || value > 1024) return MPA_ERR_INVALID_ARG;
         ctx->prof_repeat = (int32_t)value;
+        return MPA_OK;
+    case MPA_OPT_FUSE_APPEND:
+        if (value > 1) return MPA_ERR_INVALID_ARG;
+        ctx->fuse_append = value == 1;
         return MPA_OK;
     case MPA_OPT_TILE_MODE:
         if (value > 2) return MPA_ERR_INVALID_ARG;
@@ -383,7 +388,9 @@ int attend(mpa_ctx *ctx, const AppendArgs *app, const void *q, const void *k_cac
                                ctx->uploaded_ws == workspace && ctx->uploaded_stream == stream;
     hipStream_t s = (hipStream_t)stream;
     hipError_t e;
-    if (list_in_place && app) {
+    // the append inside the attention launch: no append kernel of its own, in either branch below
+    const bool fused = app && ctx->fuse_append && plan.fusable;
+    if (list_in_place && app && !fused) {
         int ae = launch_kv_append(app->k_new, app->v_new, app->slot_map, num_tokens, ctx->cfg.num_kv_heads,
                                   ctx->cfg.head_dim, ctx->cfg.block_size, app->k_cache, app->v_cache, stream);
         if (ae != 0) return fail((hipError_t)ae);
@@ -429,7 +436,7 @@ int attend(mpa_ctx *ctx, const AppendArgs *app, const void *q, const void *k_cac
         write_list(h);
         if (list_bytes % 16 != 0) return MPA_ERR_WORKSPACE;   // the plan pads its sections
         st.ticket = ctx->next_ticket++;
-        const int ue = app ? launch_append_upload(app->k_new, app->v_new, app->slot_map, num_tokens, ctx->cfg.num_kv_heads,
+        const int ue = app && !fused ? launch_append_upload(app->k_new, app->v_new, app->slot_map, num_tokens, ctx->cfg.num_kv_heads,
                                                   ctx->cfg.head_dim, ctx->cfg.block_size, app->k_cache, app->v_cache, h,
                                                   workspace, list_bytes, const_cast<uint64_t *>(st.flag()), st.ticket, stream)
                            : launch_upload(h, workspace, list_bytes, const_cast<uint64_t *>(st.flag()), st.ticket, stream);
@@ -466,6 +473,12 @@ int attend(mpa_ctx *ctx, const AppendArgs *app, const void *q, const void *k_cac
     p.teams = reinterpret_cast<const TeamRef *>(ws + plan.off_teams);
     p.progress = reinterpret_cast<uint32_t *>(ws + plan.off_progress);
     p.wide = plan.wide ? 1 : 0;
+    p.k_new = fused ? static_cast<const uint16_t *>(app->k_new) : nullptr;
+    p.v_new = fused ? static_cast<const uint16_t *>(app->v_new) : nullptr;
+    p.slot_map = fused ? app->slot_map : nullptr;
+    p.n_new = fused ? num_tokens : 0;
+    p.block_size = ctx->cfg.block_size;
+    p.n_append_wgs = 0;   // the launcher counts them
 
     const bool prof = (size_t)(2 * ctx->prof_used + 1) < ctx->prof_events.size() &&
                       ctx->prof_calls++ % ctx->prof_every == 0;

@@ -263,6 +263,26 @@ __device__ __forceinline__ void issue_loads(KvRegs<D> &r, const uint16_t *__rest
     for (int i = 0; i < RowCfg<D>::NL; ++i) r.v[i] = __builtin_nontemporal_load(vp + i * 64);
 }
 
+// The same loads for the page that holds the row's own position when this iteration's K/V is not
+// in the cache yet (append inside the launch): the lanes of that token (in-page index `slot`) read
+// their 16 bytes from the new rows nk / nv, every other lane from the cache as usual.
+template <int D>
+__device__ __forceinline__ void issue_loads_own(KvRegs<D> &r, const uint16_t *__restrict__ k_cache,
+                                                const uint16_t *__restrict__ v_cache, int32_t page, int32_t HK,
+                                                int32_t kv_head, int32_t page_shift, int lane, const u32x4 *nk,
+                                                const u32x4 *nv, int slot)
+{
+    using C = RowCfg<D>;
+    const size_t tile = page_offset<D>(page, HK, kv_head, page_shift);
+    const u32x4 *kp = reinterpret_cast<const u32x4 *>(k_cache + tile) + lane;
+    const u32x4 *vp = reinterpret_cast<const u32x4 *>(v_cache + tile) + lane;
+    const int c = lane % C::LPR, sub = lane / C::LPR;
+#pragma unroll
+    for (int i = 0; i < C::NL; ++i) r.k[i] = __builtin_nontemporal_load(i * C::TPL + sub == slot ? nk + c : kp + i * 64);
+#pragma unroll
+    for (int i = 0; i < C::NL; ++i) r.v[i] = __builtin_nontemporal_load(i * C::TPL + sub == slot ? nv + c : vp + i * 64);
+}
+
 template <class E, int D, bool MASKED>
 __device__ __forceinline__ void consume(const KvRegs<D> &r, const float (&qf)[8], float &m,
                                         float &l, float (&acc)[8], int32_t tok0, int32_t limit,
@@ -344,6 +364,15 @@ __device__ __forceinline__ void row_body(const AttnParams &p, const WorkItem &it
     const int32_t nblk = (limit - it.kv_begin + kPage - 1) / kPage;
     const int32_t *tab = p.block_table + (size_t)it.seq * p.table_stride;
     const int32_t page_shift = p.page_shift;
+    // Append inside the launch: the row's own token (position q_pos0, the last key of the range that
+    // reaches it) is not in the cache yet; its K/V is row q_row0 of k_new / v_new.
+    const bool own_new = p.k_new != nullptr && it.kv_end > it.q_pos0;
+    const u32x4 *own_k = nullptr, *own_v = nullptr;
+    if (own_new) {
+        const size_t el = ((size_t)it.q_row0 * HK + kv_head) * D;
+        own_k = reinterpret_cast<const u32x4 *>(p.k_new + el);
+        own_v = reinterpret_cast<const u32x4 *>(p.v_new + el);
+    }
 
     for (int32_t g0 = 0; g0 < nblk; g0 += 64) {
         const int32_t n = min(64, nblk - g0);
@@ -357,15 +386,21 @@ __device__ __forceinline__ void row_body(const AttnParams &p, const WorkItem &it
         };
         // NS register sets rotate: NS-1 blocks (8 KiB each at D=128) are in flight while one is consumed
         KvRegs<D> r[NS];
+        auto issue = [&](KvRegs<D> &rr, int jj) {   // page g0 + jj of the range
+            if (own_new && g0 + jj == nblk - 1)
+                issue_loads_own<D>(rr, p.k_cache, p.v_cache, blk_of(jj), HK, kv_head, page_shift, lane, own_k, own_v,
+                                   it.q_pos0 % kPage);
+            else
+                issue_loads<D>(rr, p.k_cache, p.v_cache, blk_of(jj), HK, kv_head, page_shift, lane);
+        };
 #pragma unroll
         for (int s = 0; s < NS - 1; ++s)
-            if (s < n) issue_loads<D>(r[s], p.k_cache, p.v_cache, blk_of(s), HK, kv_head, page_shift, lane);
+            if (s < n) issue(r[s], s);
         for (int j = 0; j < n; j += NS) {
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
                 if (j + s < n) {
-                    if (j + s + NS - 1 < n)
-                        issue_loads<D>(r[(s + NS - 1) % NS], p.k_cache, p.v_cache, blk_of(j + s + NS - 1), HK, kv_head, page_shift, lane);
+                    if (j + s + NS - 1 < n) issue(r[(s + NS - 1) % NS], j + s + NS - 1);
                     step(r[s], j + s);
                 }
             }
@@ -461,6 +496,11 @@ struct TileNext {
     uint32_t voff[TileCfg<D, WAVES>::NL]; // same with the V swizzle
     uint32_t lds_w;                       // LDS address of the wavefront's 16 rows in the K tile of buffer 0
     bool stream;                          // K/V of this item are read once (see load_to_lds_16)
+    // Append inside the launch: rows of the tile from position `new_begin` of the sequence on are not in
+    // the cache yet.  nk / nv: where the page that holds the wavefront's rows would start in k_new /
+    // v_new (token rows there are new_extra bytes further apart than in a cache page).
+    const char *nk, *nv;
+    uint32_t new_extra;
 };
 
 // 16 bytes per lane from base + off (base wavefront-uniform, in scalar registers) straight into
@@ -496,9 +536,10 @@ __device__ __forceinline__ void wait_loads_to_lds() { asm volatile("s_waitcnt vm
 // rows at or past it (all rows if !have_block) are not loaded; the V rows among them are zeroed
 // instead (their scores are masked, but 0 * NaN would poison the PV product), the K rows may hold
 // anything.  Nothing is waited for here.
+// Rows from new_from on (tile row index; none by default) come from n.nk / n.nv instead.
 template <int D, int WAVES = kWaves>
 __device__ __forceinline__ void tile_load(const TileNext<D, WAVES> &n, uint32_t buf_off, bool have_block, int32_t keys_valid,
-                                          int wave, int lane)
+                                          int wave, int lane, int32_t new_from = 0x7FFFFFFF)
 {
     using C = TileCfg<D, WAVES>;
     typedef __attribute__((address_space(3))) u32x4 lds_u32x4;
@@ -506,7 +547,11 @@ __device__ __forceinline__ void tile_load(const TileNext<D, WAVES> &n, uint32_t 
     for (int i = 0; i < C::NL; ++i) {
         const int row = wave * C::KPW + i * C::RPL + lane / C::CPR;   // row inside the tile
         const uint32_t dst = n.lds_w + buf_off + i * C::RPL * C::ROW;
-        if (have_block && row < keys_valid) {
+        if (row < keys_valid && row >= new_from) {
+            const uint32_t extra = (uint32_t)(row % kPage) * n.new_extra;
+            load_to_lds_16(n.nk, n.koff[i] + extra, dst, false);
+            load_to_lds_16(n.nv, n.voff[i] + extra, dst + C::K_BYTES, false);
+        } else if (have_block && row < keys_valid) {
             load_to_lds_16(n.gk, n.koff[i], dst, n.stream);
             load_to_lds_16(n.gv, n.voff[i], dst + C::K_BYTES, n.stream);
         } else {
@@ -869,7 +914,31 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
         next.lds_w = __builtin_amdgcn_readfirstlane(lds0 + wave * C::KPW * C::ROW);
         next.gk = next.gv = nullptr;
         next.stream = grouped || (it.kind & kSoloTile) != 0;
+        next.nk = next.nv = nullptr;
+        next.new_extra = (uint32_t)(p.kv_heads * D * 2 - C::ROW);
     }
+    // Append inside the launch: the keys from position new_begin of this sequence on -- the chunk's own
+    // tokens, a generation row's own token -- are not in the cache yet and are loaded from k_new / v_new,
+    // where position pos is row q_row0 + (pos - q_pos0).  A wavefront's rows of a tile lie in one page;
+    // point_new aims nk / nv at where that page would start in the new rows (before their first row if
+    // the page begins with old keys: those lanes do not load from there).
+    const int32_t new_begin = p.k_new == nullptr ? 0x7FFFFFFF : grouped ? it.q_pos0 : it.q_pos0 - (it.kind >> kTileRowShift);
+    const int32_t wave_row0 = __builtin_amdgcn_readfirstlane(wave * C::KPW);
+    auto point_new = [&](int32_t k0_tile) {
+        const int64_t row = (int64_t)it.q_row0 + ((int64_t)k0_tile + (wave_row0 & ~(kPage - 1)) - it.q_pos0);
+        const int64_t bytes = (row * p.kv_heads + kv_head) * (int64_t)(D * 2);
+        const uint64_t ak = reinterpret_cast<uint64_t>(p.k_new) + (uint64_t)bytes, av = reinterpret_cast<uint64_t>(p.v_new) + (uint64_t)bytes;
+        // (wavefront-uniform by construction; the intrinsic returns a signed int: widen its bits, not its value)
+        auto uniform64 = [](uint64_t a) {
+            const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)a);
+            const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(a >> 32));
+            return ((uint64_t)hi << 32) | (uint64_t)lo;
+        };
+        next.nk = reinterpret_cast<const char *>(uniform64(ak));
+        next.nv = reinterpret_cast<const char *>(uniform64(av));
+    };
+    // does the wavefront's share of the tile that starts at key k0_tile reach new keys?
+    auto reaches_new = [&](int32_t k0_tile) { return k0_tile + wave_row0 + C::KPW > new_begin; };
 
     // Pipeline: while step s is computed from LDS buffer s&1, the direct loads of step s+1 fill the
     // other buffer.  That buffer was last read in step s-1, which every wavefront has left, and the
@@ -884,7 +953,12 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
     if constexpr (WAVES == kWaves) {
         const int32_t blk0 = step_block(0);
         point_at(blk0);
-        tile_load<D, WAVES>(next, 0, blk0 >= 0, it.kv_end - it.kv_begin, wave, lane);
+        if (reaches_new(it.kv_begin)) {
+            point_new(it.kv_begin);
+            tile_load<D, WAVES>(next, 0, blk0 >= 0, it.kv_end - it.kv_begin, wave, lane, new_begin - it.kv_begin);
+        } else {
+            tile_load<D, WAVES>(next, 0, blk0 >= 0, it.kv_end - it.kv_begin, wave, lane);
+        }
     } else {
         // ring: the tiles of the first kRingAhead steps
 #pragma unroll
@@ -892,7 +966,13 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
             if (t < nsteps) {
                 const int32_t blk = step_block(t);
                 point_at(blk);
-                tile_load<D, WAVES>(next, t * kBuf, blk >= 0, it.kv_end - it.kv_begin - t * kKvTile, wave, lane);
+                const int32_t k0_t = it.kv_begin + t * kKvTile;
+                if (reaches_new(k0_t)) {
+                    point_new(k0_t);
+                    tile_load<D, WAVES>(next, t * kBuf, blk >= 0, it.kv_end - k0_t, wave, lane, new_begin - k0_t);
+                } else {
+                    tile_load<D, WAVES>(next, t * kBuf, blk >= 0, it.kv_end - k0_t, wave, lane);
+                }
             }
         }
     }
@@ -921,10 +1001,16 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
             if (lane < team.size) mates = progress_load(pace + lane);
         }
         if (more) point_at(blk_n);
-        if (active && blk_n >= 0 && keys_n >= kKvTile && !next.stream) {
+        const bool new_n = more && reaches_new(k0 + kKvTile);
+        if (active && blk_n >= 0 && keys_n >= kKvTile && !next.stream && !new_n) {
             tile_compute<E, D, true, BUFI>(kaddr, vaddr, qf, o, m, l, c2, k0, pos, half, masked, next);
         } else {
-            if (more) tile_load<D, WAVES>(next, (BUFI ^ 1) * kBuf, blk_n >= 0, keys_n, wave, lane);
+            if (new_n) {
+                point_new(k0 + kKvTile);
+                tile_load<D, WAVES>(next, (BUFI ^ 1) * kBuf, blk_n >= 0, keys_n, wave, lane, new_begin - (k0 + kKvTile));
+            } else if (more) {
+                tile_load<D, WAVES>(next, (BUFI ^ 1) * kBuf, blk_n >= 0, keys_n, wave, lane);
+            }
             if (active) tile_compute<E, D, false, BUFI>(kaddr, vaddr, qf, o, m, l, c2, k0, pos, half, masked, next);
         }
         wait_loads_to_lds();
@@ -969,12 +1055,19 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
 #pragma unroll
             for (int db = 0; db < C::DB; ++db) va[db] = vaddr[db] + ring_s;
             if (more) point_at(blk_t);
-            if (active && more && blk_t >= 0 && keys_t >= kKvTile && !next.stream) {
+            const int32_t k0_t = it.kv_begin + t * kKvTile;
+            const bool new_t = more && reaches_new(k0_t);
+            if (active && more && blk_t >= 0 && keys_t >= kKvTile && !next.stream && !new_t) {
                 next.lds_w = lds_w0 + ring_t - kBuf;   // tile_compute aims at "the other buffer" of buffer 0
                 tile_compute<E, D, true, 0, WAVES>(ka, va, qf, o, m, l, c2, k0, pos, half, masked, next);
             } else {
                 next.lds_w = lds_w0;
-                if (more) tile_load<D, WAVES>(next, ring_t, blk_t >= 0, keys_t, wave, lane);
+                if (new_t) {
+                    point_new(k0_t);
+                    tile_load<D, WAVES>(next, ring_t, blk_t >= 0, keys_t, wave, lane, new_begin - k0_t);
+                } else if (more) {
+                    tile_load<D, WAVES>(next, ring_t, blk_t >= 0, keys_t, wave, lane);
+                }
                 if (active) tile_compute<E, D, false, 0, WAVES>(ka, va, qf, o, m, l, c2, k0, pos, half, masked, next);
             }
             ring_s = ring_s + kBuf == kRingBufs * kBuf ? 0u : ring_s + kBuf;
@@ -1114,6 +1207,14 @@ attention_kernel(const AttnParams p)
     }
     const int hg = (H + WAVES - 1) / WAVES;
     const int32_t idx = (int32_t)blockIdx.x - n_tile_wg - p.n_group_items;
+    if (idx >= p.n_row_items * hg) {
+        // the iteration's append (see AttnParams::k_new): nothing in this launch reads these slots
+        append_body((int64_t)(idx - p.n_row_items * hg) * (WAVES * 64) + threadIdx.x, reinterpret_cast<const uint4 *>(p.k_new),
+                    reinterpret_cast<const uint4 *>(p.v_new), p.slot_map, p.n_new, p.kv_heads, D / 8, p.block_size,
+                    reinterpret_cast<uint4 *>(const_cast<uint16_t *>(p.k_cache)),
+                    reinterpret_cast<uint4 *>(const_cast<uint16_t *>(p.v_cache)));
+        return;
+    }
     const int32_t item = p.n_tile_items + p.n_group_items + idx / hg;
     const int head = (idx % hg) * WAVES + wave;
     if (head >= H) return;
@@ -1274,14 +1375,19 @@ int launch_copy_blocks(const void *src_k, const void *src_v, void *dst_k, void *
     return (int)hipGetLastError();
 }
 
-int launch_attention(const AttnParams &p, int32_t D, bool fp16, void *stream)
+int launch_attention(const AttnParams &params, int32_t D, bool fp16, void *stream)
 {
+    AttnParams p = params;
     const int waves = p.wide ? kWideWaves : kWaves;
     const int hg = (p.heads + waves - 1) / waves;
-    const int64_t grid = (int64_t)p.n_tile_wgs + p.n_group_items + (int64_t)p.n_row_items * hg;
+    const int64_t row_wgs = (int64_t)p.n_row_items * hg;
+    // the append's work-groups: one thread per 16 bytes of K (and of V) of the new rows
+    const int64_t append_wgs = p.k_new ? ((int64_t)p.n_new * p.kv_heads * (D / 8) + waves * 64 - 1) / (waves * 64) : 0;
+    const int64_t grid = (int64_t)p.n_tile_wgs + p.n_group_items + row_wgs + append_wgs;
     if (grid == 0) return 0;
     const int64_t units = (int64_t)p.n_tile_items * p.heads + p.n_group_items;
-    if (grid > 0x7FFFFFFF || units > 0x7FFFFFFF) return (int)hipErrorInvalidConfiguration;
+    if (grid > 0x7FFFFFFF || units > 0x7FFFFFFF || row_wgs > 0x7FFFFFFF) return (int)hipErrorInvalidConfiguration;
+    p.n_append_wgs = (int32_t)append_wgs;
     void (*kernel)(const AttnParams);
     if (p.wide)
         kernel = fp16 ? (D == 128 ? attention_kernel<Fp16, 128, kWideWaves> : attention_kernel<Fp16, 64, kWideWaves>)

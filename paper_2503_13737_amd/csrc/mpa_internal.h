@@ -35,6 +35,11 @@ enum ItemKind : int32_t { kRowItem = 0, kTileItem = 1, kGroupItem = 2 };
 // only the chunk's last tile reaches) and no other head does (every query head has its own K/V
 // head), so its K/V passes through the caches once.
 constexpr int32_t kSoloTile = 1 << 8;
+// Above it, the kind of a tile item carries the tile's first row counted from the first row of its
+// chunk: q_pos0 minus that is the first position of the sequence whose K/V arrives with this very
+// iteration (needed when the append runs inside the attention launch).
+constexpr int kTileRowShift = 9;
+constexpr int32_t kTileRowMax = 1 << (31 - kTileRowShift);
 
 // One unit of work.  A tile item is executed by one work-group per head; a row item by one
 // wavefront per head (a work-group covers kWaves consecutive heads).
@@ -96,6 +101,7 @@ struct Plan {
     int32_t n_row_items = 0;
     int32_t n_tile_wgs = 0;       // work-groups that share the n_tile_items * heads tile units
     bool wide = false;            // work-groups of kWideWaves wavefronts, tiles of kWideTileRows rows
+    bool fusable = true;          // the append may run inside the attention launch (see AttnParams::k_new)
     int64_t part_rows = 0;
 
     // workspace layout (byte offsets)
@@ -133,6 +139,15 @@ struct AttnParams {
     const TeamRef *teams;   // [n_tile_items]
     uint32_t *progress;
     int32_t wide;           // Plan::wide
+    // Append inside the launch (k_new != nullptr): the iteration's new K/V [n_new, kv_heads, D] is
+    // stored to the caches by n_append_wgs extra work-groups at the end of the grid, and every reader
+    // takes the keys of its own sequence's new positions from k_new / v_new instead of the cache.
+    const uint16_t *k_new;
+    const uint16_t *v_new;
+    const int64_t *slot_map;
+    int32_t n_new;
+    int32_t block_size;
+    int32_t n_append_wgs;
 };
 
 // The entry point that allocates nothing keeps work list and partial results in a device array of

@@ -249,6 +249,7 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
     plan->items.clear();
     plan->merge.clear();
     plan->teams.clear();
+    plan->fusable = !opt.pp_rowstream;   // a prompt row on the streaming body would need several new keys
     plan->progress_words = 0;
     plan->part_rows = 0;
     if (S < 0) return MPA_ERR_BAD_BATCH;
@@ -357,7 +358,9 @@ int build_plan(const PlanOptions &opt, const int32_t *cs, const int32_t *ctx, in
             const int64_t len_seq = ceil_div(ceil_div((int64_t)ctx[i], n_seq), kKvTile) * kKvTile;
             for (int32_t r0 = 0; r0 < q_len; r0 += (int32_t)kTileRows) {
                 int32_t nr = (int32_t)std::min<int64_t>(kTileRows, q_len - r0);
-                emit(tiles, kTileItem, i, cs[i] + r0, nr, prior + r0, len_seq, kKvTile, true);
+                if (r0 >= kTileRowMax) plan->fusable = false;   // (a chunk of 4 M rows)
+                emit(tiles, kTileItem | (r0 < kTileRowMax ? r0 << kTileRowShift : 0), i, cs[i] + r0, nr, prior + r0, len_seq,
+                     kKvTile, true);
             }
         }
     }

@@ -238,3 +238,71 @@ def test_append_and_attend_equals_the_two_calls(mpa, make):
     assert_close(outs[0][0], ref, b.name, dtype=b.dtype)
     kc, vc = oracle_run(b)[1:]
     assert np.array_equal(outs[2][1], kc) and np.array_equal(outs[2][2], vc)
+
+
+INSIDE_CASES = {
+    # chunks that start inside a page / on a page / at position 0, chunks shorter than a page, generation
+    # rows whose own token is first / last / in the middle of its page
+    "cfg1": lambda: W.config1(),
+    "cfg1-fp16": lambda: W.config1(dtype="fp16"),
+    "ragged-pages": lambda: W.make_batch("inside-ragged", 71, 4, 128, 16, 700,
+                                         [600, 300, 5, 130, 64, 1, 1, 1, 1, 1], [1500, 300, 21, 130 + 47, 64 + 1024, 1, 16, 17, 700, 2000]),
+    "ragged-gqa-bs32": lambda: W.random_ragged(7100, H=8, D=128, bs=32, n_pp=3, n_tg=5, max_q=300, max_prior=900, max_ctx=1500, Hkv=2),
+    "group-items-bs128": lambda: W.make_batch("inside-groups", 72, 16, 128, 128, 40, [1, 1, 1, 200], [1, 129, 1000, 333], Hkv=2),
+    "d64": lambda: W.make_batch("inside-d64", 73, 4, 64, 16, 300, [257, 1, 1, 33], [257 + 30, 100, 1, 33 + 640]),
+}
+
+
+@pytest.mark.parametrize("case", sorted(INSIDE_CASES))
+@pytest.mark.parametrize("opts", [{}, {"MPA_OPT_TILE_MODE": 2}, {"MPA_OPT_PP_SPLIT_TOKENS": 128, "MPA_OPT_TG_SPLIT_BLOCKS": 2}],
+                         ids=["auto", "wide", "split"])
+def test_append_inside_the_attention_launch(mpa, case, opts):
+    """MPA_OPT_FUSE_APPEND: the iteration's K/V stored by work-groups of the attention launch itself while
+    every row reads its own sequence's new keys from k_new / v_new.  The cache slots of the new tokens hold
+    NaN patterns when the launch starts, so a row that read them instead would show.  Outputs and caches
+    bit for bit equal to kv_append followed by mixed_paged_attention, with a fresh work list and with the
+    list left in the workspace (then the call is the attention launch and the merge alone)."""
+    import torch
+    b = INSIDE_CASES[case]()
+    dt = mpa.MPA_FP16 if b.dtype == "fp16" else mpa.MPA_BF16
+    outs = []
+    for inside in (False, True):
+        ctx = mpa.Context(b.H, b.D, block_size=b.bs, num_kv_heads=b.HK, dtype=dt)
+        ctx.set_option(mpa.MPA_OPT_PLAN_CACHE, 2)
+        ctx.set_option(mpa.MPA_OPT_FUSE_APPEND, 1 if inside else 0)
+        for k, v in opts.items():
+            ctx.set_option(getattr(mpa, k), v)
+        ws = torch.empty(ctx.workspace_bytes_for_batch(b.chunk_starts, b.context_lens), dtype=torch.uint8, device="cuda")
+        ws.fill_(0xFF)
+        for call in range(2):
+            db = DeviceBatch(b, "prior")
+            if inside:
+                ctx.append_and_attend(db.k_new, db.v_new, db.slot_map, db.q, db.k_cache, db.v_cache, db.block_table,
+                                      b.chunk_starts, b.context_lens, db.out, ws, scale=b.scale)
+            else:
+                run_on(ctx, db, b, ws)
+            torch.cuda.synchronize()
+            outs.append((to_host_u16(db.out), to_host_u16(db.k_cache), to_host_u16(db.v_cache)))
+    for o in outs[1:]:
+        for got, want in zip(o, outs[0]):
+            assert np.array_equal(got, want)
+    ref, kc, vc = oracle_run(b)
+    assert_close(outs[0][0], ref, b.name, dtype=b.dtype)
+    assert np.array_equal(outs[3][1], kc) and np.array_equal(outs[3][2], vc)
+
+
+def test_append_inside_the_launch_falls_back_for_streamed_prompt_rows(mpa):
+    """With prompt rows on the row-streaming body (a test option) a row would need several new keys: the
+    call then appends before the attention launch as usual, with the same results."""
+    import torch
+    b = W.config1()
+    ref = oracle_run(b)[0]
+    ctx = mpa.Context(b.H, b.D, block_size=b.bs, num_kv_heads=b.HK)
+    ctx.set_option(mpa.MPA_OPT_FUSE_APPEND, 1)
+    ctx.set_option(mpa.MPA_OPT_PP_ROWSTREAM, 1)
+    ws = torch.empty(ctx.workspace_bytes_for_batch(b.chunk_starts, b.context_lens), dtype=torch.uint8, device="cuda")
+    db = DeviceBatch(b, "prior")
+    ctx.append_and_attend(db.k_new, db.v_new, db.slot_map, db.q, db.k_cache, db.v_cache, db.block_table,
+                          b.chunk_starts, b.context_lens, db.out, ws, scale=b.scale)
+    torch.cuda.synchronize()
+    assert_close(to_host_u16(db.out), ref, b.name)

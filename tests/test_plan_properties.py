@@ -29,7 +29,12 @@ def test_random_batches_plan_invariants(seed, wide):
     tiles = items[:n_tile]
     for it in tiles:
         alone = ((tiles[:, 0] == it[0]) & (tiles[:, 4] == it[4])).sum() == 1
-        assert (it[7] >> 8) == int(alone)
+        assert ((it[7] >> 8) & 1) == int(alone)
+        # above it: the tile's first row counted from its chunk's first row (q_pos0 minus it = the first
+        # position of the sequence whose K/V arrives with this iteration)
+        seq = int(it[0])
+        assert (it[7] >> 9) == int(it[1]) - int(b.chunk_starts[seq])
+        assert int(it[3]) - (it[7] >> 9) == int(b.context_lens[seq]) - int(b.q_lens[seq])
     assert (items[:, 4] % 16 == 0).all() and (items[:n_tile, 4] % 64 == 0).all()
     assert (items[:, 5] > items[:, 4]).all()
     assert (items[n_tile:, 2] == 1).all() and (items[:n_tile, 2] <= tile_rows).all() and (items[:, 2] >= 1).all()
@@ -97,7 +102,7 @@ def test_grouped_heads_plan(H, HK):
         kinds = items[:, 7] & 0xFF
         assert counts[0] + counts[1] == len(items)
         if H != HK:   # shared K/V heads: no tile is marked as the only reader of its keys
-            assert ((items[kinds == 1][:, 7] >> 8) == 0).all()
+            assert (((items[kinds == 1][:, 7] >> 8) & 1) == 0).all()
         if 4 <= H // HK <= 128:
             assert counts[1] == 0 and (kinds == 2).sum() > 0 and (items[kinds == 2][:, 4] % 64 == 0).all()
             # group items sit between the prompt tiles and the (absent) row items
