@@ -579,6 +579,8 @@ def main():
     ap.add_argument("--ceilings", action="store_true",
                     help="only measure what the library's micro-kernels reach on this machine (streaming read, random "
                          "4 KiB / 16 KiB chunk reads, matrix instructions from registers) and print them")
+    ap.add_argument("--fuse-append", action="store_true",
+                    help="the step's append runs inside the attention launch (MPA_OPT_FUSE_APPEND) instead of before it")
     ap.add_argument("--clocks", action="store_true",
                     help="run each part of the workload (and the matrix-instruction micro-kernels) for a few seconds and "
                          "report the shader clock the chip sustains under it (rocm-smi), plus the prompt part on all-zero data")
@@ -612,6 +614,8 @@ def main():
         run_clocks(args, mpa, b)
         return
     dw = DeviceWorkload(b, mpa)
+    if args.fuse_append:
+        dw.ctx.set_option(mpa.MPA_OPT_FUSE_APPEND, 1)
     torch.cuda.synchronize()
 
     if args.only_part:
@@ -665,7 +669,8 @@ def main():
         "config": {"workload": f"{b.name}: H={b.H} D={b.D} bs={b.bs}, {int((b.q_lens > 1).sum())} prompt chunk(s) "
                                f"{b.q_lens[b.q_lens > 1].tolist()} at prior {b.priors[b.q_lens > 1].tolist()}, "
                                f"{int((b.q_lens == 1).sum())} generation rows, {b.tg_kv_tokens()} generation KV tokens",
-                   "rows": b.T, "seqs": b.S, "step": "kv_append + mixed_paged_attention in the one-call form mpa_append_and_attend (plan + upload included)"},
+                   "rows": b.T, "seqs": b.S, "step": "kv_append + mixed_paged_attention in the one-call form mpa_append_and_attend (plan + upload included)"
+                           + ("; append inside the attention launch" if args.fuse_append else "")},
         "roofline": {"kernel": "attention_kernel (mixed)", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "algorithmic_bytes": bytes_alg, "kernel_ms": attn_avg_ms,

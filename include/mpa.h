@@ -110,7 +110,7 @@ enum {
                                     next call would use is marked as still being read by an upload
                                     that never reports back (no GPU involved)                    */
     MPA_OPT_FUSE_APPEND = 12,    /* 1 = mpa_append_and_attend stores the iteration's K/V from inside the
-                                    attention launch (extra work-groups at the end of its grid) instead
+                                    attention launch (extra work-groups of its grid) instead
                                     of in a launch before it, and every row takes the keys of its own
                                     sequence's new positions -- the chunk's own tokens, a generation
                                     row's own token -- from k_new / v_new, since the cache slots are

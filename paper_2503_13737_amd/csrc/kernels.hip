@@ -1206,15 +1206,17 @@ attention_kernel(const AttnParams p)
         return;
     }
     const int hg = (H + WAVES - 1) / WAVES;
-    const int32_t idx = (int32_t)blockIdx.x - n_tile_wg - p.n_group_items;
-    if (idx >= p.n_row_items * hg) {
-        // the iteration's append (see AttnParams::k_new): nothing in this launch reads these slots
-        append_body((int64_t)(idx - p.n_row_items * hg) * (WAVES * 64) + threadIdx.x, reinterpret_cast<const uint4 *>(p.k_new),
+    int32_t idx = (int32_t)blockIdx.x - n_tile_wg - p.n_group_items;
+    if (idx < p.n_append_wgs) {
+        // The iteration's append (see AttnParams::k_new): nothing in this launch reads these slots.  Ahead
+        // of the rows in launch order, so that it runs beside them and not as a tail behind them.
+        append_body((int64_t)idx * (WAVES * 64) + threadIdx.x, reinterpret_cast<const uint4 *>(p.k_new),
                     reinterpret_cast<const uint4 *>(p.v_new), p.slot_map, p.n_new, p.kv_heads, D / 8, p.block_size,
                     reinterpret_cast<uint4 *>(const_cast<uint16_t *>(p.k_cache)),
                     reinterpret_cast<uint4 *>(const_cast<uint16_t *>(p.v_cache)));
         return;
     }
+    idx -= p.n_append_wgs;
     const int32_t item = p.n_tile_items + p.n_group_items + idx / hg;
     const int head = (idx % hg) * WAVES + wave;
     if (head >= H) return;

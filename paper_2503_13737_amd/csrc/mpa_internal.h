@@ -140,7 +140,7 @@ struct AttnParams {
     uint32_t *progress;
     int32_t wide;           // Plan::wide
     // Append inside the launch (k_new != nullptr): the iteration's new K/V [n_new, kv_heads, D] is
-    // stored to the caches by n_append_wgs extra work-groups at the end of the grid, and every reader
+    // stored to the caches by n_append_wgs extra work-groups (between the tiles' and the rows'), and every reader
     // takes the keys of its own sequence's new positions from k_new / v_new instead of the cache.
     const uint16_t *k_new;
     const uint16_t *v_new;

@@ -3,7 +3,8 @@ times: kv_append + mixed_paged_attention on the whole batch, compared with the o
 can compute one by one -- every row and every head on configs 2 and 3; on configs 4 and 5 every
 generation row and, of the prompt rows, the first, the last, every 61st and those straddling 16-
 and 128-row boundaries, all heads each -- plus bit-exact kv_append on the blocks the new tokens
-land in.  The whole output is NaN-poisoned first and checked for rows left unwritten."""
+land in.  The whole output is NaN-poisoned first and checked for rows left unwritten.  Most configs then run
+once more with the append inside the attention launch and must reproduce output and caches bit for bit."""
 import os
 import sys
 
@@ -36,7 +37,28 @@ def sample_rows(b, all_prompt_rows):
     return np.asarray(rows, dtype=np.int32), np.asarray(heads, dtype=np.int32)
 
 
-def check_config(b, all_prompt_rows=False):
+def check_append_inside_the_launch(b, dw):
+    """The same step with the append inside the attention launch (MPA_OPT_FUSE_APPEND) on a fresh copy of
+    the workload, whose new tokens' cache slots hold NaN patterns when the launch starts: output and the
+    blocks the new tokens land in bit for bit equal to the step just checked."""
+    import torch
+    import bench
+    import paper_2503_13737_amd as mpa
+    dw2 = bench.DeviceWorkload(b, mpa)
+    dw2.ctx.set_option(mpa.MPA_OPT_FUSE_APPEND, 1)
+    dw2.out.fill_(0x7FFF)
+    dw2.ws.fill_(0xFF)
+    dw2.step()
+    torch.cuda.synchronize()
+    assert torch.equal(dw2.out, dw.out), f"{b.name}: output differs with the append inside the launch"
+    touched = torch.from_numpy(np.unique(b.slot_map // b.bs)).cuda()
+    assert torch.equal(dw2.k_cache[touched], dw.k_cache[touched]) and torch.equal(dw2.v_cache[touched], dw.v_cache[touched])
+    del dw2
+    torch.cuda.empty_cache()
+    print(f"[{b.name}] append inside the launch: identical", flush=True)
+
+
+def check_config(b, all_prompt_rows=False, also_fused=False):
     import torch
     import bench
     import oracle
@@ -79,6 +101,8 @@ def check_config(b, all_prompt_rows=False):
     # per-row worst case stays within the absolute bound too
     per_row = np.abs(W.to_f64(got, b.dtype) - ref).max(axis=1)
     assert per_row.max() <= abs_tol
+    if also_fused:
+        check_append_inside_the_launch(b, dw)
     del dw
     torch.cuda.empty_cache()
 
@@ -88,7 +112,7 @@ def test_config2_13b_generation_only():
 
 
 def test_config3_13b_mixed():
-    check_config(W.config3(), all_prompt_rows=True)
+    check_config(W.config3(), all_prompt_rows=True, also_fused=True)
 
 
 @pytest.mark.parametrize("prior", [0, 2048, 4096])
@@ -97,25 +121,25 @@ def test_config3_prior_extremes(prior):
 
 
 def test_config4_175b_slice():
-    check_config(W.config4())
+    check_config(W.config4(), also_fused=True)
 
 
 def test_grouped_kv_layer():
-    check_config(W.config_gqa())
+    check_config(W.config_gqa(), also_fused=True)
 
 
 def test_grouped_kv_decode_of_a_whole_layer():
     """64 query / 8 K/V heads, 64 generation rows at 4-12 K: every row runs as group items over
     several key ranges (streamed K/V, partials, merge)."""
-    check_config(W.config_gqa_decode())
+    check_config(W.config_gqa_decode(), also_fused=True)
 
 
 @pytest.mark.parametrize("iteration", [0, 12, 24, 36, 47, 48])
 def test_config5_long_prompt(iteration):
-    check_config(W.config5(iteration))
+    check_config(W.config5(iteration), also_fused=iteration in (24, 48))
 
 
 @pytest.mark.parametrize("make", [W.config2, W.config3, W.config4, lambda dtype: W.config5(47, dtype=dtype)],
                          ids=["cfg2", "cfg3", "cfg4", "cfg5:47"])
 def test_fp16_storage_at_full_size(make):
-    check_config(make(dtype="fp16"))
+    check_config(make(dtype="fp16"), also_fused=True)
