@@ -337,7 +337,7 @@ __device__ __forceinline__ void consume(const KvRegs<D> &r, const float (&qf)[8]
     m = m_new;
 }
 
-template <class E, int D, int NS>
+template <class E, int D, int NS, bool FUSED>
 __device__ __forceinline__ void row_body(const AttnParams &p, const WorkItem &it, int head, int lane)
 {
     using C = RowCfg<D>;
@@ -366,7 +366,7 @@ __device__ __forceinline__ void row_body(const AttnParams &p, const WorkItem &it
     const int32_t page_shift = p.page_shift;
     // Append inside the launch: the row's own token (position q_pos0, the last key of the range that
     // reaches it) is not in the cache yet; its K/V is row q_row0 of k_new / v_new.
-    const bool own_new = p.k_new != nullptr && it.kv_end > it.q_pos0;
+    const bool own_new = FUSED && it.kv_end > it.q_pos0;
     const u32x4 *own_k = nullptr, *own_v = nullptr;
     if (own_new) {
         const size_t el = ((size_t)it.q_row0 * HK + kv_head) * D;
@@ -829,7 +829,8 @@ __device__ __forceinline__ void progress_store(uint32_t *w, uint32_t v)
 // head of the group of a group item (its rows are the group's heads, all at the token q_row0):
 // row r of the item is row (q_row0 * H + head) + r * rstride of q / out seen as [T * H, D], and
 // likewise in the partial buffers.
-template <class E, int D, int WAVES>
+// FUSED: the launch also appends (AttnParams::k_new); without it none of that code is compiled in.
+template <class E, int D, int WAVES, bool FUSED>
 __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &it, const TeamRef &team, int head,
                                           char *lds)
 {
@@ -922,7 +923,7 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
     // where position pos is row q_row0 + (pos - q_pos0).  A wavefront's rows of a tile lie in one page;
     // point_new aims nk / nv at where that page would start in the new rows (before their first row if
     // the page begins with old keys: those lanes do not load from there).
-    const int32_t new_begin = p.k_new == nullptr ? 0x7FFFFFFF : grouped ? it.q_pos0 : it.q_pos0 - (it.kind >> kTileRowShift);
+    const int32_t new_begin = !FUSED ? 0x7FFFFFFF : grouped ? it.q_pos0 : it.q_pos0 - (it.kind >> kTileRowShift);
     const int32_t wave_row0 = __builtin_amdgcn_readfirstlane(wave * C::KPW);
     auto point_new = [&](int32_t k0_tile) {
         const int64_t row = (int64_t)it.q_row0 + ((int64_t)k0_tile + (wave_row0 & ~(kPage - 1)) - it.q_pos0);
@@ -938,7 +939,7 @@ __device__ __forceinline__ void tile_body(const AttnParams &p, const WorkItem &i
         next.nv = reinterpret_cast<const char *>(uniform64(av));
     };
     // does the wavefront's share of the tile that starts at key k0_tile reach new keys?
-    auto reaches_new = [&](int32_t k0_tile) { return k0_tile + wave_row0 + C::KPW > new_begin; };
+    auto reaches_new = [&](int32_t k0_tile) { return FUSED && k0_tile + wave_row0 + C::KPW > new_begin; };
 
     // Pipeline: while step s is computed from LDS buffer s&1, the direct loads of step s+1 fill the
     // other buffer.  That buffer was last read in step s-1, which every wavefront has left, and the
@@ -1150,7 +1151,7 @@ __device__ __forceinline__ WorkItem load_item(const WorkItem *src)
 // ------------------------------------------------------------------------------------------
 constexpr int kXcds = 8;   // accelerator dies of the chip, each with its own L2
 
-template <class E, int D, int WAVES>
+template <class E, int D, int WAVES, bool FUSED>
 __global__ void __launch_bounds__(WAVES * 64, 8 / WAVES)
 attention_kernel(const AttnParams p)
 {
@@ -1193,7 +1194,7 @@ attention_kernel(const AttnParams p)
             team.member = __builtin_amdgcn_readfirstlane(p.teams[item].member);
             team.size = __builtin_amdgcn_readfirstlane(p.teams[item].size);
             team.stride = __builtin_amdgcn_readfirstlane(p.teams[item].stride);
-            tile_body<E, D, WAVES>(p, it, team, head, lds);
+            tile_body<E, D, WAVES, FUSED>(p, it, team, head, lds);
             __syncthreads();   // the next unit's first loads overwrite the tile buffers
         }
         return;
@@ -1202,12 +1203,12 @@ attention_kernel(const AttnParams p)
         // a group item (a generation row of grouped K/V heads) names its K/V head; one work-group each
         const WorkItem it = load_item(p.items + p.n_tile_items + ((int32_t)blockIdx.x - n_tile_wg));
         const TeamRef team = {-1, 0, 1, 0};
-        tile_body<E, D, WAVES>(p, it, team, (it.kind >> 8) * p.group, lds);
+        tile_body<E, D, WAVES, FUSED>(p, it, team, (it.kind >> 8) * p.group, lds);
         return;
     }
     const int hg = (H + WAVES - 1) / WAVES;
     int32_t idx = (int32_t)blockIdx.x - n_tile_wg - p.n_group_items;
-    if (idx < p.n_append_wgs) {
+    if (FUSED && idx < p.n_append_wgs) {
         // The iteration's append (see AttnParams::k_new): nothing in this launch reads these slots.  Ahead
         // of the rows in launch order, so that it runs beside them and not as a tail behind them.
         append_body((int64_t)idx * (WAVES * 64) + threadIdx.x, reinterpret_cast<const uint4 *>(p.k_new),
@@ -1216,12 +1217,12 @@ attention_kernel(const AttnParams p)
                     reinterpret_cast<uint4 *>(const_cast<uint16_t *>(p.v_cache)));
         return;
     }
-    idx -= p.n_append_wgs;
+    if (FUSED) idx -= p.n_append_wgs;
     const int32_t item = p.n_tile_items + p.n_group_items + idx / hg;
     const int head = (idx % hg) * WAVES + wave;
     if (head >= H) return;
     const WorkItem it = load_item(p.items + item);
-    row_body<E, D, kRowSets>(p, it, head, lane);
+    row_body<E, D, kRowSets, FUSED>(p, it, head, lane);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1377,6 +1378,16 @@ int launch_copy_blocks(const void *src_k, const void *src_v, void *dst_k, void *
     return (int)hipGetLastError();
 }
 
+template <bool FUSED>
+static void (*pick_kernel(bool wide, bool fp16, int32_t D))(const AttnParams)
+{
+    if (wide)
+        return fp16 ? (D == 128 ? attention_kernel<Fp16, 128, kWideWaves, FUSED> : attention_kernel<Fp16, 64, kWideWaves, FUSED>)
+                    : (D == 128 ? attention_kernel<Bf16, 128, kWideWaves, FUSED> : attention_kernel<Bf16, 64, kWideWaves, FUSED>);
+    return fp16 ? (D == 128 ? attention_kernel<Fp16, 128, kWaves, FUSED> : attention_kernel<Fp16, 64, kWaves, FUSED>)
+                : (D == 128 ? attention_kernel<Bf16, 128, kWaves, FUSED> : attention_kernel<Bf16, 64, kWaves, FUSED>);
+}
+
 int launch_attention(const AttnParams &params, int32_t D, bool fp16, void *stream)
 {
     AttnParams p = params;
@@ -1390,13 +1401,7 @@ int launch_attention(const AttnParams &params, int32_t D, bool fp16, void *strea
     const int64_t units = (int64_t)p.n_tile_items * p.heads + p.n_group_items;
     if (grid > 0x7FFFFFFF || units > 0x7FFFFFFF || row_wgs > 0x7FFFFFFF) return (int)hipErrorInvalidConfiguration;
     p.n_append_wgs = (int32_t)append_wgs;
-    void (*kernel)(const AttnParams);
-    if (p.wide)
-        kernel = fp16 ? (D == 128 ? attention_kernel<Fp16, 128, kWideWaves> : attention_kernel<Fp16, 64, kWideWaves>)
-                      : (D == 128 ? attention_kernel<Bf16, 128, kWideWaves> : attention_kernel<Bf16, 64, kWideWaves>);
-    else
-        kernel = fp16 ? (D == 128 ? attention_kernel<Fp16, 128, kWaves> : attention_kernel<Fp16, 64, kWaves>)
-                      : (D == 128 ? attention_kernel<Bf16, 128, kWaves> : attention_kernel<Bf16, 64, kWaves>);
+    void (*kernel)(const AttnParams) = p.k_new ? pick_kernel<true>(p.wide != 0, fp16, D) : pick_kernel<false>(p.wide != 0, fp16, D);
     hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(waves * 64), 0, (hipStream_t)stream, p);
     return (int)hipGetLastError();
 }
