@@ -381,6 +381,8 @@ def run_scheduled(args, mpa):
     q_all, k_all, v_all = pool[0], pool[1], pool[2]
     out = torch.empty((max_tokens, H, D), dtype=torch.int16, device=dev)
     ctx = mpa.Context(H, D, block_size=bs, num_kv_heads=HK)
+    if args.fuse_append:
+        ctx.set_option(mpa.MPA_OPT_FUSE_APPEND, 1)
     ws = {"buf": torch.empty(1 << 30, dtype=torch.uint8, device=dev)}
     sched = mpa.Scheduler(bs, NB, s_pf, t_pf, t_max, gamma, max_tokens, block_order=order)
     state = {"now": 0.0, "next": 0}
