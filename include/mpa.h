@@ -17,7 +17,8 @@
  *
  * Conventions
  *   - Every function returns an int status (MPA_OK == 0, errors < 0) unless stated; nothing
- *     throws or aborts.
+ *     throws or aborts (a host allocation that fails inside a call is reported as
+ *     MPA_ERR_NO_MEMORY, by any function that plans a batch).
  *   - "device" pointers are HIP device memory owned by the caller; "host" pointers are ordinary
  *     host memory read during the call only.  The library allocates no device memory.
  *   - Work is enqueued on the HIP stream passed as `stream` (a hipStream_t cast to void*,
@@ -55,7 +56,10 @@ enum {
     MPA_ERR_UNSUPPORTED = -2, /* head_dim / block_size / dtype / head layout not built      */
     MPA_ERR_WORKSPACE = -3,   /* workspace missing or smaller than the batch needs          */
     MPA_ERR_BAD_BATCH = -4,   /* chunk_starts / context_lens describe no valid batch        */
-    MPA_ERR_HIP = -5          /* a HIP runtime call failed; see mpa_last_hip_error          */
+    MPA_ERR_HIP = -5,         /* a HIP runtime call failed; see mpa_last_hip_error          */
+    MPA_ERR_NO_MEMORY = -6    /* the host ran out of memory inside the call (work lists and
+                                 scheduler state live in ordinary host memory); the object stays
+                                 usable, a cached plan is dropped                            */
 };
 
 enum {
@@ -280,7 +284,7 @@ int mpa_mixed_paged_attention_static(mpa_ctx *ctx, const void *q, const void *k_
  * calls; n == 0 switches it off and frees the events.  mpa_profile_read waits for the recorded
  * events, writes the elapsed milliseconds of up to `cap` calls (oldest first) to `ms` (host),
  * stores the count in *n_out and starts a new series.
- * Errors: INVALID_ARG, HIP.
+ * Errors: INVALID_ARG (also n above 2^24), HIP, NO_MEMORY.
  */
 int mpa_profile_enable(mpa_ctx *ctx, int32_t max_calls);
 int mpa_profile_read(mpa_ctx *ctx, float *ms, int32_t cap, int32_t *n_out);

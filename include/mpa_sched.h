@@ -27,7 +27,9 @@
  * to copy come with the batch; mpa_copy_blocks does the copying); one preempted for the token
  * budget keeps its blocks.
  *
- * All pointers are host memory.  Functions return MPA_OK or a negative MPA_ERR_* of mpa.h.
+ * All pointers are host memory.  Functions return MPA_OK or a negative MPA_ERR_* of mpa.h; no C++
+ * exception leaves them.  After MPA_ERR_NO_MEMORY (the host ran out of memory half way through a
+ * decision) the scheduler's state is unspecified: destroy it.
  * One scheduler must not be used from two threads at once.
  */
 #ifndef MPA_SCHED_H

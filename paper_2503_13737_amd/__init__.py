@@ -20,6 +20,7 @@ MPA_ERR_UNSUPPORTED = -2
 MPA_ERR_WORKSPACE = -3
 MPA_ERR_BAD_BATCH = -4
 MPA_ERR_HIP = -5
+MPA_ERR_NO_MEMORY = -6
 MPA_BF16 = 1
 MPA_FP16 = 2
 MPA_OPT_TG_SPLIT_BLOCKS = 1

@@ -86,6 +86,17 @@ struct mpa_ctx {
 
 static bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
+// No C++ exception leaves the library: host containers may fail to grow.
+template <class F>
+static auto guarded(F &&f, decltype(f()) on_no_memory) noexcept -> decltype(f())
+{
+    try {
+        return f();
+    } catch (...) {
+        return on_no_memory;
+    }
+}
+
 extern "C" {
 
 const char *mpa_status_string(int status)
@@ -97,6 +108,7 @@ const char *mpa_status_string(int status)
     case MPA_ERR_WORKSPACE: return "workspace missing or too small";
     case MPA_ERR_BAD_BATCH: return "malformed batch description";
     case MPA_ERR_HIP: return "HIP runtime error";
+    case MPA_ERR_NO_MEMORY: return "out of host memory";
     default: return "unknown status";
     }
 }
@@ -113,7 +125,7 @@ int mpa_create(mpa_ctx **out, const mpa_config *cfg)
     if (cfg->block_size != 16 && cfg->block_size != 32 && cfg->block_size != 64 && cfg->block_size != 128)
         return MPA_ERR_UNSUPPORTED;
     mpa_ctx *c = new (std::nothrow) mpa_ctx();
-    if (!c) return MPA_ERR_INVALID_ARG;
+    if (!c) return MPA_ERR_NO_MEMORY;
     c->cfg = *cfg;
     c->opt.heads = cfg->num_heads;
     c->opt.kv_heads = cfg->num_kv_heads;
@@ -137,22 +149,25 @@ int mpa_destroy(mpa_ctx *ctx)
 
 int mpa_profile_enable(mpa_ctx *ctx, int32_t max_calls)
 {
-    if (!ctx || max_calls < 0) return MPA_ERR_INVALID_ARG;
+    if (!ctx || max_calls < 0 || max_calls > (1 << 24)) return MPA_ERR_INVALID_ARG;
     std::lock_guard<std::mutex> g(ctx->mu);
     for (hipEvent_t e : ctx->prof_events) (void)hipEventDestroy(e);
     ctx->prof_events.clear();
     ctx->prof_used = 0;
     ctx->prof_calls = 0;
-    for (int32_t i = 0; i < 2 * max_calls; ++i) {
-        hipEvent_t e;
-        hipError_t rc = hipEventCreate(&e);
-        if (rc != hipSuccess) {
-            ctx->last_hip = (int)rc;
-            return MPA_ERR_HIP;
+    return guarded([&]() -> int {
+        ctx->prof_events.reserve(2 * (size_t)max_calls);
+        for (int32_t i = 0; i < 2 * max_calls; ++i) {
+            hipEvent_t e;
+            hipError_t rc = hipEventCreate(&e);
+            if (rc != hipSuccess) {
+                ctx->last_hip = (int)rc;
+                return MPA_ERR_HIP;
+            }
+            ctx->prof_events.push_back(e);
         }
-        ctx->prof_events.push_back(e);
-    }
-    return MPA_OK;
+        return MPA_OK;
+    }, MPA_ERR_NO_MEMORY);
 }
 
 int mpa_profile_read(mpa_ctx *ctx, float *ms, int32_t cap, int32_t *n_out)
@@ -242,9 +257,11 @@ size_t mpa_workspace_bytes_for_batch(const mpa_ctx *ctx, const int32_t *chunk_st
                                      const int32_t *context_lens, int32_t num_seqs)
 {
     if (!ctx || num_seqs < 0 || (num_seqs > 0 && (!chunk_starts || !context_lens))) return 0;
-    Plan p;
-    if (build_plan(ctx->opt, chunk_starts, context_lens, num_seqs, &p) != MPA_OK) return 0;
-    return p.total_bytes > 256 ? p.total_bytes : 256;
+    return guarded([&]() -> size_t {
+        Plan p;
+        if (build_plan(ctx->opt, chunk_starts, context_lens, num_seqs, &p) != MPA_OK) return 0;
+        return p.total_bytes > 256 ? p.total_bytes : 256;
+    }, (size_t)0);
 }
 
 size_t mpa_workspace_bytes(const mpa_ctx *ctx, int32_t max_seqs, int32_t max_tokens, int32_t max_ctx)
@@ -260,18 +277,20 @@ int64_t mpa_plan_describe(const mpa_ctx *ctx, const int32_t *chunk_starts,
     if (!ctx || num_seqs < 0 || (num_seqs > 0 && (!chunk_starts || !context_lens)) || cap < 0 ||
         (cap > 0 && !items))
         return MPA_ERR_INVALID_ARG;
-    Plan p;
-    int rc = build_plan(ctx->opt, chunk_starts, context_lens, num_seqs, &p);
-    if (rc != MPA_OK) return rc;
-    const int64_t n = (int64_t)p.items.size();
-    if (cap > 0) std::memcpy(items, p.items.data(), (size_t)(n < cap ? n : cap) * sizeof(WorkItem));
-    if (counts) {
-        counts[0] = p.n_tile_items + p.n_group_items;
-        counts[1] = p.n_row_items;
-        counts[2] = (int32_t)p.merge.size();
-        counts[3] = (int32_t)p.part_rows;
-    }
-    return n;
+    return guarded([&]() -> int64_t {
+        Plan p;
+        int rc = build_plan(ctx->opt, chunk_starts, context_lens, num_seqs, &p);
+        if (rc != MPA_OK) return rc;
+        const int64_t n = (int64_t)p.items.size();
+        if (cap > 0) std::memcpy(items, p.items.data(), (size_t)(n < cap ? n : cap) * sizeof(WorkItem));
+        if (counts) {
+            counts[0] = p.n_tile_items + p.n_group_items;
+            counts[1] = p.n_row_items;
+            counts[2] = (int32_t)p.merge.size();
+            counts[3] = (int32_t)p.part_rows;
+        }
+        return n;
+    }, (int64_t)MPA_ERR_NO_MEMORY);
 }
 
 int mpa_kv_append(mpa_ctx *ctx, const void *k_new, const void *v_new, const int64_t *slot_map,
@@ -324,10 +343,33 @@ struct AppendArgs {
     void *k_cache, *v_cache;
 };
 
+int attend_may_throw(mpa_ctx *ctx, const AppendArgs *app, const void *q, const void *k_cache, const void *v_cache,
+                     const int32_t *block_table, int32_t block_table_stride, const int32_t *chunk_starts,
+                     const int32_t *context_lens, int32_t num_seqs, int32_t num_tokens, float scale, void *out,
+                     void *workspace, size_t workspace_bytes, bool static_ws, void *stream);
+
 int attend(mpa_ctx *ctx, const AppendArgs *app, const void *q, const void *k_cache, const void *v_cache,
            const int32_t *block_table, int32_t block_table_stride, const int32_t *chunk_starts,
            const int32_t *context_lens, int32_t num_seqs, int32_t num_tokens, float scale, void *out,
            void *workspace, size_t workspace_bytes, bool static_ws, void *stream)
+{
+    const int rc = guarded([&]() -> int {
+        return attend_may_throw(ctx, app, q, k_cache, v_cache, block_table, block_table_stride, chunk_starts, context_lens,
+                                num_seqs, num_tokens, scale, out, workspace, workspace_bytes, static_ws, stream);
+    }, MPA_ERR_NO_MEMORY);
+    if (rc == MPA_ERR_NO_MEMORY && ctx) {
+        // whatever was being put together is not trusted: the next call plans and uploads afresh
+        std::lock_guard<std::mutex> g(ctx->mu);
+        ctx->plan_valid = false;
+        ctx->uploaded_valid = false;
+    }
+    return rc;
+}
+
+int attend_may_throw(mpa_ctx *ctx, const AppendArgs *app, const void *q, const void *k_cache, const void *v_cache,
+                     const int32_t *block_table, int32_t block_table_stride, const int32_t *chunk_starts,
+                     const int32_t *context_lens, int32_t num_seqs, int32_t num_tokens, float scale, void *out,
+                     void *workspace, size_t workspace_bytes, bool static_ws, void *stream)
 {
     if (!ctx || num_seqs < 0 || num_tokens < 0) return MPA_ERR_INVALID_ARG;
     if (num_seqs == 0) return num_tokens == 0 ? MPA_OK : MPA_ERR_BAD_BATCH;

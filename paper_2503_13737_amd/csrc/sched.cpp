@@ -201,7 +201,7 @@ void mpa_sched::select_requests(int64_t a_c, int64_t a_m, const std::vector<Req 
 extern "C" {
 
 int mpa_sched_create(mpa_sched **out, const mpa_sched_config *cfg, const int32_t *block_order)
-{
+try {
     if (!out || !cfg) return MPA_ERR_INVALID_ARG;
     *out = nullptr;
     if (cfg->block_size < 1 || cfg->num_blocks < 1 || cfg->pivot_forward_size < 1 || cfg->max_batch_tokens < 1 ||
@@ -209,7 +209,7 @@ int mpa_sched_create(mpa_sched **out, const mpa_sched_config *cfg, const int32_t
         !(cfg->preempt_max_time >= 0.0) || !(cfg->preempt_probability >= 0.0) || cfg->num_swap_blocks < 0)
         return MPA_ERR_INVALID_ARG;
     std::unique_ptr<mpa_sched> s(new (std::nothrow) mpa_sched());
-    if (!s) return MPA_ERR_INVALID_ARG;
+    if (!s) return MPA_ERR_NO_MEMORY;
     s->cfg = *cfg;
     const int32_t n = cfg->num_blocks;
     s->free_blocks.resize(n);
@@ -224,6 +224,8 @@ int mpa_sched_create(mpa_sched **out, const mpa_sched_config *cfg, const int32_t
     for (int32_t i = 0; i < cfg->num_swap_blocks; ++i) s->swap_free[(size_t)(cfg->num_swap_blocks - 1 - i)] = i;
     *out = s.release();
     return MPA_OK;
+} catch (...) {
+    return MPA_ERR_NO_MEMORY;   // host containers could not grow
 }
 
 int mpa_sched_destroy(mpa_sched *s)
@@ -234,12 +236,12 @@ int mpa_sched_destroy(mpa_sched *s)
 
 int mpa_sched_add_request(mpa_sched *s, int64_t id, int32_t prompt_len, int32_t max_new_tokens,
                           double slo_first, double slo_token, double now)
-{
+try {
     if (!s || prompt_len < 1 || max_new_tokens < 1) return MPA_ERR_INVALID_ARG;
     if ((int64_t)prompt_len + max_new_tokens - 1 > (int64_t)s->cfg.num_blocks * s->cfg.block_size) return MPA_ERR_INVALID_ARG;
     if (s->live.count(id)) return MPA_ERR_INVALID_ARG;
     std::unique_ptr<Req> r(new (std::nothrow) Req());
-    if (!r) return MPA_ERR_INVALID_ARG;
+    if (!r) return MPA_ERR_NO_MEMORY;
     r->id = id;
     r->prompt_len = prompt_len;
     r->max_new = max_new_tokens;
@@ -248,11 +250,13 @@ int mpa_sched_add_request(mpa_sched *s, int64_t id, int32_t prompt_len, int32_t 
     r->t_enter = now;
     s->live.emplace(id, std::move(r));
     return MPA_OK;
+} catch (...) {
+    return MPA_ERR_NO_MEMORY;   // host containers could not grow
 }
 
 int mpa_sched_add_offline_request(mpa_sched *s, int64_t id, int32_t prompt_len, int32_t max_new_tokens,
                                   int32_t predicted_new_tokens, double slo_jct, double now)
-{
+try {
     if (!s || predicted_new_tokens < 1) return MPA_ERR_INVALID_ARG;
     const int rc = mpa_sched_add_request(s, id, prompt_len, max_new_tokens, 0.0, 0.0, now);
     if (rc != MPA_OK) return rc;
@@ -266,11 +270,13 @@ int mpa_sched_add_offline_request(mpa_sched *s, int64_t id, int32_t prompt_len, 
     r.offline = true;
     r.allowance = (slo_jct - t_e) / (n_ck + (double)predicted_new_tokens);
     return MPA_OK;
+} catch (...) {
+    return MPA_ERR_NO_MEMORY;   // host containers could not grow
 }
 
 // Algorithm 1.
 int mpa_sched_next_batch(mpa_sched *s, double now, mpa_sched_batch *info)
-{
+try {
     if (!s || !info) return MPA_ERR_INVALID_ARG;
     s->batch.clear();
     s->swap_out.clear();
@@ -389,20 +395,24 @@ int mpa_sched_next_batch(mpa_sched *s, double now, mpa_sched_batch *info)
     info->num_swap_out = (int32_t)(s->swap_out.size() / 2);
     info->num_swap_in = (int32_t)(s->swap_in.size() / 2);
     return MPA_OK;
+} catch (...) {
+    return MPA_ERR_NO_MEMORY;   // host containers could not grow
 }
 
 int mpa_sched_batch_swaps(const mpa_sched *s, int64_t *out_pairs, int64_t *in_pairs)
-{
+try {
     if (!s) return MPA_ERR_INVALID_ARG;
     if (out_pairs) std::copy(s->swap_out.begin(), s->swap_out.end(), out_pairs);
     if (in_pairs) std::copy(s->swap_in.begin(), s->swap_in.end(), in_pairs);
     return MPA_OK;
+} catch (...) {
+    return MPA_ERR_NO_MEMORY;   // host containers could not grow
 }
 
 int mpa_sched_batch_arrays(const mpa_sched *s, int64_t *request_ids, int32_t *chunk_starts,
                            int32_t *context_lens, int64_t *slot_map, int32_t *block_table,
                            int32_t block_table_stride)
-{
+try {
     if (!s) return MPA_ERR_INVALID_ARG;
     int32_t row0 = 0;
     const int64_t b = s->cfg.block_size;
@@ -426,10 +436,12 @@ int mpa_sched_batch_arrays(const mpa_sched *s, int64_t *request_ids, int32_t *ch
     }
     if (chunk_starts) chunk_starts[s->batch.size()] = row0;
     return MPA_OK;
+} catch (...) {
+    return MPA_ERR_NO_MEMORY;   // host containers could not grow
 }
 
 int mpa_sched_complete(mpa_sched *s, double now, int64_t *finished_ids, int32_t cap, int32_t *num_finished)
-{
+try {
     if (!s) return MPA_ERR_INVALID_ARG;
     int32_t n = 0;
     for (const Entry &e : s->batch) {
@@ -456,6 +468,8 @@ int mpa_sched_complete(mpa_sched *s, double now, int64_t *finished_ids, int32_t 
     s->batch.clear();
     if (num_finished) *num_finished = n;
     return MPA_OK;
+} catch (...) {
+    return MPA_ERR_NO_MEMORY;   // host containers could not grow
 }
 
 int32_t mpa_sched_live_requests(const mpa_sched *s) { return s ? (int32_t)s->live.size() : 0; }

@@ -228,3 +228,38 @@ def test_options_and_measurement_aid_reject_bad_arguments_without_gpu():
     assert call(mpa.MPA_CEIL_MFMA_BF16_NOISY, None, 0, 0, fake, None) == mpa.MPA_ERR_INVALID_ARG        # no iterations
     assert call(mpa.MPA_CEIL_MFMA_BF16_NOISY + 1, None, 0, 4, fake, None) == mpa.MPA_ERR_INVALID_ARG    # no such kind
     assert call(17, fake, 1 << 30, 2, fake, None) == mpa.MPA_ERR_INVALID_ARG
+
+
+def test_no_exception_crosses_the_boundary_when_the_host_runs_out_of_memory():
+    """In a child process whose address space is capped just above what it already uses, planning a batch
+    of eight million sequences cannot allocate its work list: the call reports MPA_ERR_NO_MEMORY (no abort,
+    no C++ exception through the C frames) and the context keeps working."""
+    import subprocess
+    import sys
+    code = r'''
+import resource, numpy as np
+import paper_2503_13737_amd as mpa
+mpa.load()
+ctx = mpa.Context(4, 128)
+S = 8_000_000
+cs = np.arange(S + 1, dtype=np.int32)
+cl = np.full(S, 40, dtype=np.int32)
+small = ctx.plan_describe(cs[:3], cl[:2])[0].shape[0]
+vm = int(next(l for l in open("/proc/self/status") if l.startswith("VmSize")).split()[1]) * 1024
+resource.setrlimit(resource.RLIMIT_AS, (vm + (160 << 20), vm + (160 << 20)))
+try:
+    ctx.plan_describe(cs, cl)
+    print("status", 0)
+except mpa.MpaError as e:
+    print("status", e.status)
+print("bytes", ctx.workspace_bytes_for_batch(cs, cl))
+print("again", ctx.plan_describe(cs[:3], cl[:2])[0].shape[0] == small)
+'''
+    r = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300,
+                       cwd=os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
+    assert r.returncode == 0, r.stderr[-2000:]
+    got = dict(line.split() for line in r.stdout.splitlines() if line.strip())
+    assert int(got["status"]) == mpa.MPA_ERR_NO_MEMORY
+    assert int(got["bytes"]) == 0          # the size query reports "no valid answer" the way it does for a bad batch
+    assert got["again"] == "True"
+    assert mpa.status_string(mpa.MPA_ERR_NO_MEMORY) == "out of host memory"
