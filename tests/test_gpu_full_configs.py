@@ -143,3 +143,12 @@ def test_config5_long_prompt(iteration):
                          ids=["cfg2", "cfg3", "cfg4", "cfg5:47"])
 def test_fp16_storage_at_full_size(make):
     check_config(make(dtype="fp16"), also_fused=True)
+
+
+def test_million_token_contexts():
+    """The largest shape tried: a generation row and a 64-row prompt chunk, each over a context of 2^20
+    tokens (65,536 blocks per sequence; the tile body walks 16,384 steps, the table words of a range are
+    re-read every 64 pages), plus a short sequence beside them."""
+    n = 1 << 20
+    b = W.make_batch("million", 99, 2, 128, 16, 2 * (n // 16) + 16, [1, 64, 1], [n, n, 100])
+    check_config(b, also_fused=True)
