@@ -318,7 +318,8 @@ def test_fp16_flat_softmax_over_a_long_context(mpa):
 def test_random_combinations_of_geometry_dtype_and_options(mpa):
     """Thirty seeded draws over head layout, head_dim, block size, storage type, batch mix and
     planner options at once (the dedicated tests vary these one or two at a time), each through the
-    one-call form and checked against the oracle, caches included."""
+    one-call form -- with the append before or inside the attention launch -- and checked against the
+    oracle, caches included."""
     import torch
     draws = W.bits(30 * 12, 4711).reshape(30, 12)
     for n, u in enumerate(draws):
@@ -337,9 +338,11 @@ def test_random_combinations_of_geometry_dtype_and_options(mpa):
             opts = {"MPA_OPT_TG_SPLIT_BLOCKS": 1 + u[11] % 7, "MPA_OPT_PP_SPLIT_TOKENS": 64 * (1 + u[11] % 5)}
         elif u[10] % 3 == 2:
             opts = {"MPA_OPT_PP_RESIDENT_WGS": 1 + u[11] % 9, "MPA_OPT_PP_TEAM_MIN_STEPS": 1 + u[11] % 3}
-        what = f"draw {n}: H={H} HK={HK} D={D} bs={bs} {dtype} pp={n_pp} tg={n_tg} T={b.T} {opts}"
+        inside = (u[11] // 16) % 2     # every other draw or so: the append inside the attention launch
+        what = f"draw {n}: H={H} HK={HK} D={D} bs={bs} {dtype} pp={n_pp} tg={n_tg} T={b.T} {opts} append inside {inside}"
         print(what, flush=True)
         ctx = ctx_for(mpa, b, **opts)
+        ctx.set_option(mpa.MPA_OPT_FUSE_APPEND, inside)
         db = DeviceBatch(b, "prior")
         ws = torch.empty(ctx.workspace_bytes_for_batch(b.chunk_starts, b.context_lens), dtype=torch.uint8, device="cuda")
         ws.fill_(0xFF)
