@@ -142,21 +142,21 @@ def run_clocks(args, mpa, b):
 
     tg = [i for i in range(b.S) if b.q_lens[i] == 1]
     pp = [i for i in range(b.S) if b.q_lens[i] > 1]
+    def parts(suffix):
+        if pp:
+            sub, q, out, ws = sub_batch(dw, pp)
+            load("prompt chunks only" + suffix, lambda: dw.attention_only(sub, q, out, ws), algorithmic_flops_pp(b, pp), ("TFLOP/s", 1e12))
+        if tg:
+            sub2, q2, out2, ws2 = sub_batch(dw, tg)
+            load("generation rows only" + suffix, lambda: dw.attention_only(sub2, q2, out2, ws2), algorithmic_bytes(b, tg), ("GB/s", 1e9))
+        if tg and pp:
+            load("mixed" + suffix, lambda: dw.ctx.mixed_paged_attention(dw.q, dw.k_cache, dw.v_cache, dw.block_table, b.chunk_starts,
+                                                                          b.context_lens, dw.out, dw.ws, scale=b.scale))
+
+    parts("")
     if pp:
-        sub, q, out, ws = sub_batch(dw, pp)
-        fl = algorithmic_flops_pp(b, pp)
-        load("prompt chunks only", lambda: dw.attention_only(sub, q, out, ws), fl, ("TFLOP/s", 1e12))
-        kc, vc, qc = dw.k_cache.clone(), dw.v_cache.clone(), q.clone()
-        dw.k_cache.zero_(); dw.v_cache.zero_(); q.zero_()
-        load("prompt chunks only, all-zero q/K/V", lambda: dw.attention_only(sub, q, out, ws), fl, ("TFLOP/s", 1e12))
-        dw.k_cache.copy_(kc); dw.v_cache.copy_(vc); q.copy_(qc)
-        del kc, vc, qc
-    if tg:
-        sub2, q2, out2, ws2 = sub_batch(dw, tg)
-        load("generation rows only", lambda: dw.attention_only(sub2, q2, out2, ws2), algorithmic_bytes(b, tg), ("GB/s", 1e9))
-    if tg and pp:
-        load("mixed", lambda: dw.ctx.mixed_paged_attention(dw.q, dw.k_cache, dw.v_cache, dw.block_table, b.chunk_starts,
-                                                            b.context_lens, dw.out, dw.ws, scale=b.scale))
+        dw.k_cache.zero_(); dw.v_cache.zero_(); dw.q.zero_()     # (the workload is not used again)
+        parts(", all-zero q/K/V")
     sink = torch.zeros(1, dtype=torch.int32, device="cuda")
     for label, kind in (("matrix instructions from registers", mpa.MPA_CEIL_MFMA_BF16),
                         ("matrix instructions from registers, noisy operands", mpa.MPA_CEIL_MFMA_BF16_NOISY)):
