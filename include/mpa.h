@@ -25,7 +25,8 @@
  *     NULL = the default stream) and the call returns without waiting for the GPU.
  *   - The attention calls plan on the host from the two host arrays and hand the plan to the GPU
  *     through a ring of pinned host buffers owned by the context: they are asynchronous, but not
- *     meant for capture into a HIP graph (a replay would re-read a buffer that later calls reuse).
+ *     meant for capture into a HIP graph (a replay would re-read a buffer that later calls reuse);
+ *     mpa_mixed_paged_attention_static is the form that can be captured.
  *   - Elements are 16-bit (bf16 or fp16, fixed per context; passed as bit patterns); scores,
  *     softmax sums and outputs accumulate in fp32.
  *
@@ -268,6 +269,11 @@ int mpa_append_and_attend(mpa_ctx *ctx, const void *k_new, const void *v_new, co
  *     GPU (different streams, different threads) race.  Calls on one stream are ordered and safe;
  *     nothing is assumed to be in the array from an earlier call.
  *   - The device that is current at the call must be the one `stream` belongs to.
+ *   - Under stream capture the call records kernel launches only (no memset, no copy, nothing that
+ *     reads host memory later: the plan is made at capture time and travels inside the launches'
+ *     arguments), so a graph holding it replays the attention step of that very batch layout
+ *     (chunk_starts, context_lens, pointers) on whatever the buffers then hold.  Call it once
+ *     outside a capture first: the first call on a device looks up the array's address.
  * Errors: INVALID_ARG, BAD_BATCH, WORKSPACE (batch too large for the array), HIP.
  */
 #define MPA_STATIC_SCRATCH_BYTES ((size_t)64 << 20)

@@ -76,3 +76,51 @@ def test_static_form_refuses_a_batch_that_does_not_fit(mpa):
     rc = mpa.load().mpa_mixed_paged_attention_static(c._h, fake, fake, fake, fake, 8192, mpa._ptr(b.chunk_starts),
                                                      mpa._ptr(b.context_lens), b.S, b.T, 0.0, fake, None)
     assert rc == mpa.MPA_ERR_WORKSPACE
+
+
+def test_static_form_replays_from_a_hip_graph(mpa):
+    """The entry point that allocates nothing reads no host memory after it returns (its work list travels as
+    kernel arguments) and records no memset, so a serving loop can capture it into a HIP graph for a fixed
+    batch shape.  Captured once, replayed four times with eager calls on another batch (which overwrite the
+    library's device array) and fresh query values in between; every replay must equal the eager call on the
+    same inputs bit for bit."""
+    import torch
+    b = W.make_batch("graph-decode", 77, 8, 128, 16, 400, [1, 1, 1, 1, 40], [900, 64, 2100, 17, 300])
+    other = W.config1()
+    ctx = mpa.Context(b.H, b.D, block_size=b.bs, num_kv_heads=b.HK)
+    ctx2 = mpa.Context(other.H, other.D, block_size=other.bs, num_kv_heads=other.HK)
+    db, db2 = DeviceBatch(b, "prior"), DeviceBatch(other, "prior")
+    ctx.kv_append(db.k_new, db.v_new, db.slot_map, db.k_cache, db.v_cache)
+    ctx2.kv_append(db2.k_new, db2.v_new, db2.slot_map, db2.k_cache, db2.v_cache)
+
+    def eager(out):
+        ctx.mixed_paged_attention_static(db.q, db.k_cache, db.v_cache, db.block_table, b.chunk_starts, b.context_lens, out,
+                                         scale=b.scale)
+
+    def eager_other():
+        ctx2.mixed_paged_attention_static(db2.q, db2.k_cache, db2.v_cache, db2.block_table, other.chunk_starts,
+                                          other.context_lens, db2.out, scale=other.scale)
+
+    want = torch.full_like(db.out, 0x7FFF)
+    eager(want)                       # also the first use of the device array on this GPU: its address is looked up here
+    eager_other()
+    torch.cuda.synchronize()
+    ref = oracle_run(b)[0]
+    assert_close(to_host_u16(want), ref, "eager static call")
+
+    got = torch.full_like(db.out, 0x7FFF)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):      # the binding launches on torch's current stream: the capturing one
+        eager(got)
+    q0 = db.q.clone()
+    for rep in range(4):
+        if rep:                        # new query values in the same buffer: rows rotated by `rep`
+            db.q.copy_(torch.roll(q0, rep, dims=2))
+            eager(want)
+        eager_other()                  # overwrites the work list and the partial results in the device array
+        torch.cuda.synchronize()
+        got.fill_(0x7FFF)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(got, want), f"replay {rep} differs from the eager call"
+    assert not torch.equal(got, torch.full_like(got, 0x7FFF))
