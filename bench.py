@@ -166,6 +166,23 @@ def run_clocks(args, mpa, b):
                       "note": "wall time per call over back-to-back calls (launch gaps included); sclk from rocm-smi --showclocks"}), flush=True)
 
 
+def stored_mfma_busy(workload: str) -> dict:
+    """Matrix-pipe utilisation of the prompt part from the profiler's counters (a stored figure, like `traffic`:
+    counters need a profiler run of their own): busy cycles of the matrix pipe over the cycles the compute
+    units were busy.  Counts only if it was taken on the kernel sources this library is built from."""
+    path = os.path.join(ROOT, "profiles", "mfma_busy.json")
+    if not os.path.exists(path):
+        return {"mfma_pipe_busy": None, "mfma_pipe_busy_note": "no counter run stored"}
+    rec = json.load(open(path))
+    v = rec.get("mfma_busy_over_cu_busy", {}).get(workload)
+    if v is None:
+        return {"mfma_pipe_busy": None, "mfma_pipe_busy_note": "no counter run stored for this workload"}
+    if rec.get("csrc_digest") != csrc_digest():
+        return {"mfma_pipe_busy": None, "mfma_pipe_busy_note": f"stale: the stored figure ({v:.3f}) was taken on other kernel sources"}
+    return {"mfma_pipe_busy": v, "mfma_pipe_busy_note": "SQ_VALU_MFMA_BUSY_CYCLES / (4 x SQ_BUSY_CU_CYCLES), rocprofv3 counters on these "
+                                                        f"sources ({rec['source']}); in cycles, whatever clock the chip held"}
+
+
 def spread(ms) -> dict:
     """Median and 10th / 90th percentile of the sampled kernel durations."""
     p10, p50, p90 = (float(x) for x in np.percentile(ms, [10, 50, 90]))
@@ -636,7 +653,7 @@ def main():
             fl = algorithmic_flops_pp(b, sel)
             part = {"kernel": "attention_kernel (prompt chunks only)", "bound": "mfma", "achieved": fl / t / 1e12,
                     "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": fl / t / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-                    "algorithmic_flops": fl, "kernel_ms": t * 1e3}
+                    "algorithmic_flops": fl, "kernel_ms": t * 1e3, **stored_mfma_busy(args.workload)}
         part["launches_per_event_pair"] = args.part_repeat
         print(json.dumps({"only_part": args.only_part, "workload": b.name, "steps": args.steps, "roofline": part}), flush=True)
         return
@@ -708,7 +725,8 @@ def main():
                                      # matrix instructions back to back from registers on operands as noisy as the
                                      # batch's (the chip lowers its clock under them): what any kernel could reach here
                                      "achievable_peak": ceil["mfma_bf16_noisy_operands_TFLOPs"],
-                                     "frac_of_achievable": a / ceil["mfma_bf16_noisy_operands_TFLOPs"]}
+                                     "frac_of_achievable": a / ceil["mfma_bf16_noisy_operands_TFLOPs"],
+                                     **stored_mfma_busy(args.workload)}
         if tg and pp:
             # how much of the two parts' time the one launch hides: 1.0 = no overlap, lower is better
             result["mixed_over_parts"] = attn_avg_ms / (result["roofline_tg"]["kernel_ms"] + result["roofline_pp"]["kernel_ms"])
