@@ -179,12 +179,12 @@ class Scheduler:
         for r in order:
             if r.state == RETURNED:
                 batch.append(Entry(r, 1, self.new_blocks(r, 1)))
-        # urgent requests (line 1)
+        # urgent requests enter first (Alg. 1, its opening step)
         for r in order:
             if r.state != RETURNED and r.t_r <= self.t_max:
                 t = min(r.prompt_len - r.processed, s_b) if r.is_prompt else 1
                 batch.append(Entry(r, t, self.new_blocks(r, t)))
-        # over-committed: the request with the largest T_r gives way (lines 2-4)
+        # over-committed: the request with the largest T_r gives way, until the batch fits (Alg. 1, the preemption loop)
         while s_f() > s_b or need() > len(self.free):
             victim = max(batch, key=lambda e: (e.req.t_r, e.req.id))
             r = victim.req
@@ -199,7 +199,7 @@ class Scheduler:
                 kvc_short = need() > len(self.free)
                 batch.remove(victim)
                 self.preempt(r, now, release=kvc_short)
-        # fill what is left (line 5)
+        # fill what is left by multi-resource selection (Alg. 1, its last step: Alg. 2)
         a_c = s_b - s_f()
         a_m = len(self.free) - need()          # in blocks
         if a_c > 0:

@@ -140,7 +140,7 @@ def _generation_task(s, rid, slo_token, context, state=SO.RETURNED, t_enter=0.0)
 
 
 def test_algorithm1_preempts_the_largest_remaining_time_when_blocks_run_out():
-    """Alg. 1, lines 2-4 (Sec. 4.4): while a resource is over-committed the request of the batch
+    """Alg. 1, the preemption loop (Sec. 4.4): while a resource is over-committed the request of the batch
     with the largest T_r gives way.  Hand-built: block size 16, a pool of 8 blocks; three generation
     tasks back from the last iteration, each with a full last block (context 32: the next token
     needs a new block), T_r = slo_token - T_max = 0.2, 0.4, 0.3 for ids 10, 11, 12; an urgent prompt
@@ -211,7 +211,7 @@ def test_select_requests_takes_the_nearest_demand_first(seed):
 
 
 def brute_force_selection(a_c, a_m, b, cands):
-    """Alg. 2 lines 7-12 written out on plain numbers: cands = [(id, tokens left, is_long)]; every
+    """Alg. 2's greedy selection loop written out on plain numbers: cands = [(id, tokens left, is_long)]; every
     round re-derives each remaining candidate's chunk (all its tokens, or what the tokens / the
     KVC left allow), its KVC demand in tokens (whole blocks), and takes the smallest real Euclidean
     distance to (A_c, A_m); only one long prompt may be under way."""
