@@ -51,6 +51,12 @@ extern "C" {
 
 typedef struct mpa_ctx mpa_ctx; /* opaque, host-side */
 
+/* Version of this interface: raised whenever a declaration, an option or a status of this header or
+ * of mpa_sched.h changes meaning.  mpa_abi_version() returns the value the library was built with:
+ * a caller compiled against another header (or a binding written for one) can tell. */
+#define MPA_ABI_VERSION 3
+int mpa_abi_version(void);
+
 enum {
     MPA_OK = 0,
     MPA_ERR_INVALID_ARG = -1, /* null pointer, negative size, misaligned pointer           */

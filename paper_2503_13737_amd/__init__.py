@@ -38,8 +38,10 @@ MPA_OPT_FUSE_APPEND = 12
 MPA_STATIC_SCRATCH_BYTES = 64 << 20
 MPA_CEIL_STREAM_READ, MPA_CEIL_RANDOM_4K, MPA_CEIL_RANDOM_16K, MPA_CEIL_MFMA_BF16, MPA_CEIL_MFMA_BF16_NOISY = 1, 2, 3, 4, 5
 
+MPA_ABI_VERSION = 3   # of include/mpa.h as this binding was written for it
+
 EXPORTS = [
-    "mpa_create", "mpa_destroy", "mpa_set_option", "mpa_last_hip_error", "mpa_status_string",
+    "mpa_abi_version", "mpa_create", "mpa_destroy", "mpa_set_option", "mpa_last_hip_error", "mpa_status_string",
     "mpa_workspace_bytes_for_batch", "mpa_workspace_bytes", "mpa_kv_append", "mpa_copy_blocks", "mpa_append_and_attend",
     "mpa_mixed_paged_attention", "mpa_mixed_paged_attention_static", "mpa_plan_describe", "mpa_profile_enable", "mpa_profile_read", "mpa_ceiling_launch",
     "mpa_sched_create", "mpa_sched_destroy", "mpa_sched_add_request", "mpa_sched_add_offline_request", "mpa_sched_next_batch",
@@ -83,6 +85,14 @@ def load() -> ctypes.CDLL:
             raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2503_13737_amd.build`")
         lib = ctypes.CDLL(LIB_PATH)
         vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+        try:
+            lib.mpa_abi_version.restype = ctypes.c_int
+            built = int(lib.mpa_abi_version())
+        except AttributeError:
+            built = None
+        if built != MPA_ABI_VERSION:
+            raise ImportError(f"{LIB_PATH} was built from another version of include/mpa.h ({built}, this binding: "
+                              f"{MPA_ABI_VERSION}); run `python -m paper_2503_13737_amd.build`")
         lib.mpa_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(MpaConfig)]
         lib.mpa_create.restype = ctypes.c_int
         lib.mpa_destroy.argtypes = [vp]

@@ -99,6 +99,8 @@ static auto guarded(F &&f, decltype(f()) on_no_memory) noexcept -> decltype(f())
 
 extern "C" {
 
+int mpa_abi_version(void) { return MPA_ABI_VERSION; }
+
 const char *mpa_status_string(int status)
 {
     switch (status) {

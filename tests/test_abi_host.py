@@ -30,6 +30,9 @@ def test_library_exports_every_declared_symbol():
     for n in names:
         assert hasattr(lib, n), n
     assert sorted(mpa.EXPORTS) == names
+    # the library, the header and the binding agree on the interface's version
+    header = open(os.path.join(ROOT, "include", "mpa.h")).read()
+    assert int(re.search(r"#define MPA_ABI_VERSION (\d+)", header).group(1)) == lib.mpa_abi_version() == mpa.MPA_ABI_VERSION
 
 
 def test_create_validates_config():
