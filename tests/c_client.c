@@ -19,6 +19,10 @@
 
 int main(void)
 {
+    if (mpa_abi_version() != MPA_ABI_VERSION) {
+        fprintf(stderr, "library built from another header version\n");
+        return 4;
+    }
     mpa_config cfg = {40, 40, 128, 32, MPA_BF16};
     mpa_ctx *ctx = NULL;
     CHECK(mpa_create(&ctx, &cfg));
