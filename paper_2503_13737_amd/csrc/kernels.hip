@@ -1167,21 +1167,31 @@ attention_kernel(const AttnParams p)
         // work-groups as units each takes one; with fewer (mixed batches: part of the resident
         // slots, so that generation rows stream through the others from the start) each
         // walks its share, longest units first.
+        // Launch order inside a run of tiles that read the same keys (see TeamRef: member, size):
+        // eight heads at a time, the run's tiles of one head kXcds positions apart -- so the
+        // tiles that share K/V run at the same time, on one XCD, whatever the number of
+        // work-groups (in plain item order a run spans size * H units and its late members
+        // find the K/V gone from L2: measured 2.1 x the K/V bytes from HBM on a 12-head layer).  The
+        // heads left over when H is not a multiple of kXcds follow tile by tile, H mod kXcds positions
+        // apart (their tiles land on 8 / gcd XCDs; padding them to eight positions instead, so that
+        // they too share one XCD, unbalances the XCDs by more than the fetches saved are worth).
         const int32_t n_tile_units = p.n_tile_items * H;   // the launcher checks that this fits
         for (int32_t u = (int32_t)blockIdx.x; u < n_tile_units; u += n_tile_wg) {
-            // Launch order inside a run of tiles that read the same keys (see TeamRef: member, size):
-            // eight heads at a time, the run's tiles of one head kXcds positions apart -- so the
-            // tiles that share K/V run at the same time, on one XCD, whatever the number of
-            // work-groups (in plain item order a run spans size * H units and its late members
-            // find the K/V gone from L2).
-            int32_t item = u / H, j = u % H;
-            if (H % kXcds == 0) {
+            int32_t item = u / H, j;
+            {
                 const int32_t m = __builtin_amdgcn_readfirstlane(p.teams[item].member);
                 const int32_t size = __builtin_amdgcn_readfirstlane(p.teams[item].size);
                 const int32_t first = item - m, v = u - first * H;          // v in [0, size * H)
-                const int32_t block = v / (kXcds * size), within = v % (kXcds * size);
-                item = first + within / kXcds;
-                j = block * kXcds + within % kXcds;
+                const int32_t full = H / kXcds * kXcds * size;              // units of the whole groups of eight heads
+                if (v < full) {
+                    const int32_t block = v / (kXcds * size), within = v % (kXcds * size);
+                    item = first + within / kXcds;
+                    j = block * kXcds + within % kXcds;
+                } else {
+                    const int32_t r = H % kXcds, w = v - full;
+                    item = first + w / r;
+                    j = H - r + w % r;
+                }
             }
             const WorkItem it = load_item(p.items + item);
             // Query heads that share a K/V head read the same K/V tiles: their units are placed
