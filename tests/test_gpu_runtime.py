@@ -306,3 +306,42 @@ def test_append_inside_the_launch_falls_back_for_streamed_prompt_rows(mpa):
                           b.chunk_starts, b.context_lens, db.out, ws, scale=b.scale)
     torch.cuda.synchronize()
     assert_close(to_host_u16(db.out), ref, b.name)
+
+
+def test_two_threads_two_contexts_two_streams(mpa):
+    """Two host threads, each with its own context, workspace and stream, issue forty calls at the same time
+    (the binding releases the interpreter lock inside a call): every output equals the single-threaded one."""
+    import threading
+    import torch
+    batches = [W.config1(), W.make_batch("thread-b", 91, 8, 128, 16, 300, [130, 1, 1, 1], [700, 900, 33, 1500])]
+    want, jobs = [], []
+    for b in batches:
+        ctx = mpa.Context(b.H, b.D, block_size=b.bs, num_kv_heads=b.HK)
+        db = DeviceBatch(b, "prior")
+        ws = torch.empty(ctx.workspace_bytes_for_batch(b.chunk_starts, b.context_lens), dtype=torch.uint8, device="cuda")
+        run_on(ctx, db, b, ws)
+        torch.cuda.synchronize()
+        want.append(to_host_u16(db.out))
+        jobs.append((ctx, db, b, ws, torch.cuda.Stream()))
+    errors_seen = []
+
+    def worker(k):
+        ctx, db, b, ws, stream = jobs[k]
+        try:
+            for _ in range(40):
+                db.out.fill_(0x7FFF)          # on torch's default stream: ordered before the side stream below by the wait
+                stream.wait_stream(torch.cuda.current_stream())
+                run_on(ctx, db, b, ws, stream=stream)
+                stream.synchronize()
+                if not np.array_equal(to_host_u16(db.out), want[k]):
+                    errors_seen.append(f"thread {k}: output differs")
+                    return
+        except Exception as e:   # noqa: BLE001
+            errors_seen.append(f"thread {k}: {e!r}")
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors_seen, errors_seen
