@@ -15,7 +15,7 @@ oracle timed on the host cores on a sample of the same batch.  Other workloads (
 cfg2, cfg3:p<prior>, cfg4, cfg5[:iteration], gqa, gqa-decode, <cfg>@bs32|64|128, <cfg>@fp16, held:<name> (scheduler-shaped
 batches no planner constant was fitted on), sched13b (batches formed by the scheduler from a Poisson trace), swap13b
 (block copies).  Modes: --clocks (the clock sustained under each part), --ceilings (the library's micro-kernels: what this machine reaches), --planner-sweep (the planner's
-choices against a grid of forced ones), --only-part tg|pp.
+choices against a grid of forced ones), --only-part tg|pp, --fuse-append (the step's append inside the attention launch).
 """
 from __future__ import annotations
 
